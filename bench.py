@@ -1,0 +1,144 @@
+#!/usr/bin/env python3
+"""Benchmark of the A2SGD step on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic gradients: a2sgd_local_averages ->
+a2sgd_global_average -> a2sgd_apply_and_update_error (Algorithm 1 lines 3-7), with g, e and w already resident
+in HBM.  The same g is reused every step; e and w evolve, which does not change the traffic.
+
+Prints ONE JSON line: params/s (model parameters updated per second), the roofline of the dominant kernel (the
+fused apply pass) from HIP events recorded around it on the launch stream in every timed step, and the CPU
+oracle timed on a bounded sample of the same workload on this machine's host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+
+# HBM bytes per launch of the apply kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
+# same counters' reading of a plain copy kernel; filled in from the summaries under profiles/.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--blocks-per-worker", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 28, help="parameters in the CPU-baseline sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the P workers are simulated as P buffer pairs on it. "
+              "--gpus must be 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2006_07405_amd as A
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = workloads.FULL[args.config]()
+    n, P = wl.n, wl.num_workers
+    g = [wl.gradient(p, 0, device="cuda") for p in range(P)]
+    e = [wl.initial_error(p, device="cuda") for p in range(P)]
+    w = wl.weights(device="cuda")
+    plan = A.a2sgd_plan(n, P, A.A2SGD_MODE_RETAINED_ERROR, args.blocks_per_worker)
+    ws = A.alloc_workspace(plan)
+
+    def step(ev=None):
+        if ev is not None:
+            ev[0].record()
+        A.a2sgd_local_averages(plan, g, e, ws)
+        if ev is not None:
+            ev[1].record()
+        A.a2sgd_global_average(plan, ws)
+        if ev is not None:
+            ev[2].record()
+        A.a2sgd_apply_and_update_error(plan, g, e, w, wl.eta, ws)
+        if ev is not None:
+            ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_reduce = sum(ev[0].elapsed_time(ev[1]) for ev in events) / args.steps
+    ms_global = sum(ev[1].elapsed_time(ev[2]) for ev in events) / args.steps
+    ms_apply = sum(ev[2].elapsed_time(ev[3]) for ev in events) / args.steps
+    bytes_reduce = 8 * n * P
+    bytes_apply = 12 * n * P + 8 * n
+    bytes_step = bytes_reduce + bytes_apply
+    achieved = bytes_apply / (ms_apply * 1e-3) / 1e9
+    stats, gmu = A.a2sgd_read_stats(plan, ws)
+
+    out = {
+        "metric": "a2sgd_step_params_per_s",
+        "value": n / (ms_per_step * 1e-3),
+        "unit": "params/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"config{args.config}:{wl.name}", "n": n, "num_workers": P, "seed": wl.seed,
+                   "recipe": wl.recipe, "mode": "retained_error", "eta": wl.eta,
+                   "blocks_per_worker": A.a2sgd_plan_blocks_per_worker(plan)},
+        "step_hbm_gbps": bytes_step / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "kernels_ms": {"local_averages": ms_reduce, "global_average": ms_global, "apply_and_update_error": ms_apply},
+        "local_averages_gbps": bytes_reduce / (ms_reduce * 1e-3) / 1e9,
+        "roofline": {"kernel": "k_apply (a2sgd_apply_and_update_error)", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "algorithmic_bytes_per_launch": bytes_apply,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(f"config{args.config}")},
+        "result_check": {"gmu_pos": gmu[0], "gmu_neg": gmu[1], "n_pos_worker0": stats[0].n_pos},
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, g, w, min(args.cpu_sample, n))
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(wl, g, w, m):
+    """The oracle as it stands, single-threaded, on the first m parameters of every worker: one whole step (both
+    passes).  Only the compute is timed; the device-to-host copies are not."""
+    import numpy as np
+    from oracle import a2sgd_oracle as O
+    P = wl.num_workers
+    gh = [x[:m].cpu().numpy() for x in g]
+    eh = [np.zeros(m, dtype=np.float32) for _ in range(P)]
+    wh = w[:m].cpu().numpy()
+    O.lib()
+    t0 = time.perf_counter()
+    O.step(gh, eh, wh, wl.eta, O.RETAINED_ERROR)
+    dt = time.perf_counter() - t0
+    return {"value": m / dt, "unit": "params/s", "cores": 1, "kind": "oracle", "seconds": dt,
+            "sample": f"first {m} of {wl.n} parameters of all {P} workers, one whole step (both passes), e = 0"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,142 @@
+/*
+ * a2sgd.h — C ABI of the A2SGD (two-level gradient averaging) per-step hot path for one MI355X (gfx950).
+ *
+ * The method (arXiv 2006.07405): each of P data-parallel workers reduces its n-element gradient to two
+ * numbers, the mean of the entries >= 0 and the mean magnitude of the entries < 0 (Sec. 3.1); the workers
+ * average those two numbers (Algorithm 1 line 5); each rebuilds an update from the two global means at the
+ * positions of its own two sign groups and keeps the difference to its own means as a local error vector
+ * (Algorithm 1 lines 4 and 6; Eq. 2); the model takes w <- w - eta * update (line 7).
+ *
+ * Here the P workers are P (gradient, error) buffer pairs resident on one GPU plus one shared weight buffer,
+ * which stands for the average of the P replicas: the applied update is the mean over the workers of their
+ * rebuilt updates (Eq. 1 with each worker's gradient replaced by its rebuilt one).
+ *
+ * Notation: n parameters, P workers, g^p / e^p worker p's gradient / error, v^p = fl32(g^p + e^p) the vector
+ * that is encoded.  All buffers are fp32.
+ *
+ * Conventions for every entry point
+ *   - Pointers named g, e, w, workspace, mask are DEVICE pointers; `g` and `e` themselves are HOST arrays of
+ *     P device pointers (copied into the kernel arguments at launch).  Everything else is host memory.
+ *   - Ownership: the library never allocates, frees or keeps user device memory.  Buffers are borrowed until
+ *     the work enqueued on `stream` has completed.  The plan is the only object the library owns.
+ *   - Aliasing: g^p is read-only; e^p and w are updated in place.  No two of g^p, e^p, w, workspace overlap.
+ *   - Alignment: every device pointer must be 16-byte aligned (else A2SGD_ERR_ALIGNMENT).  n is arbitrary.
+ *   - Asynchrony: the step calls only enqueue kernels on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and return.  Only a2sgd_read_stats synchronises.
+ *   - Errors: a status code is returned; nothing is thrown or aborted.  Argument errors are found before any
+ *     kernel is launched, so a failed call has enqueued nothing.
+ *   - Determinism: no floating-point atomics; the same plan on the same inputs gives bit-identical outputs.
+ *   - Inputs are expected finite.  A NaN in v^p belongs to neither sign group: it is counted in n_nan, adds to
+ *     no sum, and turns only its own e and w entries into NaN.
+ */
+#ifndef A2SGD_H
+#define A2SGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define A2SGD_MAX_WORKERS 64u
+
+typedef struct a2sgd_plan a2sgd_plan_t; /* opaque; host memory owned by the library */
+typedef void *a2sgd_stream_t;           /* a hipStream_t */
+
+typedef enum {
+    A2SGD_OK = 0,
+    A2SGD_ERR_INVALID_ARG = 1, /* NULL where a pointer is required, n == 0, P out of range, bad mode */
+    A2SGD_ERR_ALIGNMENT = 2,   /* a device pointer is not 16-byte aligned */
+    A2SGD_ERR_DEVICE = 3,      /* a HIP call or kernel launch failed */
+    A2SGD_ERR_NOMEM = 4        /* host allocation of the plan failed */
+} a2sgd_status_t;
+
+typedef enum {
+    /* v = fl32(g + e_old); the update applied is the global-mean vector alone; e_new = v - enc(v) is kept
+     * for the next step.  (Abstract and Sec. 3: the method "retains local errors" in a local error vector.) */
+    A2SGD_MODE_RETAINED_ERROR = 0,
+    /* Algorithm 1 lines 4-7 as printed: the error is added back in the same step, update = e_new + global-mean
+     * vector, which is Theorem 1's g + (net gain of the means).  e may be NULL (then v = g and no error is
+     * stored); if e is given it is folded in and overwritten like in the other mode. */
+    A2SGD_MODE_ALG1_LITERAL = 1
+} a2sgd_mode_t;
+
+typedef struct {
+    uint64_t n;                 /* model size, 1 <= n <= 2^40 */
+    uint32_t num_workers;       /* P, 1 <= P <= A2SGD_MAX_WORKERS */
+    int32_t mode;               /* an a2sgd_mode_t */
+    uint32_t blocks_per_worker; /* 0 = let the plan choose; else the first-level reduction's grid width */
+    uint32_t reserved;          /* must be 0 */
+} a2sgd_config_t;
+
+/* Per-worker result of the reduction (Sec. 3.1; the pair (mu_pos, mu_neg) is the worker's 64-bit message of
+ * Sec. 4.3).  An empty group has mean 0.  n_zero (entries == 0, a subset of n_pos) and n_nan are diagnostics. */
+typedef struct {
+    float mu_pos, mu_neg;
+    uint64_t n_pos, n_neg, n_zero, n_nan;
+} a2sgd_worker_stats_t;
+
+/* The two global means of Algorithm 1 line 5: plain averages of the P workers' means. */
+typedef struct {
+    float gmu_pos, gmu_neg;
+} a2sgd_global_stats_t;
+
+/* Host only, launches nothing.  Validates cfg and fixes the launch geometry and the workspace layout.
+ * *out_plan is written only on success and must be released with a2sgd_plan_destroy. */
+a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan);
+a2sgd_status_t a2sgd_plan_destroy(a2sgd_plan_t *plan);
+
+/* Bytes of device workspace the caller must provide (16-byte aligned) to the calls below.  Its contents need
+ * no initialisation; it carries the block partials, the per-worker means and counts and the global means from
+ * one call of a step to the next.  Returns 0 for a NULL plan. */
+size_t a2sgd_workspace_bytes(const a2sgd_plan_t *plan);
+
+/* Algorithm 1 line 3.  For every worker p: one pass over v^p = fl32(g^p + e^p) giving n_pos = #{v >= 0},
+ * n_neg = #{v < 0}, the two sums, and from them mu_pos = fl32(S_pos / n_pos), mu_neg = fl32(S_neg / n_neg)
+ * (0 for an empty group).  Sums are accumulated in fp64 and combined in a fixed order.  Results stay in the
+ * workspace.  e may be NULL only in A2SGD_MODE_ALG1_LITERAL (then v = g).  Reads g and e once. */
+a2sgd_status_t a2sgd_local_averages(const a2sgd_plan_t *plan, const float *const *g, const float *const *e,
+                                    void *workspace, a2sgd_stream_t stream);
+
+/* Algorithm 1 line 5, the stand-in for the Allreduce(average) of two floats per worker: gmu_pos and gmu_neg
+ * are the fp64 sums over p = 0..P-1 of the workers' fp32 means, divided by P and rounded to fp32.  Reads and
+ * writes only the workspace; must follow a2sgd_local_averages on the same stream. */
+a2sgd_status_t a2sgd_global_average(const a2sgd_plan_t *plan, void *workspace, a2sgd_stream_t stream);
+
+/* Algorithm 1 lines 4, 6 and 7 in one pass.  For every i and p: v = fl32(g^p_i + e^p_i); if v >= 0 then
+ * e^p_i <- v - mu_pos^p and u^p = +gmu_pos, else e^p_i <- v + mu_neg^p and u^p = -gmu_neg (literal mode:
+ * u^p = new e^p_i + that).  Then w_i <- w_i - eta * (1/P) * sum_p u^p.  g, e and w are each read once, e and
+ * w written once; the rebuilt gradient is never stored.  Must follow a2sgd_global_average on the same stream
+ * with the same g and e that a2sgd_local_averages saw.  eta is the learning rate of this step. */
+a2sgd_status_t a2sgd_apply_and_update_error(const a2sgd_plan_t *plan, const float *const *g, float *const *e,
+                                            float *w, float eta, void *workspace, a2sgd_stream_t stream);
+
+/* The three calls above, in order, on one stream: one whole step of Algorithm 1's loop body (lines 3-7). */
+a2sgd_status_t a2sgd_step(const a2sgd_plan_t *plan, const float *const *g, float *const *e, float *w, float eta,
+                          void *workspace, a2sgd_stream_t stream);
+
+/* Copies the per-worker and global results of the last completed reduction out of the workspace into host
+ * memory: out_workers[P] and *out_global (either may be NULL).  Synchronises `stream`.  For tests and logging. */
+a2sgd_status_t a2sgd_read_stats(const a2sgd_plan_t *plan, const void *workspace, a2sgd_stream_t stream,
+                                a2sgd_worker_stats_t *out_workers, a2sgd_global_stats_t *out_global);
+
+/* Test aid: writes pos(v^p) of Eq. 2 as a bitmap, mask[p * ceil(n/64) + i/64] bit (i % 64) = (v^p_i >= 0),
+ * bits beyond n are 0.  mask is a device buffer of P * ceil(n/64) uint64.  e may be NULL (v = g). */
+a2sgd_status_t a2sgd_export_mask(const a2sgd_plan_t *plan, const float *const *g, const float *const *e,
+                                 uint64_t *mask, a2sgd_stream_t stream);
+
+/* Dense data-parallel SGD, Eq. 1, which is also the final synchronisation step of Algorithm 1 (lines 9-10):
+ * w_i <- w_i - eta * (1/P) * sum_p g^p_i.  Reads every g^p and w once, writes w once. */
+a2sgd_status_t a2sgd_dense_step(const a2sgd_plan_t *plan, const float *const *g, float *w, float eta,
+                                a2sgd_stream_t stream);
+
+/* Geometry the plan chose, for reports: blocks per worker of the first-level reduction. */
+uint32_t a2sgd_plan_blocks_per_worker(const a2sgd_plan_t *plan);
+
+const char *a2sgd_status_string(a2sgd_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* A2SGD_H */

@@ -1,0 +1,197 @@
+"""Thin ctypes binding of liba2sgd.so: the same names as the C ABI in include/a2sgd.h, argument marshalling only.
+
+Tensors are torch CUDA tensors used as plain device memory (data_ptr) and the current torch stream supplies
+the hipStream_t.  Every step of the path runs inside the library's kernels.  There is no fallback: if the
+shared library is missing or fails to load, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liba2sgd.so")
+
+A2SGD_MAX_WORKERS = 64
+A2SGD_OK, A2SGD_ERR_INVALID_ARG, A2SGD_ERR_ALIGNMENT, A2SGD_ERR_DEVICE, A2SGD_ERR_NOMEM = range(5)
+A2SGD_MODE_RETAINED_ERROR, A2SGD_MODE_ALG1_LITERAL = 0, 1
+
+
+class a2sgd_config_t(C.Structure):
+    _fields_ = [("n", C.c_uint64), ("num_workers", C.c_uint32), ("mode", C.c_int32),
+                ("blocks_per_worker", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class a2sgd_worker_stats_t(C.Structure):
+    _fields_ = [("mu_pos", C.c_float), ("mu_neg", C.c_float), ("n_pos", C.c_uint64), ("n_neg", C.c_uint64),
+                ("n_zero", C.c_uint64), ("n_nan", C.c_uint64)]
+
+
+class a2sgd_global_stats_t(C.Structure):
+    _fields_ = [("gmu_pos", C.c_float), ("gmu_neg", C.c_float)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(there is no CPU fallback)")
+    L = C.CDLL(LIB_PATH)
+    vp, u64p = C.c_void_p, C.POINTER(C.c_uint64)
+    tab = C.POINTER(C.c_void_p)
+    L.a2sgd_plan.argtypes = [C.POINTER(a2sgd_config_t), C.POINTER(vp)]
+    L.a2sgd_plan_destroy.argtypes = [vp]
+    L.a2sgd_workspace_bytes.argtypes = [vp]
+    L.a2sgd_workspace_bytes.restype = C.c_size_t
+    L.a2sgd_plan_blocks_per_worker.argtypes = [vp]
+    L.a2sgd_plan_blocks_per_worker.restype = C.c_uint32
+    L.a2sgd_local_averages.argtypes = [vp, tab, tab, vp, vp]
+    L.a2sgd_global_average.argtypes = [vp, vp, vp]
+    L.a2sgd_apply_and_update_error.argtypes = [vp, tab, tab, vp, C.c_float, vp, vp]
+    L.a2sgd_step.argtypes = [vp, tab, tab, vp, C.c_float, vp, vp]
+    L.a2sgd_read_stats.argtypes = [vp, vp, vp, C.POINTER(a2sgd_worker_stats_t), C.POINTER(a2sgd_global_stats_t)]
+    L.a2sgd_export_mask.argtypes = [vp, tab, tab, vp, vp]
+    L.a2sgd_dense_step.argtypes = [vp, tab, vp, C.c_float, vp]
+    L.a2sgd_status_string.argtypes = [C.c_int]
+    L.a2sgd_status_string.restype = C.c_char_p
+    for name in ("a2sgd_plan", "a2sgd_plan_destroy", "a2sgd_local_averages", "a2sgd_global_average",
+                 "a2sgd_apply_and_update_error", "a2sgd_step", "a2sgd_read_stats", "a2sgd_export_mask",
+                 "a2sgd_dense_step"):
+        getattr(L, name).restype = C.c_int
+    return L
+
+
+raw = _load()  # the bare ctypes library, for tests that pass hand-made pointers
+
+
+class A2sgdError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {raw.a2sgd_status_string(status).decode()} (status {status})")
+
+
+def _check(status: int, where: str) -> None:
+    if status != A2SGD_OK:
+        raise A2sgdError(status, where)
+
+
+class Plan:
+    """Owns an a2sgd_plan_t*; remembers n and P so the binding can check tensor shapes before marshalling."""
+
+    def __init__(self, handle: int, n: int, num_workers: int, mode: int):
+        self.handle, self.n, self.num_workers, self.mode = handle, n, num_workers, mode
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            raw.a2sgd_plan_destroy(self.handle)
+            self.handle = None
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev_ptr(t: torch.Tensor, numel: Optional[int], dtype, what: str) -> int:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError(f"{what}: expected a contiguous CUDA tensor of {dtype}")
+    if numel is not None and t.numel() < numel:
+        raise ValueError(f"{what}: {t.numel()} elements, the plan needs {numel}")
+    return t.data_ptr()
+
+
+def _table(plan: Plan, ts: Optional[Sequence[torch.Tensor]], what: str):
+    if ts is None:
+        return None
+    if len(ts) != plan.num_workers:
+        raise ValueError(f"{what}: {len(ts)} buffers for a plan of {plan.num_workers} workers")
+    return (C.c_void_p * plan.num_workers)(*[_dev_ptr(t, plan.n, torch.float32, f"{what}[{i}]")
+                                             for i, t in enumerate(ts)])
+
+
+def _workspace(plan: Plan, ws: torch.Tensor) -> int:
+    need = a2sgd_workspace_bytes(plan)
+    if not (isinstance(ws, torch.Tensor) and ws.is_cuda and ws.is_contiguous()):
+        raise TypeError("workspace: expected a contiguous CUDA tensor")
+    if ws.numel() * ws.element_size() < need:
+        raise ValueError(f"workspace: {ws.numel() * ws.element_size()} bytes, the plan needs {need}")
+    return ws.data_ptr()
+
+
+def a2sgd_plan(n: int, num_workers: int, mode: int = A2SGD_MODE_RETAINED_ERROR, blocks_per_worker: int = 0) -> Plan:
+    cfg = a2sgd_config_t(n, num_workers, mode, blocks_per_worker, 0)
+    h = C.c_void_p()
+    _check(raw.a2sgd_plan(C.byref(cfg), C.byref(h)), "a2sgd_plan")
+    return Plan(h.value, n, num_workers, mode)
+
+
+def a2sgd_workspace_bytes(plan: Plan) -> int:
+    return int(raw.a2sgd_workspace_bytes(plan.handle))
+
+
+def a2sgd_plan_blocks_per_worker(plan: Plan) -> int:
+    return int(raw.a2sgd_plan_blocks_per_worker(plan.handle))
+
+
+def alloc_workspace(plan: Plan, device="cuda") -> torch.Tensor:
+    """Convenience for callers that let torch own the memory: an uninitialised device buffer of the right size."""
+    return torch.empty((a2sgd_workspace_bytes(plan) + 7) // 8, dtype=torch.int64, device=device)
+
+
+def a2sgd_local_averages(plan: Plan, g, e, workspace: torch.Tensor, stream=None) -> None:
+    _check(raw.a2sgd_local_averages(plan.handle, _table(plan, g, "g"), _table(plan, e, "e"),
+                                    _workspace(plan, workspace), _stream(stream)), "a2sgd_local_averages")
+
+
+def a2sgd_global_average(plan: Plan, workspace: torch.Tensor, stream=None) -> None:
+    _check(raw.a2sgd_global_average(plan.handle, _workspace(plan, workspace), _stream(stream)),
+           "a2sgd_global_average")
+
+
+def a2sgd_apply_and_update_error(plan: Plan, g, e, w: torch.Tensor, eta: float, workspace: torch.Tensor,
+                                 stream=None) -> None:
+    _check(raw.a2sgd_apply_and_update_error(plan.handle, _table(plan, g, "g"), _table(plan, e, "e"),
+                                            _dev_ptr(w, plan.n, torch.float32, "w"), C.c_float(eta),
+                                            _workspace(plan, workspace), _stream(stream)),
+           "a2sgd_apply_and_update_error")
+
+
+def a2sgd_step(plan: Plan, g, e, w: torch.Tensor, eta: float, workspace: torch.Tensor, stream=None) -> None:
+    _check(raw.a2sgd_step(plan.handle, _table(plan, g, "g"), _table(plan, e, "e"),
+                          _dev_ptr(w, plan.n, torch.float32, "w"), C.c_float(eta), _workspace(plan, workspace),
+                          _stream(stream)), "a2sgd_step")
+
+
+@dataclass
+class WorkerStats:
+    mu_pos: float
+    mu_neg: float
+    n_pos: int
+    n_neg: int
+    n_zero: int
+    n_nan: int
+
+
+def a2sgd_read_stats(plan: Plan, workspace: torch.Tensor, stream=None):
+    """Returns ([WorkerStats] * P, (gmu_pos, gmu_neg)).  Synchronises the stream."""
+    ws = (a2sgd_worker_stats_t * plan.num_workers)()
+    gs = a2sgd_global_stats_t()
+    _check(raw.a2sgd_read_stats(plan.handle, _workspace(plan, workspace), _stream(stream), ws, C.byref(gs)),
+           "a2sgd_read_stats")
+    return ([WorkerStats(s.mu_pos, s.mu_neg, s.n_pos, s.n_neg, s.n_zero, s.n_nan) for s in ws],
+            (gs.gmu_pos, gs.gmu_neg))
+
+
+def a2sgd_export_mask(plan: Plan, g, e, mask: torch.Tensor, stream=None) -> None:
+    words = plan.num_workers * ((plan.n + 63) // 64)
+    _check(raw.a2sgd_export_mask(plan.handle, _table(plan, g, "g"), _table(plan, e, "e"),
+                                 _dev_ptr(mask, words, torch.int64, "mask"), _stream(stream)), "a2sgd_export_mask")
+
+
+def a2sgd_dense_step(plan: Plan, g, w: torch.Tensor, eta: float, stream=None) -> None:
+    _check(raw.a2sgd_dense_step(plan.handle, _table(plan, g, "g"), _dev_ptr(w, plan.n, torch.float32, "w"),
+                                C.c_float(eta), _stream(stream)), "a2sgd_dense_step")

@@ -1,0 +1,247 @@
+// Host side of the C ABI declared in include/a2sgd.h: plan construction, argument validation, and the
+// sequencing of the kernels of one step.  No device memory is allocated here.
+#include <new>
+
+#include "a2sgd_internal.h"
+
+using namespace a2sgd;
+
+namespace {
+
+constexpr uint64_t kMaxN = 1ull << 40;
+// Compute units of one MI355X and the workgroups of 256 threads each of them keeps resident.
+constexpr uint32_t kComputeUnits = 256;
+constexpr uint32_t kBlocksPerCU = 8;
+// Above this many bytes of g + e + w the step cannot live in the 256 MiB last-level cache between its two
+// passes, and every load and store is issued as non-temporal.
+constexpr uint64_t kStreamingBytes = 192ull << 20;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+uint32_t choose_blocks_per_worker(uint64_t n, uint32_t P)
+{
+    const uint64_t tile = static_cast<uint64_t>(kBlock) * kReduceUnroll * 4;  // elements per tile
+    uint64_t tiles = (n + tile - 1) / tile;
+    uint64_t want = (static_cast<uint64_t>(kComputeUnits) * kBlocksPerCU + P - 1) / P;
+    uint64_t B = tiles < want ? tiles : want;
+    if (B < 1)
+        B = 1;
+    if (B > kMaxBlocksPerWorker)
+        B = kMaxBlocksPerWorker;
+    return static_cast<uint32_t>(B);
+}
+
+// Checks the P pointers of one table; `required` = a NULL table or entry is an error.
+a2sgd_status_t check_table(const float *const *tab, uint32_t P, bool required, bool *present)
+{
+    *present = false;
+    if (tab == nullptr)
+        return required ? A2SGD_ERR_INVALID_ARG : A2SGD_OK;
+    for (uint32_t p = 0; p < P; ++p) {
+        if (tab[p] == nullptr)
+            return A2SGD_ERR_INVALID_ARG;
+        if (!aligned16(tab[p]))
+            return A2SGD_ERR_ALIGNMENT;
+    }
+    *present = true;
+    return A2SGD_OK;
+}
+
+a2sgd_status_t check_buffer(const void *p)
+{
+    if (p == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    return aligned16(p) ? A2SGD_OK : A2SGD_ERR_ALIGNMENT;
+}
+
+void fill_table(PtrTable &t, uint32_t P, const float *const *g, const float *const *e)
+{
+    for (uint32_t p = 0; p < kMaxWorkers; ++p) {
+        t.g[p] = (g && p < P) ? g[p] : nullptr;
+        t.e[p] = (e && p < P) ? const_cast<float *>(e[p]) : nullptr;
+    }
+}
+
+inline a2sgd_status_t dev(hipError_t err) { return err == hipSuccess ? A2SGD_OK : A2SGD_ERR_DEVICE; }
+
+// Validation shared by the calls that take g and e.  In retained-error mode e is required.
+a2sgd_status_t check_g_e(const a2sgd_plan_t *plan, const float *const *g, const float *const *e, bool *has_e)
+{
+    if (plan == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    bool has_g = false;
+    a2sgd_status_t st = check_table(g, plan->P, true, &has_g);
+    if (st != A2SGD_OK)
+        return st;
+    return check_table(e, plan->P, plan->mode == A2SGD_MODE_RETAINED_ERROR, has_e);
+}
+
+}  // namespace
+
+extern "C" {
+
+a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
+{
+    if (cfg == nullptr || out_plan == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    if (cfg->n == 0 || cfg->n > kMaxN)
+        return A2SGD_ERR_INVALID_ARG;
+    if (cfg->num_workers == 0 || cfg->num_workers > kMaxWorkers)
+        return A2SGD_ERR_INVALID_ARG;
+    if (cfg->mode != A2SGD_MODE_RETAINED_ERROR && cfg->mode != A2SGD_MODE_ALG1_LITERAL)
+        return A2SGD_ERR_INVALID_ARG;
+    if (cfg->blocks_per_worker > kMaxBlocksPerWorker || cfg->reserved != 0)
+        return A2SGD_ERR_INVALID_ARG;
+    a2sgd_plan_t *pl = new (std::nothrow) a2sgd_plan_t;
+    if (pl == nullptr)
+        return A2SGD_ERR_NOMEM;
+    pl->n = cfg->n;
+    pl->P = cfg->num_workers;
+    pl->mode = cfg->mode;
+    pl->B = cfg->blocks_per_worker ? cfg->blocks_per_worker : choose_blocks_per_worker(pl->n, pl->P);
+    pl->streaming = (2ull * pl->P + 1) * 4ull * pl->n > kStreamingBytes;
+    pl->workspace_bytes = kHeaderBytes + 5ull * 8ull * pl->P * pl->B;
+    *out_plan = pl;
+    return A2SGD_OK;
+}
+
+a2sgd_status_t a2sgd_plan_destroy(a2sgd_plan_t *plan)
+{
+    delete plan;
+    return A2SGD_OK;
+}
+
+size_t a2sgd_workspace_bytes(const a2sgd_plan_t *plan) { return plan ? plan->workspace_bytes : 0; }
+
+uint32_t a2sgd_plan_blocks_per_worker(const a2sgd_plan_t *plan) { return plan ? plan->B : 0; }
+
+a2sgd_status_t a2sgd_local_averages(const a2sgd_plan_t *plan, const float *const *g, const float *const *e,
+                                    void *workspace, a2sgd_stream_t stream)
+{
+    bool has_e = false;
+    a2sgd_status_t st = check_g_e(plan, g, e, &has_e);
+    if (st != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(workspace)) != A2SGD_OK)
+        return st;
+    PtrTable tab;
+    fill_table(tab, plan->P, g, has_e ? e : nullptr);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if ((st = dev(launch_local_partials(*plan, tab, has_e, workspace, s))) != A2SGD_OK)
+        return st;
+    return dev(launch_local_finalize(*plan, workspace, s));
+}
+
+a2sgd_status_t a2sgd_global_average(const a2sgd_plan_t *plan, void *workspace, a2sgd_stream_t stream)
+{
+    if (plan == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    a2sgd_status_t st = check_buffer(workspace);
+    if (st != A2SGD_OK)
+        return st;
+    return dev(launch_global_average(*plan, workspace, static_cast<hipStream_t>(stream)));
+}
+
+a2sgd_status_t a2sgd_apply_and_update_error(const a2sgd_plan_t *plan, const float *const *g, float *const *e,
+                                            float *w, float eta, void *workspace, a2sgd_stream_t stream)
+{
+    bool has_e = false;
+    a2sgd_status_t st = check_g_e(plan, g, e, &has_e);
+    if (st != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(w)) != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(workspace)) != A2SGD_OK)
+        return st;
+    PtrTable tab;
+    fill_table(tab, plan->P, g, has_e ? e : nullptr);
+    return dev(launch_apply(*plan, tab, has_e, w, eta, workspace, static_cast<hipStream_t>(stream)));
+}
+
+a2sgd_status_t a2sgd_step(const a2sgd_plan_t *plan, const float *const *g, float *const *e, float *w, float eta,
+                          void *workspace, a2sgd_stream_t stream)
+{
+    // validate everything first so that a failed step has enqueued nothing
+    bool has_e = false;
+    a2sgd_status_t st = check_g_e(plan, g, e, &has_e);
+    if (st != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(w)) != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(workspace)) != A2SGD_OK)
+        return st;
+    if ((st = a2sgd_local_averages(plan, g, e, workspace, stream)) != A2SGD_OK)
+        return st;
+    if ((st = a2sgd_global_average(plan, workspace, stream)) != A2SGD_OK)
+        return st;
+    return a2sgd_apply_and_update_error(plan, g, e, w, eta, workspace, stream);
+}
+
+a2sgd_status_t a2sgd_read_stats(const a2sgd_plan_t *plan, const void *workspace, a2sgd_stream_t stream,
+                                a2sgd_worker_stats_t *out_workers, a2sgd_global_stats_t *out_global)
+{
+    if (plan == nullptr || workspace == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    WsHeader hdr;
+    if (hipMemcpyAsync(&hdr, workspace, sizeof(WsHeader), hipMemcpyDeviceToHost, s) != hipSuccess)
+        return A2SGD_ERR_DEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess)
+        return A2SGD_ERR_DEVICE;
+    if (out_workers)
+        for (uint32_t p = 0; p < plan->P; ++p)
+            out_workers[p] = hdr.workers[p];
+    if (out_global) {
+        out_global->gmu_pos = hdr.gmu_pos;
+        out_global->gmu_neg = hdr.gmu_neg;
+    }
+    return A2SGD_OK;
+}
+
+a2sgd_status_t a2sgd_export_mask(const a2sgd_plan_t *plan, const float *const *g, const float *const *e,
+                                 uint64_t *mask, a2sgd_stream_t stream)
+{
+    if (plan == nullptr || plan->n > (1ull << 38))
+        return A2SGD_ERR_INVALID_ARG;
+    bool has_g = false, has_e = false;
+    a2sgd_status_t st = check_table(g, plan->P, true, &has_g);
+    if (st != A2SGD_OK)
+        return st;
+    if ((st = check_table(e, plan->P, false, &has_e)) != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(mask)) != A2SGD_OK)
+        return st;
+    PtrTable tab;
+    fill_table(tab, plan->P, g, has_e ? e : nullptr);
+    return dev(launch_export_mask(*plan, tab, has_e, mask, static_cast<hipStream_t>(stream)));
+}
+
+a2sgd_status_t a2sgd_dense_step(const a2sgd_plan_t *plan, const float *const *g, float *w, float eta,
+                                a2sgd_stream_t stream)
+{
+    if (plan == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    bool has_g = false;
+    a2sgd_status_t st = check_table(g, plan->P, true, &has_g);
+    if (st != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(w)) != A2SGD_OK)
+        return st;
+    PtrTable tab;
+    fill_table(tab, plan->P, g, nullptr);
+    return dev(launch_dense_step(*plan, tab, w, eta, static_cast<hipStream_t>(stream)));
+}
+
+const char *a2sgd_status_string(a2sgd_status_t status)
+{
+    switch (status) {
+    case A2SGD_OK: return "ok";
+    case A2SGD_ERR_INVALID_ARG: return "invalid argument";
+    case A2SGD_ERR_ALIGNMENT: return "device pointer not 16-byte aligned";
+    case A2SGD_ERR_DEVICE: return "HIP call or kernel launch failed";
+    case A2SGD_ERR_NOMEM: return "out of host memory";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

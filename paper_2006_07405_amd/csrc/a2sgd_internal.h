@@ -1,0 +1,78 @@
+// Shared between the host API (a2sgd_api.cpp) and the kernels (a2sgd_kernels.hip): workspace layout, the
+// plan, and the launchers' signatures.  Nothing outside this library includes it.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "a2sgd.h"
+
+namespace a2sgd {
+
+constexpr uint32_t kMaxWorkers = A2SGD_MAX_WORKERS;
+constexpr int kBlock = 256;           // threads per workgroup: 4 wavefronts of 64
+constexpr int kReduceUnroll = 4;      // float4 loads per array per thread per tile in the reduction
+constexpr uint32_t kMaxBlocksPerWorker = 65536;
+
+// Device workspace, in this order:
+//   WsHeader                                   (kHeaderBytes, padded)
+//   double   s_pos [P][B]   block partial sums of v over v >= 0
+//   double   s_neg [P][B]   block partial sums of |v| over v < 0
+//   uint64_t n_pos [P][B], n_neg [P][B], n_zero [P][B]
+struct WsHeader {
+    float gmu_pos, gmu_neg;  // Algorithm 1 line 5
+    uint32_t pad[2];
+    a2sgd_worker_stats_t workers[kMaxWorkers];  // Algorithm 1 line 3, per worker
+};
+constexpr size_t kHeaderBytes = 4096;
+static_assert(sizeof(WsHeader) <= kHeaderBytes, "header must fit its slot");
+static_assert(sizeof(a2sgd_worker_stats_t) == 40, "stats record layout is part of the ABI");
+
+struct Partials {
+    double *s_pos, *s_neg;
+    uint64_t *n_pos, *n_neg, *n_zero;
+};
+
+inline Partials partials_of(void *workspace, uint32_t P, uint32_t B)
+{
+    char *base = static_cast<char *>(workspace) + kHeaderBytes;
+    const size_t stride = static_cast<size_t>(P) * B * 8;
+    Partials q;
+    q.s_pos = reinterpret_cast<double *>(base);
+    q.s_neg = reinterpret_cast<double *>(base + stride);
+    q.n_pos = reinterpret_cast<uint64_t *>(base + 2 * stride);
+    q.n_neg = reinterpret_cast<uint64_t *>(base + 3 * stride);
+    q.n_zero = reinterpret_cast<uint64_t *>(base + 4 * stride);
+    return q;
+}
+
+// Kernel argument block: the P device pointers of each kind, passed by value (1 KiB of kernarg).
+struct PtrTable {
+    const float *g[kMaxWorkers];
+    float *e[kMaxWorkers];
+};
+
+}  // namespace a2sgd
+
+struct a2sgd_plan {
+    uint64_t n;
+    uint32_t P;
+    int32_t mode;
+    uint32_t B;           // blocks per worker in the first-level reduction
+    bool streaming;       // footprint exceeds the on-chip caches: use non-temporal loads and stores
+    size_t workspace_bytes;
+};
+
+namespace a2sgd {
+
+// Launchers: enqueue on `stream`, return the launch status.  Arguments were validated by the caller.
+hipError_t launch_local_partials(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, void *ws, hipStream_t s);
+hipError_t launch_local_finalize(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
+hipError_t launch_global_average(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
+hipError_t launch_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
+                        hipStream_t s);
+hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, uint64_t *mask, hipStream_t s);
+hipError_t launch_dense_step(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eta, hipStream_t s);
+
+}  // namespace a2sgd

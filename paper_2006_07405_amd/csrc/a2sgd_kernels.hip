@@ -1,0 +1,489 @@
+// HIP kernels of the A2SGD step for gfx950 (CDNA4, 64-wide wavefronts).
+//
+// The whole path is bandwidth-bound streaming: a reduction pass over g and e (Algorithm 1 line 3) and one
+// fused elementwise pass (lines 4, 6, 7).  Every global access of the two big passes is a 128-bit load or
+// store, consecutive lanes touching consecutive 16-byte groups, so a wavefront moves 1 KiB per instruction.
+// No matrix cores: there is no contraction anywhere in the method.
+#include "a2sgd_internal.h"
+
+namespace a2sgd {
+
+typedef float vf4 __attribute__((ext_vector_type(4)));
+
+template <bool NT>
+__device__ __forceinline__ vf4 ld4(const vf4 *p)
+{
+    if (NT)
+        return __builtin_nontemporal_load(p);
+    return *p;
+}
+
+template <bool NT>
+__device__ __forceinline__ void st4(vf4 *p, vf4 v)
+{
+    if (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// First-level reduction (Algorithm 1 line 3; group definitions of Sec. 3.1)
+// ---------------------------------------------------------------------------------------------------------
+
+// Running sums and counts of one lane.  Sums in fp64 so that the fp32 means come out the same as an exactly
+// summed reference; counts are taken per wavefront with a ballot and a scalar popcount, which keeps them off
+// the vector ALU.  A NaN fails both comparisons: it is counted nowhere and added to neither sum.
+struct LaneAcc {
+    double s_pos = 0.0, s_neg = 0.0;
+    // Counts of the whole wavefront, identical in every active lane.  The block reduction reads them from
+    // lane 0, which is active whenever any lane of its wavefront is (indices grow with the lane number).
+    // 32 bits hold one tile's worth (at most 64 * 16 per call of flush); the totals are 64-bit.
+    uint32_t t_pos = 0, t_neg = 0, t_zero = 0;
+    uint64_t c_pos = 0, c_neg = 0, c_zero = 0;
+
+    __device__ __forceinline__ void add(float v)
+    {
+        const bool ge = v >= 0.0f;
+        const bool lt = v < 0.0f;
+        s_pos += static_cast<double>(ge ? v : 0.0f);
+        s_neg -= static_cast<double>(lt ? v : 0.0f);
+        t_pos += __popcll(__ballot(ge));
+        t_neg += __popcll(__ballot(lt));
+        t_zero += __popcll(__ballot(v == 0.0f));
+    }
+    __device__ __forceinline__ void flush()
+    {
+        c_pos += t_pos;
+        c_neg += t_neg;
+        c_zero += t_zero;
+        t_pos = t_neg = t_zero = 0;
+    }
+    __device__ __forceinline__ void add4(vf4 v)
+    {
+        add(v.x);
+        add(v.y);
+        add(v.z);
+        add(v.w);
+    }
+};
+
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+        x += __shfl_down(x, off);
+    return x;  // valid in lane 0; the tree shape is fixed, so the result is reproducible
+}
+
+__device__ __forceinline__ uint64_t wave_sum(uint64_t x)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+        x += __shfl_down(static_cast<unsigned long long>(x), off);
+    return x;
+}
+
+// grid = (B, P).  Block b of worker p takes the tiles b, b + B, b + 2B, ... of that worker's vector; a tile is
+// kBlock * kReduceUnroll consecutive float4 groups.  Whatever does not fill a tile is taken one float4 group
+// per thread, and the last n % 4 elements one per thread, both with exact bounds: a padded lane would
+// otherwise count as "v >= 0".
+template <bool HAS_E, bool NT>
+__global__ __launch_bounds__(kBlock) void k_local_partials(const PtrTable tab, const uint64_t n, const uint32_t B,
+                                                           Partials out)
+{
+    const uint32_t p = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
+    const float *__restrict__ g = tab.g[p];
+    const float *__restrict__ e = HAS_E ? tab.e[p] : nullptr;
+    const vf4 *__restrict__ g4 = reinterpret_cast<const vf4 *>(g);
+    const vf4 *__restrict__ e4 = reinterpret_cast<const vf4 *>(e);
+
+    const uint64_t nvec = n >> 2;
+    constexpr uint64_t kTile = static_cast<uint64_t>(kBlock) * kReduceUnroll;
+    const uint64_t ntile = nvec / kTile;
+
+    LaneAcc acc;
+    for (uint64_t t = b; t < ntile; t += B) {
+        const uint64_t base = t * kTile + tid;
+        vf4 gv[kReduceUnroll], ev[kReduceUnroll];
+#pragma unroll
+        for (int u = 0; u < kReduceUnroll; ++u)
+            gv[u] = ld4<NT>(g4 + base + u * kBlock);
+        if (HAS_E) {
+#pragma unroll
+            for (int u = 0; u < kReduceUnroll; ++u)
+                ev[u] = ld4<NT>(e4 + base + u * kBlock);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keep every load of the tile ahead of the first use
+#pragma unroll
+        for (int u = 0; u < kReduceUnroll; ++u)
+            acc.add4(HAS_E ? gv[u] + ev[u] : gv[u]);
+        acc.flush();
+    }
+    // float4 groups past the last full tile
+    for (uint64_t i = ntile * kTile + static_cast<uint64_t>(b) * kBlock + tid; i < nvec;
+         i += static_cast<uint64_t>(B) * kBlock) {
+        vf4 v = ld4<NT>(g4 + i);
+        if (HAS_E)
+            v += ld4<NT>(e4 + i);
+        acc.add4(v);
+        acc.flush();
+    }
+    // last n % 4 elements
+    if (b == 0 && tid < (n & 3)) {
+        const uint64_t i = (nvec << 2) + tid;
+        acc.add(HAS_E ? g[i] + e[i] : g[i]);
+        acc.flush();
+    }
+
+    // block reduction: shuffle tree inside each wavefront, then the 4 wavefront results in index order
+    __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
+    __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
+    const double wp = wave_sum(acc.s_pos), wn = wave_sum(acc.s_neg);
+    const uint32_t lane = tid & 63, wave = tid >> 6;
+    if (lane == 0) {
+        sh_pos[wave] = wp;
+        sh_neg[wave] = wn;
+        sh_cp[wave] = acc.c_pos;
+        sh_cn[wave] = acc.c_neg;
+        sh_cz[wave] = acc.c_zero;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double sp = 0.0, sn = 0.0;
+        uint64_t cp = 0, cn = 0, cz = 0;
+#pragma unroll
+        for (int k = 0; k < kBlock / 64; ++k) {
+            sp += sh_pos[k];
+            sn += sh_neg[k];
+            cp += sh_cp[k];
+            cn += sh_cn[k];
+            cz += sh_cz[k];
+        }
+        const size_t slot = static_cast<size_t>(p) * B + b;
+        out.s_pos[slot] = sp;
+        out.s_neg[slot] = sn;
+        out.n_pos[slot] = cp;
+        out.n_neg[slot] = cn;
+        out.n_zero[slot] = cz;
+    }
+}
+
+// Second level, one block per worker: the B block partials in a fixed order (strided per thread, shuffle
+// tree, wavefronts in index order), then the two local means rounded to the fp32 that a worker would send
+// (Sec. 4.3: two means, 64 bits).  An empty group has mean 0.
+__global__ __launch_bounds__(kBlock) void k_local_finalize(const uint64_t n, const uint32_t B, const Partials in,
+                                                           WsHeader *__restrict__ hdr)
+{
+    const uint32_t p = blockIdx.x, tid = threadIdx.x;
+    const size_t row = static_cast<size_t>(p) * B;
+    double sp = 0.0, sn = 0.0;
+    uint64_t cp = 0, cn = 0, cz = 0;
+    for (uint32_t j = tid; j < B; j += kBlock) {
+        sp += in.s_pos[row + j];
+        sn += in.s_neg[row + j];
+        cp += in.n_pos[row + j];
+        cn += in.n_neg[row + j];
+        cz += in.n_zero[row + j];
+    }
+    __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
+    __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
+    sp = wave_sum(sp);
+    sn = wave_sum(sn);
+    cp = wave_sum(cp);
+    cn = wave_sum(cn);
+    cz = wave_sum(cz);
+    const uint32_t lane = tid & 63, wave = tid >> 6;
+    if (lane == 0) {
+        sh_pos[wave] = sp;
+        sh_neg[wave] = sn;
+        sh_cp[wave] = cp;
+        sh_cn[wave] = cn;
+        sh_cz[wave] = cz;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double tp = 0.0, tn = 0.0;
+        uint64_t np = 0, nn = 0, nz = 0;
+#pragma unroll
+        for (int k = 0; k < kBlock / 64; ++k) {
+            tp += sh_pos[k];
+            tn += sh_neg[k];
+            np += sh_cp[k];
+            nn += sh_cn[k];
+            nz += sh_cz[k];
+        }
+        a2sgd_worker_stats_t r;
+        r.mu_pos = np ? static_cast<float>(tp / static_cast<double>(np)) : 0.0f;
+        r.mu_neg = nn ? static_cast<float>(tn / static_cast<double>(nn)) : 0.0f;
+        r.n_pos = np;
+        r.n_neg = nn;
+        r.n_zero = nz;
+        r.n_nan = n - np - nn;
+        hdr->workers[p] = r;
+    }
+}
+
+// Algorithm 1 line 5 on one GPU: the 2P fp32 scalars to 2, summed p = 0..P-1 in fp64, divided by P.
+__global__ void k_global_average(const uint32_t P, WsHeader *__restrict__ hdr)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        double sp = 0.0, sn = 0.0;
+        for (uint32_t p = 0; p < P; ++p) {
+            sp += static_cast<double>(hdr->workers[p].mu_pos);
+            sn += static_cast<double>(hdr->workers[p].mu_neg);
+        }
+        hdr->gmu_pos = static_cast<float>(sp / static_cast<double>(P));
+        hdr->gmu_neg = static_cast<float>(sn / static_cast<double>(P));
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Fused apply pass (Algorithm 1 lines 4, 6, 7; Eq. 2 for the encoding; Eq. 1 for the average over workers)
+// ---------------------------------------------------------------------------------------------------------
+
+// One element of one worker: rewrites v into the new error and returns that worker's contribution u to the
+// update.  Written as selects on register values so that it compiles to v_cndmask, not to branches.  A NaN
+// fails v >= 0, so v + mu_neg keeps it NaN in e; the extra select keeps it NaN in u as well.
+template <int MODE>
+__device__ __forceinline__ float apply1(float &v, float neg_mu_pos, float mu_neg, float gmu_pos, float neg_gmu_neg)
+{
+    const bool ge = v >= 0.0f;
+    const float err = v + (ge ? neg_mu_pos : mu_neg);  // v - enc(v): Eq. 2, Algorithm 1 line 4
+    float glob = ge ? gmu_pos : neg_gmu_neg;           // global-mean vector at this position: line 6
+    glob = (v != v) ? v : glob;
+    v = err;
+    return MODE == A2SGD_MODE_ALG1_LITERAL ? err + glob : glob;
+}
+
+template <int MODE>
+__device__ __forceinline__ void apply4(vf4 &v, vf4 &acc, float neg_mu_pos, float mu_neg, float gmu_pos,
+                                       float neg_gmu_neg)
+{
+    float x = v.x, y = v.y, z = v.z, t = v.w;
+    acc.x += apply1<MODE>(x, neg_mu_pos, mu_neg, gmu_pos, neg_gmu_neg);
+    acc.y += apply1<MODE>(y, neg_mu_pos, mu_neg, gmu_pos, neg_gmu_neg);
+    acc.z += apply1<MODE>(z, neg_mu_pos, mu_neg, gmu_pos, neg_gmu_neg);
+    acc.w += apply1<MODE>(t, neg_mu_pos, mu_neg, gmu_pos, neg_gmu_neg);
+    v = vf4{x, y, z, t};
+}
+
+constexpr int kApplyUnrollP = 4;  // workers whose loads are issued together
+
+// grid = ceil(ceil(n/4) / kBlock) blocks; thread i owns float4 group i of every worker and of w.  The loop
+// over workers issues the g and e loads of kApplyUnrollP workers before using any of them.  The last block's
+// first n % 4 threads also take the scalar tail.
+template <int MODE, bool HAS_E, bool NT>
+__global__ __launch_bounds__(kBlock) void k_apply(const PtrTable tab, float *__restrict__ w, const uint64_t n,
+                                                  const uint32_t P, const float eta_over_P,
+                                                  const WsHeader *__restrict__ hdr)
+{
+    __shared__ float s_neg_mu_pos[kMaxWorkers], s_mu_neg[kMaxWorkers];
+    const uint32_t tid = threadIdx.x;
+    if (tid < P) {
+        s_neg_mu_pos[tid] = -hdr->workers[tid].mu_pos;
+        s_mu_neg[tid] = hdr->workers[tid].mu_neg;
+    }
+    const float gmu_pos = hdr->gmu_pos, neg_gmu_neg = -hdr->gmu_neg;
+    __syncthreads();
+
+    const uint64_t nvec = n >> 2;
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * kBlock + tid;
+    if (i < nvec) {
+        vf4 *w4 = reinterpret_cast<vf4 *>(w) + i;
+        const vf4 wv = ld4<NT>(w4);
+        vf4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        uint32_t p0 = 0;
+        for (; p0 + kApplyUnrollP <= P; p0 += kApplyUnrollP) {
+            vf4 v[kApplyUnrollP], ev[kApplyUnrollP];
+#pragma unroll
+            for (int u = 0; u < kApplyUnrollP; ++u)
+                v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + i);
+            if (HAS_E) {
+#pragma unroll
+                for (int u = 0; u < kApplyUnrollP; ++u)
+                    ev[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0 + u]) + i);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep every load of the group ahead of the first use
+#pragma unroll
+            for (int u = 0; u < kApplyUnrollP; ++u) {
+                if (HAS_E)
+                    v[u] += ev[u];
+                apply4<MODE>(v[u], acc, s_neg_mu_pos[p0 + u], s_mu_neg[p0 + u], gmu_pos, neg_gmu_neg);
+                if (HAS_E)
+                    st4<NT>(reinterpret_cast<vf4 *>(tab.e[p0 + u]) + i, v[u]);
+            }
+        }
+        for (; p0 < P; ++p0) {
+            vf4 v = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0]) + i);
+            if (HAS_E)
+                v += ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0]) + i);
+            apply4<MODE>(v, acc, s_neg_mu_pos[p0], s_mu_neg[p0], gmu_pos, neg_gmu_neg);
+            if (HAS_E)
+                st4<NT>(reinterpret_cast<vf4 *>(tab.e[p0]) + i, v);
+        }
+        st4<NT>(w4, wv - eta_over_P * acc);
+    }
+    if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
+        const uint64_t k = (nvec << 2) + tid;
+        float acc = 0.0f;
+        for (uint32_t p = 0; p < P; ++p) {
+            float v = tab.g[p][k];
+            if (HAS_E)
+                v += tab.e[p][k];
+            acc += apply1<MODE>(v, s_neg_mu_pos[p], s_mu_neg[p], gmu_pos, neg_gmu_neg);
+            if (HAS_E)
+                tab.e[p][k] = v;
+        }
+        w[k] -= eta_over_P * acc;
+    }
+}
+
+// Eq. 1 / Algorithm 1 lines 9-10: w <- w - eta * mean_p g^p.  Same thread-to-data mapping as k_apply.
+template <bool NT>
+__global__ __launch_bounds__(kBlock) void k_dense_step(const PtrTable tab, float *__restrict__ w, const uint64_t n,
+                                                       const uint32_t P, const float eta_over_P)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint64_t nvec = n >> 2;
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * kBlock + tid;
+    if (i < nvec) {
+        vf4 *w4 = reinterpret_cast<vf4 *>(w) + i;
+        const vf4 wv = ld4<NT>(w4);
+        vf4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        uint32_t p0 = 0;
+        for (; p0 + kApplyUnrollP <= P; p0 += kApplyUnrollP) {
+            vf4 v[kApplyUnrollP];
+#pragma unroll
+            for (int u = 0; u < kApplyUnrollP; ++u)
+                v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + i);
+#pragma unroll
+            for (int u = 0; u < kApplyUnrollP; ++u)
+                acc += v[u];
+        }
+        for (; p0 < P; ++p0)
+            acc += ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0]) + i);
+        st4<NT>(w4, wv - eta_over_P * acc);
+    }
+    if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
+        const uint64_t k = (nvec << 2) + tid;
+        float acc = 0.0f;
+        for (uint32_t p = 0; p < P; ++p)
+            acc += tab.g[p][k];
+        w[k] -= eta_over_P * acc;
+    }
+}
+
+// Test aid: pos(v) of Eq. 2 as one bit per element.  grid = (ceil(n / kBlock), P); a wavefront covers 64
+// consecutive elements, so its ballot is exactly one output word.
+template <bool HAS_E>
+__global__ __launch_bounds__(kBlock) void k_export_mask(const PtrTable tab, const uint64_t n, const uint64_t words,
+                                                        uint64_t *__restrict__ mask)
+{
+    const uint32_t p = blockIdx.y;
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    bool bit = false;
+    if (i < n) {
+        float v = tab.g[p][i];
+        if (HAS_E)
+            v += tab.e[p][i];
+        bit = v >= 0.0f;
+    }
+    const uint64_t word = __ballot(bit);
+    if ((threadIdx.x & 63) == 0 && (i >> 6) < words)
+        mask[static_cast<uint64_t>(p) * words + (i >> 6)] = word;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------------------------------------
+
+static inline uint32_t apply_grid(uint64_t n)
+{
+    const uint64_t nvec = (n + 3) >> 2;  // the scalar tail rides in the last block even when n < 4
+    return static_cast<uint32_t>((nvec + kBlock - 1) / kBlock);
+}
+
+hipError_t launch_local_partials(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, void *ws, hipStream_t s)
+{
+    const dim3 grid(pl.B, pl.P), block(kBlock);
+    const Partials out = partials_of(ws, pl.P, pl.B);
+    if (has_e) {
+        if (pl.streaming)
+            k_local_partials<true, true><<<grid, block, 0, s>>>(tab, pl.n, pl.B, out);
+        else
+            k_local_partials<true, false><<<grid, block, 0, s>>>(tab, pl.n, pl.B, out);
+    } else {
+        if (pl.streaming)
+            k_local_partials<false, true><<<grid, block, 0, s>>>(tab, pl.n, pl.B, out);
+        else
+            k_local_partials<false, false><<<grid, block, 0, s>>>(tab, pl.n, pl.B, out);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_local_finalize(const a2sgd_plan_t &pl, void *ws, hipStream_t s)
+{
+    k_local_finalize<<<dim3(pl.P), dim3(kBlock), 0, s>>>(pl.n, pl.B, partials_of(ws, pl.P, pl.B),
+                                                        static_cast<WsHeader *>(ws));
+    return hipGetLastError();
+}
+
+hipError_t launch_global_average(const a2sgd_plan_t &pl, void *ws, hipStream_t s)
+{
+    k_global_average<<<dim3(1), dim3(64), 0, s>>>(pl.P, static_cast<WsHeader *>(ws));
+    return hipGetLastError();
+}
+
+template <int MODE>
+static hipError_t launch_apply_mode(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eop,
+                                    const WsHeader *hdr, hipStream_t s)
+{
+    const dim3 grid(apply_grid(pl.n)), block(kBlock);
+    if (has_e) {
+        if (pl.streaming)
+            k_apply<MODE, true, true><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, hdr);
+        else
+            k_apply<MODE, true, false><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, hdr);
+    } else {
+        if (pl.streaming)
+            k_apply<MODE, false, true><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, hdr);
+        else
+            k_apply<MODE, false, false><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, hdr);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
+                        hipStream_t s)
+{
+    const float eop = static_cast<float>(static_cast<double>(eta) / static_cast<double>(pl.P));
+    const WsHeader *hdr = static_cast<const WsHeader *>(ws);
+    if (pl.mode == A2SGD_MODE_ALG1_LITERAL)
+        return launch_apply_mode<A2SGD_MODE_ALG1_LITERAL>(pl, tab, has_e, w, eop, hdr, s);
+    return launch_apply_mode<A2SGD_MODE_RETAINED_ERROR>(pl, tab, has_e, w, eop, hdr, s);
+}
+
+hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, uint64_t *mask, hipStream_t s)
+{
+    const uint64_t words = (pl.n + 63) / 64;
+    const dim3 grid(static_cast<uint32_t>((pl.n + kBlock - 1) / kBlock), pl.P), block(kBlock);
+    if (has_e)
+        k_export_mask<true><<<grid, block, 0, s>>>(tab, pl.n, words, mask);
+    else
+        k_export_mask<false><<<grid, block, 0, s>>>(tab, pl.n, words, mask);
+    return hipGetLastError();
+}
+
+hipError_t launch_dense_step(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eta, hipStream_t s)
+{
+    const float eop = static_cast<float>(static_cast<double>(eta) / static_cast<double>(pl.P));
+    const dim3 grid(apply_grid(pl.n)), block(kBlock);
+    if (pl.streaming)
+        k_dense_step<true><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop);
+    else
+        k_dense_step<false><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop);
+    return hipGetLastError();
+}
+
+}  // namespace a2sgd

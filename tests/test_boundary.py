@@ -1,0 +1,134 @@
+"""CPU-only checks of the C ABI: the library loads, exports everything include/a2sgd.h declares, and rejects bad
+arguments before launching anything (so these run with no GPU present)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "a2sgd.h")
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2006_07405_amd as A
+    return A
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(a2sgd_[a-z_]+)\s*\(", src)))
+
+
+def test_header_functions_are_exported(A):
+    names = declared_functions()
+    assert {"a2sgd_plan", "a2sgd_local_averages", "a2sgd_global_average", "a2sgd_apply_and_update_error",
+            "a2sgd_step", "a2sgd_read_stats", "a2sgd_export_mask", "a2sgd_dense_step", "a2sgd_workspace_bytes",
+            "a2sgd_plan_destroy", "a2sgd_status_string", "a2sgd_plan_blocks_per_worker"} <= set(names)
+    lib = C.CDLL(A.LIB_PATH)
+    for name in names:
+        assert hasattr(lib, name), f"{name} is declared in a2sgd.h but not exported"
+
+
+def test_binding_has_the_same_names(A):
+    for name in declared_functions():
+        if name == "a2sgd_plan_destroy" or name == "a2sgd_status_string":
+            continue  # owned by Plan.__del__ / A2sgdError
+        assert hasattr(A, name), f"binding lacks {name}"
+
+
+def test_struct_layouts_match_header(A):
+    from paper_2006_07405_amd import binding as B
+    assert C.sizeof(B.a2sgd_worker_stats_t) == 40
+    assert C.sizeof(B.a2sgd_config_t) == 24
+    assert C.sizeof(B.a2sgd_global_stats_t) == 8
+
+
+@pytest.mark.parametrize("n,P,mode,bpw", [(0, 4, 0, 0), (10, 0, 0, 0), (10, 65, 0, 0), (10, 4, 2, 0), (10, 4, -1, 0),
+                                          ((1 << 40) + 1, 4, 0, 0), (10, 4, 0, 65537)])
+def test_plan_rejects_bad_config(A, n, P, mode, bpw):
+    with pytest.raises(A.A2sgdError) as ei:
+        A.a2sgd_plan(n, P, mode, bpw)
+    assert ei.value.status == A.A2SGD_ERR_INVALID_ARG
+
+
+def test_plan_null_pointers(A):
+    from paper_2006_07405_amd import binding as B
+    cfg = B.a2sgd_config_t(10, 2, 0, 0, 0)
+    h = C.c_void_p()
+    assert A.raw.a2sgd_plan(None, C.byref(h)) == A.A2SGD_ERR_INVALID_ARG
+    assert A.raw.a2sgd_plan(C.byref(cfg), None) == A.A2SGD_ERR_INVALID_ARG
+    cfg.reserved = 1
+    assert A.raw.a2sgd_plan(C.byref(cfg), C.byref(h)) == A.A2SGD_ERR_INVALID_ARG
+    assert A.raw.a2sgd_workspace_bytes(None) == 0
+    assert A.raw.a2sgd_plan_destroy(None) == A.A2SGD_OK
+
+
+def test_plan_geometry(A):
+    p = A.a2sgd_plan(1_500_000_000, 4)
+    assert A.a2sgd_plan_blocks_per_worker(p) == 512  # 256 CUs x 8 resident workgroups / 4 workers
+    assert A.a2sgd_workspace_bytes(p) == 4096 + 5 * 8 * 4 * 512
+    p = A.a2sgd_plan(5, 3)
+    assert A.a2sgd_plan_blocks_per_worker(p) == 1
+    p = A.a2sgd_plan(1000, 2, blocks_per_worker=7)
+    assert A.a2sgd_plan_blocks_per_worker(p) == 7
+
+
+def _tab(vals):
+    return (C.c_void_p * len(vals))(*vals)
+
+
+def test_step_calls_validate_before_launch(A):
+    """Hand-made pointer values: nothing is dereferenced on the host, and every call must fail in validation."""
+    plan = A.a2sgd_plan(1000, 2)
+    good = _tab([0x10000, 0x20000])
+    misaligned = _tab([0x10000, 0x20004])
+    with_null = _tab([0x10000, 0])
+    ws, w = 0x30000, 0x40000
+    R, h = A.raw, plan.handle
+    INV, ALN = A.A2SGD_ERR_INVALID_ARG, A.A2SGD_ERR_ALIGNMENT
+    assert R.a2sgd_local_averages(None, good, good, ws, None) == INV
+    assert R.a2sgd_local_averages(h, None, good, ws, None) == INV
+    assert R.a2sgd_local_averages(h, good, None, ws, None) == INV  # retained-error mode needs e
+    assert R.a2sgd_local_averages(h, with_null, good, ws, None) == INV
+    assert R.a2sgd_local_averages(h, good, misaligned, ws, None) == ALN
+    assert R.a2sgd_local_averages(h, good, good, None, None) == INV
+    assert R.a2sgd_local_averages(h, good, good, ws + 8, None) == ALN
+    assert R.a2sgd_global_average(None, ws, None) == INV
+    assert R.a2sgd_global_average(h, None, None) == INV
+    assert R.a2sgd_apply_and_update_error(h, good, good, None, 0.1, ws, None) == INV
+    assert R.a2sgd_apply_and_update_error(h, good, good, w + 4, 0.1, ws, None) == ALN
+    assert R.a2sgd_apply_and_update_error(h, misaligned, good, w, 0.1, ws, None) == ALN
+    assert R.a2sgd_step(h, good, with_null, w, 0.1, ws, None) == INV
+    assert R.a2sgd_step(h, good, good, w, 0.1, ws + 4, None) == ALN
+    assert R.a2sgd_export_mask(h, good, good, None, None) == INV
+    assert R.a2sgd_export_mask(h, good, misaligned, ws, None) == ALN
+    assert R.a2sgd_dense_step(h, None, w, 0.1, None) == INV
+    assert R.a2sgd_dense_step(h, good, w + 2, 0.1, None) == ALN
+    assert R.a2sgd_read_stats(h, None, None, None, None) == INV
+    assert R.a2sgd_status_string(ALN) == b"device pointer not 16-byte aligned"
+
+
+def test_binding_checks_shapes_without_touching_the_gpu(A):
+    import torch
+    plan = A.a2sgd_plan(100, 2)
+    cpu = [torch.zeros(100), torch.zeros(100)]
+    with pytest.raises(TypeError):
+        A.a2sgd_local_averages(plan, cpu, cpu, torch.zeros(1000))
+    with pytest.raises(ValueError):
+        A.a2sgd_local_averages(plan, cpu[:1], cpu, torch.zeros(1000))
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2006_07405_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f"{f} mentions the oracle"
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2006_07405_amd" not in text and "a2sgd.h" not in text

@@ -1,0 +1,267 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Element-by-element at sizes the oracle finishes quickly (these span several tiles of the reduction and ragged
+tails of every kind); the five benchmark configurations at full size live in test_gpu_full_size.py.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import a2sgd_oracle as O
+from tests.helpers import (assert_array_close, check_against_oracle, compare_stats, dev, gpu_step)
+
+pytestmark = pytest.mark.gpu
+f32 = np.float32
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "worked_example.txt")
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2006_07405_amd as A
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    assert os.path.exists(A.LIB_PATH)
+    return A
+
+
+def make_case(seed, n, P, scale=1e-3, zeros=True):
+    rng = np.random.default_rng(seed)
+    g = [(rng.standard_normal(n) * scale).astype(f32) for _ in range(P)]
+    e = [(rng.standard_normal(n) * scale * 0.5).astype(f32) for _ in range(P)]
+    if zeros and n >= 8:
+        for p in range(P):
+            idx = rng.integers(0, n, max(1, n // 50))
+            g[p][idx] = 0.0
+            e[p][idx] = 0.0
+    w = (rng.standard_normal(n) * 0.02).astype(f32)
+    return g, e, w
+
+
+# a tile of the reduction is 4096 elements, a block of the apply pass covers 1024
+SIZES = [1, 2, 3, 4, 5, 7, 8, 63, 64, 65, 255, 256, 257, 1023, 1024, 1025, 1027, 4095, 4096, 4097, 4099, 8191,
+         12289, 40961, 65539, 300_001]
+
+
+@pytest.mark.parametrize("n", SIZES)
+def test_sizes_and_tails(A, n):
+    for P, mode in ((1, 0), (3, 0), (4, 1)):
+        print(f"case n={n} P={P} mode={mode}", flush=True)
+        g, e, w = make_case(n * 31 + P, n, P)
+        check_against_oracle(A, g, e, w, 0.1, mode)
+
+
+@pytest.mark.parametrize("P", [1, 2, 3, 4, 5, 7, 8, 9, 16, 17, 33, 64])
+def test_worker_counts(A, P):
+    print(f"case P={P}", flush=True)
+    g, e, w = make_case(1000 + P, 20_003, P)
+    check_against_oracle(A, g, e, w, 0.05, 0)
+    check_against_oracle(A, g, e, w, 0.05, 1, split_calls=False)
+
+
+def test_literal_mode_without_error_buffer(A):
+    g, _, w = make_case(5, 70_001, 4)
+    (stats, gmu, e_new, w_new, _), ref = check_against_oracle(A, g, None, w, 0.1, 1)
+    assert e_new is None
+    # P = 1: Theorem 1's net gain vanishes and the step is plain SGD, w - eta*g
+    g1, _, w1 = make_case(6, 33_333, 1)
+    _, _, _, w_new, _ = gpu_step(A, g1, None, w1, 0.25, 1)
+    ref = w1.astype(np.float64) - 0.25 * g1[0].astype(np.float64)
+    assert np.max(np.abs(w_new - ref)) <= 2e-8
+
+
+def test_worked_example(A):
+    G = {}
+    for line in open(GOLDEN):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split("=")
+            G[k.strip()] = [float(t) for t in v.split()]
+    w = np.zeros(6, f32)
+    e = [np.zeros(6, f32), np.zeros(6, f32)]
+    for s in ("step1", "step2"):
+        g = [np.array(G[f"{s}.gA"], f32), np.array(G[f"{s}.gB"], f32)]
+        stats, gmu, e, w, mask = gpu_step(A, g, e, w, 0.5, 0, want_mask=True)
+        for name, st in zip("AB", stats):
+            assert (st.n_pos, st.n_neg, st.n_zero) == tuple(G[f"{s}.{name}.{k}"][0] for k in ("n_pos", "n_neg", "n_zero"))
+            assert (st.mu_pos, st.mu_neg) == (G[f"{s}.{name}.mu_pos"][0], G[f"{s}.{name}.mu_neg"][0])
+        assert gmu == (G[f"{s}.gmu_pos"][0], G[f"{s}.gmu_neg"][0])
+        assert np.array_equal(e[0], np.array(G[f"{s}.eA"], f32)) and np.array_equal(e[1], np.array(G[f"{s}.eB"], f32))
+        assert list(mask[0]) == G[f"{s}.maskA"] and list(mask[1]) == G[f"{s}.maskB"]
+        assert np.array_equal(w, np.array(G[f"{s}.w"], f32))
+    g = [np.array(G["step1.gA"], f32), np.array(G["step1.gB"], f32)]
+    _, _, _, w, _ = gpu_step(A, g, None, np.zeros(6, f32), 0.5, 1)
+    assert np.array_equal(w, np.array(G["step1.literal.w"], f32))
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_small_variants_of_the_five_configs(A, k):
+    wl = workloads.small(k)
+    P = wl.num_workers
+    g = [wl.gradient(p).numpy() for p in range(P)]
+    e = [wl.synthetic_error(p).numpy() for p in range(P)]
+    w = wl.weights().numpy()
+    check_against_oracle(A, g, e, w, wl.eta, 0)
+    check_against_oracle(A, g, [np.zeros_like(x) for x in g], w, wl.eta, 0)  # the configs start from e = 0
+    check_against_oracle(A, g, e, w, wl.eta, 1)
+
+
+def test_edge_cases(A):
+    z4 = np.zeros(4, f32)
+    # all entries >= 0: the negative group is empty, its mean is 0
+    (st, gmu, e_new, w_new, _), _ = check_against_oracle(A, [np.array([1, 2, 3, 0], f32)], [z4], z4, 1.0, 0)
+    assert (st[0].n_pos, st[0].n_neg, st[0].mu_pos, st[0].mu_neg) == (4, 0, 1.5, 0.0)
+    assert np.array_equal(e_new[0], np.array([-0.5, 0.5, 1.5, -1.5], f32))
+    # all entries < 0
+    (st, gmu, e_new, w_new, _), _ = check_against_oracle(A, [np.array([-1, -2, -3, -2], f32)], [z4], z4, 1.0, 0)
+    assert (st[0].n_pos, st[0].n_neg, st[0].mu_pos, st[0].mu_neg) == (0, 4, 0.0, 2.0)
+    assert np.array_equal(w_new, np.array([2, 2, 2, 2], f32))
+    # one worker all positive, the other all negative: empty groups enter the global mean as 0
+    (st, gmu, _, w_new, _), _ = check_against_oracle(
+        A, [np.array([1, 2, 3, 0], f32), np.array([-1, -2, -3, -2], f32)], [z4, z4], z4, 1.0, 0)
+    assert gmu == (0.75, 1.0) and np.array_equal(w_new, np.full(4, 0.125, f32))
+    # all zeros, including -0.0
+    v = np.array([0.0, -0.0, 0.0, -0.0, 0.0], f32)
+    (st, _, e_new, _, mask), _ = check_against_oracle(A, [v], [np.zeros(5, f32)], np.ones(5, f32), 1.0, 0)
+    assert (st[0].n_pos, st[0].n_zero, st[0].n_neg) == (5, 5, 0) and list(mask[0]) == [1] * 5
+    # g and e cancel exactly: v = +0 belongs to the ">= 0" group
+    g = np.array([1.5, -2.5, 3.0], f32)
+    (st, _, _, _, _), _ = check_against_oracle(A, [g], [-g], np.zeros(3, f32), 1.0, 0)
+    assert st[0].n_pos == 3 and st[0].n_zero == 3
+    # denormals keep their sign group (no flush to zero)
+    d = np.array([1e-45, -1e-45, 1e-40, -1e-40, 0.0, 3e-39, -3e-39], f32)
+    (st, _, _, _, _), _ = check_against_oracle(A, [d], [np.zeros(7, f32)], np.zeros(7, f32), 1.0, 0)
+    assert (st[0].n_pos, st[0].n_neg, st[0].n_zero) == (4, 3, 1)
+    # a two-valued vector is encoded without loss
+    v = np.array([0.375, -1.25] * 3000 + [0.375], f32)
+    (_, _, e_new, _, _), _ = check_against_oracle(A, [v], [np.zeros_like(v)], np.zeros_like(v), 1.0, 0)
+    assert not e_new[0].any()
+    # huge and tiny magnitudes together: fp64 sums do not lose the tiny group
+    v = np.array([1e30, 2e30, -1e-30, -3e-30] * 1000, f32)
+    check_against_oracle(A, [v], [np.zeros_like(v)], np.zeros_like(v), 1e-30, 0)
+
+
+def test_nan_is_in_neither_group(A):
+    g, e, w = make_case(77, 10_007, 2)
+    g[0][[3, 5000, 10_006]] = np.nan
+    (st, _, e_new, w_new, _), _ = check_against_oracle(A, g, e, w, 0.1, 0)
+    assert st[0].n_nan == 3 and st[1].n_nan == 0 and st[0].n_pos + st[0].n_neg + 3 == 10_007
+    assert np.isnan(w_new).sum() == 3 and np.isnan(e_new[0]).sum() == 3 and not np.isnan(e_new[1]).any()
+    check_against_oracle(A, g, e, w, 0.1, 1)
+
+
+def test_deterministic_and_block_count_independent(A):
+    g, e, w = make_case(99, 500_009, 4)
+    a = gpu_step(A, g, e, w, 0.1, 0)
+    b = gpu_step(A, g, e, w, 0.1, 0)
+    assert [vars(s) for s in a[0]] == [vars(s) for s in b[0]] and a[1] == b[1]
+    assert all(np.array_equal(x.view(np.uint32), y.view(np.uint32)) for x, y in zip(a[2], b[2]))
+    assert np.array_equal(a[3].view(np.uint32), b[3].view(np.uint32))
+    ref = O.step(g, e, w, 0.1, 0)
+    for bpw in (1, 2, 3, 17, 128, 1000, 4096):
+        print(f"case blocks_per_worker={bpw}", flush=True)
+        st, gmu, e_new, w_new, _ = gpu_step(A, g, e, w, 0.1, 0, blocks_per_worker=bpw)
+        compare_stats(st, gmu, ref)
+        assert_array_close(w_new, ref.w_new, "w")
+
+
+def test_power_of_two_scaling_is_bitwise(A):
+    """g, e times 2^k and eta times 2^-k: means and errors scale exactly; counts and new weights are unchanged."""
+    g, e, w = make_case(123, 200_003, 3)
+    k = 6
+    a = gpu_step(A, g, e, w, 0.125, 0)
+    b = gpu_step(A, [x * f32(2.0 ** k) for x in g], [x * f32(2.0 ** k) for x in e], w, 0.125 * 2.0 ** -k, 0)
+    for sa, sb in zip(a[0], b[0]):
+        assert (sb.mu_pos, sb.mu_neg) == (sa.mu_pos * 2 ** k, sa.mu_neg * 2 ** k)
+        assert (sb.n_pos, sb.n_neg, sb.n_zero) == (sa.n_pos, sa.n_neg, sa.n_zero)
+    assert all(np.array_equal(x * f32(2.0 ** k), y) for x, y in zip(a[2], b[2]))
+    assert np.array_equal(a[3], b[3])
+
+
+def test_config1_ten_steps_teacher_forced_and_free_running(A):
+    """Config 1 at full size (n = 1,048,576, P = 4, 10 steps, fresh gradients each step).  Teacher-forced: both
+    sides start every step from the oracle's state.  Free-running: each side carries its own state."""
+    wl = workloads.config1()
+    n, P = wl.n, wl.num_workers
+    plan = A.a2sgd_plan(n, P, 0)
+    ws = A.alloc_workspace(plan)
+    w_o = wl.weights().numpy()
+    e_o = [np.zeros(n, f32) for _ in range(P)]
+    w_f = dev(w_o)
+    e_f = [dev(x) for x in e_o]
+    flips = 0
+    for t in range(wl.steps):
+        print(f"step {t}", flush=True)
+        g = [wl.gradient(p, t).numpy() for p in range(P)]
+        gd = [dev(x) for x in g]
+        ref = O.step(g, e_o, w_o, wl.eta, 0)
+        # teacher-forced
+        e_t = [dev(x) for x in e_o]
+        w_t = dev(w_o)
+        A.a2sgd_step(plan, gd, e_t, w_t, wl.eta, ws)
+        st, gmu = A.a2sgd_read_stats(plan, ws)
+        compare_stats(st, gmu, ref)
+        for p in range(P):
+            assert_array_close(e_t[p].cpu().numpy(), ref.e_new[p], f"step {t} e[{p}]")
+        assert_array_close(w_t.cpu().numpy(), ref.w_new, f"step {t} w")
+        # free-running
+        A.a2sgd_step(plan, gd, e_f, w_f, wl.eta, ws)
+        st_f, gmu_f = A.a2sgd_read_stats(plan, ws)
+        for p in range(P):
+            flips += abs(st_f[p].n_pos - ref.workers[p].n_pos)
+        e_o, w_o = ref.e_new, ref.w_new
+    for p in range(P):
+        assert_array_close(e_f[p].cpu().numpy(), e_o[p], f"free-running e[{p}] after 10 steps")
+    assert_array_close(w_f.cpu().numpy(), w_o, "free-running w after 10 steps")
+    assert flips == 0, f"{flips} sign-group flips between the free-running GPU state and the oracle"
+
+
+def test_checkpoint_resume_is_bitwise(A):
+    """State = (w, e^p): 6 steps in one go equal 3 steps, a copy of the state out and back in, and 3 more."""
+    wl = workloads.config1(n=262_147, num_workers=3)
+    n, P = wl.n, wl.num_workers
+    plan = A.a2sgd_plan(n, P, 0)
+    ws = A.alloc_workspace(plan)
+    grads = [[wl.gradient(p, t, device="cuda") for p in range(P)] for t in range(6)]
+    w1 = wl.weights(device="cuda")
+    e1 = [torch.zeros(n, device="cuda") for _ in range(P)]
+    for t in range(6):
+        A.a2sgd_step(plan, grads[t], e1, w1, wl.eta, ws)
+    w2 = wl.weights(device="cuda")
+    e2 = [torch.zeros(n, device="cuda") for _ in range(P)]
+    for t in range(3):
+        A.a2sgd_step(plan, grads[t], e2, w2, wl.eta, ws)
+    saved = ([x.cpu() for x in e2], w2.cpu())
+    plan2 = A.a2sgd_plan(n, P, 0)
+    ws2 = A.alloc_workspace(plan2)
+    e3 = [x.cuda() for x in saved[0]]
+    w3 = saved[1].cuda()
+    for t in range(3, 6):
+        A.a2sgd_step(plan2, grads[t], e3, w3, wl.eta, ws2)
+    assert torch.equal(w1, w3) and all(torch.equal(a, b) for a, b in zip(e1, e3))
+
+
+def test_dense_step(A):
+    for n, P in ((1, 1), (5, 3), (4099, 4), (300_001, 8), (65_536, 5)):
+        g, _, w = make_case(n + P, n, P)
+        plan = A.a2sgd_plan(n, P)
+        gd = [dev(x) for x in g]
+        wd = dev(w)
+        A.a2sgd_dense_step(plan, gd, wd, 0.1)
+        assert_array_close(wd.cpu().numpy(), O.dense_step(g, w, 0.1), f"dense n={n} P={P}")
+
+
+def test_runs_on_a_side_stream_and_respects_stream_order(A):
+    g, e, w = make_case(4242, 1_000_003, 4)
+    ref = O.step(g, e, w, 0.1, 0)
+    s = torch.cuda.Stream()
+    plan = A.a2sgd_plan(len(w), 4)
+    with torch.cuda.stream(s):
+        ws = A.alloc_workspace(plan)
+        gd, ed, wd = [dev(x) for x in g], [dev(x) for x in e], dev(w)
+        A.a2sgd_step(plan, gd, ed, wd, 0.1, ws)  # picks up the current torch stream
+        st, gmu = A.a2sgd_read_stats(plan, ws)
+    s.synchronize()
+    compare_stats(st, gmu, ref)
+    assert_array_close(wd.cpu().numpy(), ref.w_new, "w")
