@@ -9,9 +9,23 @@ using namespace a2sgd;
 namespace {
 
 constexpr uint64_t kMaxN = 1ull << 40;
-// Compute units of one MI355X and the workgroups of 256 threads each of them keeps resident.
+// Compute units of one MI355X.  Both big passes run fastest with few wavefronts per compute unit, each with
+// many 128-bit loads in flight (about 60 KiB in flight per CU); more wavefronts only widen the span of addresses
+// that is open at once and HBM efficiency drops.  The reduction keeps 2 workgroups of 256 threads per CU.
 constexpr uint32_t kComputeUnits = 256;
-constexpr uint32_t kBlocksPerCU = 8;
+constexpr uint32_t kReduceBlocksPerCU = 2;
+
+// The apply pass runs single-wavefront workgroups and caps how many share a CU through its dynamic-LDS request
+// (160 KiB per CU; the request sits in the middle of the range that yields the wanted count).  A wavefront
+// has 2 * up + 1 float4 loads per lane in flight, so fewer wavefronts are wanted when up is larger.
+uint32_t apply_lds_bytes(uint32_t P)
+{
+    if (P >= 16)
+        return 48 * 1024;  // 3 per CU
+    if (P >= 8)
+        return 36 * 1024;  // 4 per CU
+    return 25 * 1024;      // 6 per CU
+}
 // Above this many bytes of g + e + w the step cannot live in the 256 MiB last-level cache between its two
 // passes, and every load and store is issued as non-temporal.
 constexpr uint64_t kStreamingBytes = 192ull << 20;
@@ -22,7 +36,7 @@ uint32_t choose_blocks_per_worker(uint64_t n, uint32_t P)
 {
     const uint64_t tile = static_cast<uint64_t>(kBlock) * kReduceUnroll * 4;  // elements per tile
     uint64_t tiles = (n + tile - 1) / tile;
-    uint64_t want = (static_cast<uint64_t>(kComputeUnits) * kBlocksPerCU + P - 1) / P;
+    uint64_t want = (static_cast<uint64_t>(kComputeUnits) * kReduceBlocksPerCU + P - 1) / P;
     uint64_t B = tiles < want ? tiles : want;
     if (B < 1)
         B = 1;
@@ -100,6 +114,8 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
     pl->mode = cfg->mode;
     pl->B = cfg->blocks_per_worker ? cfg->blocks_per_worker : choose_blocks_per_worker(pl->n, pl->P);
     pl->streaming = (2ull * pl->P + 1) * 4ull * pl->n > kStreamingBytes;
+    pl->apply.up = pl->P >= 8 ? 8 : pl->P >= 4 ? 4 : pl->P >= 2 ? 2 : 1;
+    pl->apply.lds_bytes = pl->streaming ? apply_lds_bytes(pl->P) : 0;
     pl->workspace_bytes = kHeaderBytes + 5ull * 8ull * pl->P * pl->B;
     *out_plan = pl;
     return A2SGD_OK;

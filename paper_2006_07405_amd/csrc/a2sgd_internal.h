@@ -24,6 +24,8 @@ struct WsHeader {
     float gmu_pos, gmu_neg;  // Algorithm 1 line 5
     uint32_t pad[2];
     a2sgd_worker_stats_t workers[kMaxWorkers];  // Algorithm 1 line 3, per worker
+    float neg_mu_pos[kMaxWorkers];  // -mu_pos and mu_neg of every worker again, packed for the apply pass
+    float mu_neg[kMaxWorkers];
 };
 constexpr size_t kHeaderBytes = 4096;
 static_assert(sizeof(WsHeader) <= kHeaderBytes, "header must fit its slot");
@@ -55,12 +57,22 @@ struct PtrTable {
 
 }  // namespace a2sgd
 
+namespace a2sgd {
+// Shape of the apply pass: the loads of `up` workers are issued together; lds_bytes of dynamic LDS per
+// workgroup (0 = none) set how many workgroups fit a compute unit.
+struct ApplyGeom {
+    int up;
+    uint32_t lds_bytes;
+};
+}  // namespace a2sgd
+
 struct a2sgd_plan {
     uint64_t n;
     uint32_t P;
     int32_t mode;
     uint32_t B;           // blocks per worker in the first-level reduction
     bool streaming;       // footprint exceeds the on-chip caches: use non-temporal loads and stores
+    a2sgd::ApplyGeom apply;
     size_t workspace_bytes;
 };
 

@@ -236,6 +236,11 @@ __global__ void k_global_average(const uint32_t P, WsHeader *__restrict__ hdr)
         hdr->gmu_pos = static_cast<float>(sp / static_cast<double>(P));
         hdr->gmu_neg = static_cast<float>(sn / static_cast<double>(P));
     }
+    // the same local means again, packed and pre-negated the way the apply pass consumes them
+    for (uint32_t p = threadIdx.x; p < P && blockIdx.x == 0; p += blockDim.x) {
+        hdr->neg_mu_pos[p] = -hdr->workers[p].mu_pos;
+        hdr->mu_neg[p] = hdr->workers[p].mu_neg;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -256,88 +261,164 @@ __device__ __forceinline__ float apply1(float &v, float neg_mu_pos, float mu_neg
     return MODE == A2SGD_MODE_ALG1_LITERAL ? err + glob : glob;
 }
 
+// Four elements of one worker.  Returns the new error as a fresh value (storing a value that was updated in
+// place in a register array has been seen to lose its non-temporal hint on the way through the optimiser).
 template <int MODE>
-__device__ __forceinline__ void apply4(vf4 &v, vf4 &acc, float neg_mu_pos, float mu_neg, float gmu_pos,
-                                       float neg_gmu_neg)
+__device__ __forceinline__ vf4 apply4(vf4 v, vf4 &acc, float neg_mu_pos, float mu_neg, float gmu_pos,
+                                      float neg_gmu_neg)
 {
     float x = v.x, y = v.y, z = v.z, t = v.w;
     acc.x += apply1<MODE>(x, neg_mu_pos, mu_neg, gmu_pos, neg_gmu_neg);
     acc.y += apply1<MODE>(y, neg_mu_pos, mu_neg, gmu_pos, neg_gmu_neg);
     acc.z += apply1<MODE>(z, neg_mu_pos, mu_neg, gmu_pos, neg_gmu_neg);
     acc.w += apply1<MODE>(t, neg_mu_pos, mu_neg, gmu_pos, neg_gmu_neg);
-    v = vf4{x, y, z, t};
+    return vf4{x, y, z, t};
 }
 
-constexpr int kApplyUnrollP = 4;  // workers whose loads are issued together
-
-// grid = ceil(ceil(n/4) / kBlock) blocks; thread i owns float4 group i of every worker and of w.  The loop
-// over workers issues the g and e loads of kApplyUnrollP workers before using any of them.  The last block's
-// first n % 4 threads also take the scalar tail.
-template <int MODE, bool HAS_E, bool NT>
-__global__ __launch_bounds__(kBlock) void k_apply(const PtrTable tab, float *__restrict__ w, const uint64_t n,
-                                                  const uint32_t P, const float eta_over_P,
-                                                  const WsHeader *__restrict__ hdr)
+// A zero the compiler cannot see through, in a vector register.  Added to an index it turns a load with a
+// wavefront-uniform address into an ordinary vector load.  The apply pass wants that for the handful of means
+// it reads from the workspace: vector loads return in issue order and are counted apart from the scalar loads
+// of the kernel arguments, so when they are issued first they cost a freshly launched workgroup no wait of
+// their own, whereas a scalar load would be waited for together with the kernel-argument pointers before the
+// first big load could be issued.
+__device__ __forceinline__ uint32_t opaque_zero()
 {
-    __shared__ float s_neg_mu_pos[kMaxWorkers], s_mu_neg[kMaxWorkers];
-    const uint32_t tid = threadIdx.x;
-    if (tid < P) {
-        s_neg_mu_pos[tid] = -hdr->workers[tid].mu_pos;
-        s_mu_neg[tid] = hdr->workers[tid].mu_neg;
-    }
-    const float gmu_pos = hdr->gmu_pos, neg_gmu_neg = -hdr->gmu_neg;
-    __syncthreads();
+    uint32_t z;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+    return z;
+}
 
+// Body of the apply pass for one workgroup.  Thread t owns the float4 groups base + it * BLOCK (it < ITEMS) of
+// every worker and of w.  The g and e loads of UP workers x ITEMS groups are all issued before the first use:
+// the pass runs fastest with few wavefronts per compute unit, each with many loads in flight.  FULL = every
+// group of the workgroup is in range (all workgroups but the last).  lz is opaque_zero().
+template <int MODE, bool HAS_E, bool NT, int UP, int ITEMS, int BLOCK, bool FULL>
+__device__ __forceinline__ void apply_body(const PtrTable &tab, float *__restrict__ w, const uint64_t nvec,
+                                           const uint64_t base, const uint32_t P, const float eta_over_P,
+                                           const WsHeader *__restrict__ hdr, const uint32_t lz)
+{
+    vf4 *w4 = reinterpret_cast<vf4 *>(w);
+    const float *neg_mu_pos = hdr->neg_mu_pos + lz, *mu_neg = hdr->mu_neg + lz;
+    const float gmu_pos = (&hdr->gmu_pos)[lz];
+    const float neg_gmu_neg = -(&hdr->gmu_neg)[lz];
+    vf4 wv[ITEMS], acc[ITEMS];
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        acc[it] = vf4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (FULL || base + it * BLOCK < nvec)
+            wv[it] = ld4<NT>(w4 + base + it * BLOCK);
+    }
+    uint32_t p0 = 0;
+    for (; p0 + UP <= P; p0 += UP) {
+        vf4 v[UP * ITEMS], ev[UP * ITEMS];
+        float nmp[UP], mn[UP];
+#pragma unroll
+        for (int u = 0; u < UP; ++u) {
+            nmp[u] = neg_mu_pos[p0 + u];
+            mn[u] = mu_neg[p0 + u];
+        }
+#pragma unroll
+        for (int u = 0; u < UP; ++u) {
+            const vf4 *gp = reinterpret_cast<const vf4 *>(tab.g[p0 + u]);
+#pragma unroll
+            for (int it = 0; it < ITEMS; ++it)
+                if (FULL || base + it * BLOCK < nvec)
+                    v[u * ITEMS + it] = ld4<NT>(gp + base + it * BLOCK);
+        }
+        if (HAS_E) {
+#pragma unroll
+            for (int u = 0; u < UP; ++u) {
+                const vf4 *ep = reinterpret_cast<const vf4 *>(tab.e[p0 + u]);
+#pragma unroll
+                for (int it = 0; it < ITEMS; ++it)
+                    if (FULL || base + it * BLOCK < nvec)
+                        ev[u * ITEMS + it] = ld4<NT>(ep + base + it * BLOCK);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keep every load of the group ahead of the first use
+#pragma unroll
+        for (int u = 0; u < UP; ++u) {
+            vf4 *ep = reinterpret_cast<vf4 *>(tab.e[p0 + u]);
+#pragma unroll
+            for (int it = 0; it < ITEMS; ++it) {
+                if (FULL || base + it * BLOCK < nvec) {
+                    const vf4 vv = HAS_E ? v[u * ITEMS + it] + ev[u * ITEMS + it] : v[u * ITEMS + it];
+                    const vf4 err = apply4<MODE>(vv, acc[it], nmp[u], mn[u], gmu_pos, neg_gmu_neg);
+                    if (HAS_E)
+                        st4<NT>(ep + base + it * BLOCK, err);
+                }
+            }
+        }
+    }
+    for (; p0 < P; ++p0) {  // workers past the last full group of UP
+        const vf4 *gp = reinterpret_cast<const vf4 *>(tab.g[p0]);
+        vf4 *ep = reinterpret_cast<vf4 *>(tab.e[p0]);
+        const float nmp = neg_mu_pos[p0], mn = mu_neg[p0];
+        vf4 v[ITEMS], ev[ITEMS];
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it)
+            if (FULL || base + it * BLOCK < nvec) {
+                v[it] = ld4<NT>(gp + base + it * BLOCK);
+                if (HAS_E)
+                    ev[it] = ld4<NT>(ep + base + it * BLOCK);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it)
+            if (FULL || base + it * BLOCK < nvec) {
+                const vf4 vv = HAS_E ? v[it] + ev[it] : v[it];
+                const vf4 err = apply4<MODE>(vv, acc[it], nmp, mn, gmu_pos, neg_gmu_neg);
+                if (HAS_E)
+                    st4<NT>(ep + base + it * BLOCK, err);
+            }
+    }
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it)
+        if (FULL || base + it * BLOCK < nvec) {
+            const vf4 wn = wv[it] - eta_over_P * acc[it];
+            st4<NT>(w4 + base + it * BLOCK, wn);
+        }
+}
+
+// grid = ceil(ceil(n/4) / (BLOCK * ITEMS * SEQ)) workgroups, each launched once; a workgroup runs the body SEQ
+// times on consecutive spans of BLOCK * ITEMS float4 groups.  The kernel uses no LDS itself: the launcher
+// requests dynamic LDS only to cap how many workgroups share a compute unit.  The last workgroup's first
+// n % 4 threads also take the scalar tail.
+template <int MODE, bool HAS_E, bool NT, int UP, int ITEMS, int SEQ, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_apply(const PtrTable tab, float *__restrict__ w, const uint64_t n,
+                                                 const uint32_t P, const float eta_over_P,
+                                                 const WsHeader *__restrict__ hdr)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lz = opaque_zero();
     const uint64_t nvec = n >> 2;
-    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * kBlock + tid;
-    if (i < nvec) {
-        vf4 *w4 = reinterpret_cast<vf4 *>(w) + i;
-        const vf4 wv = ld4<NT>(w4);
-        vf4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-        uint32_t p0 = 0;
-        for (; p0 + kApplyUnrollP <= P; p0 += kApplyUnrollP) {
-            vf4 v[kApplyUnrollP], ev[kApplyUnrollP];
+    constexpr uint64_t kSpan = static_cast<uint64_t>(BLOCK) * ITEMS;
 #pragma unroll
-            for (int u = 0; u < kApplyUnrollP; ++u)
-                v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + i);
-            if (HAS_E) {
-#pragma unroll
-                for (int u = 0; u < kApplyUnrollP; ++u)
-                    ev[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0 + u]) + i);
-            }
-            __builtin_amdgcn_sched_barrier(0);  // keep every load of the group ahead of the first use
-#pragma unroll
-            for (int u = 0; u < kApplyUnrollP; ++u) {
-                if (HAS_E)
-                    v[u] += ev[u];
-                apply4<MODE>(v[u], acc, s_neg_mu_pos[p0 + u], s_mu_neg[p0 + u], gmu_pos, neg_gmu_neg);
-                if (HAS_E)
-                    st4<NT>(reinterpret_cast<vf4 *>(tab.e[p0 + u]) + i, v[u]);
-            }
-        }
-        for (; p0 < P; ++p0) {
-            vf4 v = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0]) + i);
-            if (HAS_E)
-                v += ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0]) + i);
-            apply4<MODE>(v, acc, s_neg_mu_pos[p0], s_mu_neg[p0], gmu_pos, neg_gmu_neg);
-            if (HAS_E)
-                st4<NT>(reinterpret_cast<vf4 *>(tab.e[p0]) + i, v);
-        }
-        st4<NT>(w4, wv - eta_over_P * acc);
+    for (int sq = 0; sq < SEQ; ++sq) {
+        const uint64_t first = (static_cast<uint64_t>(blockIdx.x) * SEQ + sq) * kSpan;
+        if (first + kSpan <= nvec)
+            apply_body<MODE, HAS_E, NT, UP, ITEMS, BLOCK, true>(tab, w, nvec, first + tid, P, eta_over_P, hdr, lz);
+        else if (first < nvec)
+            apply_body<MODE, HAS_E, NT, UP, ITEMS, BLOCK, false>(tab, w, nvec, first + tid, P, eta_over_P, hdr,
+                                                                 lz);
     }
     if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
         const uint64_t k = (nvec << 2) + tid;
+        const float gmu_pos = hdr->gmu_pos, neg_gmu_neg = -hdr->gmu_neg;
         float acc = 0.0f;
         for (uint32_t p = 0; p < P; ++p) {
             float v = tab.g[p][k];
             if (HAS_E)
                 v += tab.e[p][k];
-            acc += apply1<MODE>(v, s_neg_mu_pos[p], s_mu_neg[p], gmu_pos, neg_gmu_neg);
+            acc += apply1<MODE>(v, hdr->neg_mu_pos[p], hdr->mu_neg[p], gmu_pos, neg_gmu_neg);
             if (HAS_E)
                 tab.e[p][k] = v;
         }
         w[k] -= eta_over_P * acc;
     }
 }
+
+constexpr int kDenseUnrollP = 4;
 
 // Eq. 1 / Algorithm 1 lines 9-10: w <- w - eta * mean_p g^p.  Same thread-to-data mapping as k_apply.
 template <bool NT>
@@ -352,13 +433,13 @@ __global__ __launch_bounds__(kBlock) void k_dense_step(const PtrTable tab, float
         const vf4 wv = ld4<NT>(w4);
         vf4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
         uint32_t p0 = 0;
-        for (; p0 + kApplyUnrollP <= P; p0 += kApplyUnrollP) {
-            vf4 v[kApplyUnrollP];
+        for (; p0 + kDenseUnrollP <= P; p0 += kDenseUnrollP) {
+            vf4 v[kDenseUnrollP];
 #pragma unroll
-            for (int u = 0; u < kApplyUnrollP; ++u)
+            for (int u = 0; u < kDenseUnrollP; ++u)
                 v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + i);
 #pragma unroll
-            for (int u = 0; u < kApplyUnrollP; ++u)
+            for (int u = 0; u < kDenseUnrollP; ++u)
                 acc += v[u];
         }
         for (; p0 < P; ++p0)
@@ -435,23 +516,41 @@ hipError_t launch_global_average(const a2sgd_plan_t &pl, void *ws, hipStream_t s
     return hipGetLastError();
 }
 
-template <int MODE>
-static hipError_t launch_apply_mode(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eop,
-                                    const WsHeader *hdr, hipStream_t s)
+// One instantiation of the apply kernel.  lds_bytes of dynamic LDS are requested only to limit the workgroups
+// per compute unit (160 KiB of LDS per CU); 0 = no limit.
+template <int MODE, bool HAS_E, bool NT, int UP, int ITEMS, int SEQ, int BLOCK>
+hipError_t launch_apply_geom(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eop, const WsHeader *hdr,
+                             uint32_t lds_bytes, hipStream_t s)
 {
-    const dim3 grid(apply_grid(pl.n)), block(kBlock);
-    if (has_e) {
-        if (pl.streaming)
-            k_apply<MODE, true, true><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, hdr);
-        else
-            k_apply<MODE, true, false><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, hdr);
-    } else {
-        if (pl.streaming)
-            k_apply<MODE, false, true><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, hdr);
-        else
-            k_apply<MODE, false, false><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, hdr);
+    auto kern = k_apply<MODE, HAS_E, NT, UP, ITEMS, SEQ, BLOCK>;
+    if (lds_bytes > 64 * 1024) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
+        if (err != hipSuccess)
+            return err;
     }
+    const uint64_t nvec = (pl.n + 3) >> 2;  // the scalar tail rides in the last workgroup even when n < 4
+    const uint64_t per = static_cast<uint64_t>(BLOCK) * ITEMS * SEQ;
+    const dim3 grid(static_cast<uint32_t>((nvec + per - 1) / per)), block(BLOCK);
+    kern<<<grid, block, lds_bytes, s>>>(tab, w, pl.n, pl.P, eop, hdr);
     return hipGetLastError();
+}
+
+template <int MODE, bool HAS_E, bool NT>
+static hipError_t launch_apply_shape(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eop,
+                                     const WsHeader *hdr, hipStream_t s)
+{
+    const ApplyGeom &ge = pl.apply;
+    // single-wavefront workgroups; about 8 float4 loads of g and as many of e in flight per thread
+    if (ge.up == 8)
+        return launch_apply_geom<MODE, HAS_E, NT, 8, 1, 1, 64>(pl, tab, w, eop, hdr, ge.lds_bytes, s);
+    if (ge.up == 4)
+        return launch_apply_geom<MODE, HAS_E, NT, 4, 1, 1, 64>(pl, tab, w, eop, hdr, ge.lds_bytes, s);
+    if (ge.up == 2)
+        return launch_apply_geom<MODE, HAS_E, NT, 2, 2, 1, 64>(pl, tab, w, eop, hdr, ge.lds_bytes, s);
+    if (ge.up == 1)
+        return launch_apply_geom<MODE, HAS_E, NT, 1, 4, 1, 64>(pl, tab, w, eop, hdr, ge.lds_bytes, s);
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
@@ -459,9 +558,21 @@ hipError_t launch_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e,
 {
     const float eop = static_cast<float>(static_cast<double>(eta) / static_cast<double>(pl.P));
     const WsHeader *hdr = static_cast<const WsHeader *>(ws);
-    if (pl.mode == A2SGD_MODE_ALG1_LITERAL)
-        return launch_apply_mode<A2SGD_MODE_ALG1_LITERAL>(pl, tab, has_e, w, eop, hdr, s);
-    return launch_apply_mode<A2SGD_MODE_RETAINED_ERROR>(pl, tab, has_e, w, eop, hdr, s);
+    const bool lit = pl.mode == A2SGD_MODE_ALG1_LITERAL;
+#define A2SGD_APPLY_CASE(L, E, N)                                                                              \
+    if (lit == L && has_e == E && pl.streaming == N)                                                           \
+        return launch_apply_shape<L ? A2SGD_MODE_ALG1_LITERAL : A2SGD_MODE_RETAINED_ERROR, E, N>(pl, tab, w, eop, \
+                                                                                                 hdr, s);
+    A2SGD_APPLY_CASE(false, true, true)
+    A2SGD_APPLY_CASE(false, true, false)
+    A2SGD_APPLY_CASE(false, false, true)
+    A2SGD_APPLY_CASE(false, false, false)
+    A2SGD_APPLY_CASE(true, true, true)
+    A2SGD_APPLY_CASE(true, true, false)
+    A2SGD_APPLY_CASE(true, false, true)
+    A2SGD_APPLY_CASE(true, false, false)
+#undef A2SGD_APPLY_CASE
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, uint64_t *mask, hipStream_t s)

@@ -68,8 +68,8 @@ def test_plan_null_pointers(A):
 
 def test_plan_geometry(A):
     p = A.a2sgd_plan(1_500_000_000, 4)
-    assert A.a2sgd_plan_blocks_per_worker(p) == 512  # 256 CUs x 8 resident workgroups / 4 workers
-    assert A.a2sgd_workspace_bytes(p) == 4096 + 5 * 8 * 4 * 512
+    assert A.a2sgd_plan_blocks_per_worker(p) == 128  # 256 CUs x 2 resident workgroups / 4 workers
+    assert A.a2sgd_workspace_bytes(p) == 4096 + 5 * 8 * 4 * 128
     p = A.a2sgd_plan(5, 3)
     assert A.a2sgd_plan_blocks_per_worker(p) == 1
     p = A.a2sgd_plan(1000, 2, blocks_per_worker=7)
