@@ -23,9 +23,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 
-# HBM bytes per launch of the apply kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
-# same counters' reading of a plain copy kernel; filled in from the summaries under profiles/.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch of the apply kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, each scaled by the
+# same counter's reading of a plain copy of known size (profiles/a2sgd_step_config5_hbm_counters.txt).
+MEASURED_TRAFFIC_BYTES = {"config5": 8.40001e10}
 
 
 def main() -> int:
@@ -36,6 +36,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--blocks-per-worker", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain copy of n floats (for scaling rocprofv3 HBM counters)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28, help="parameters in the CPU-baseline sample")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -51,9 +53,13 @@ def main() -> int:
     torch.cuda.set_device(0)
     wl = workloads.FULL[args.config]()
     n, P = wl.n, wl.num_workers
-    g = [wl.gradient(p, 0, device="cuda") for p in range(P)]
-    e = [wl.initial_error(p, device="cuda") for p in range(P)]
-    w = wl.weights(device="cuda")
+    # the big buffers are allocated before anything else touches the device heap, then filled in place
+    g = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(P)]
+    e = [torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(P)]  # every workload starts from e = 0
+    w = torch.empty(n, dtype=torch.float32, device="cuda")
+    for p in range(P):
+        wl.gradient(p, 0, out=g[p])
+    wl.weights(out=w)
     plan = A.a2sgd_plan(n, P, A.A2SGD_MODE_RETAINED_ERROR, args.blocks_per_worker)
     ws = A.alloc_workspace(plan)
 
@@ -69,6 +75,13 @@ def main() -> int:
         A.a2sgd_apply_and_update_error(plan, g, e, w, wl.eta, ws)
         if ev is not None:
             ev[3].record()
+
+    if args.calibration_copy:
+        # a plain device-to-device copy of known size (4n bytes read, 4n written), for scaling HBM counters
+        scratch = torch.empty_like(w)
+        scratch.copy_(w)
+        torch.cuda.synchronize()
+        del scratch
 
     for _ in range(args.warmup):
         step()
