@@ -1,0 +1,57 @@
+"""CPU-only checks of what hipcc generated for gfx950 (cross-compiled here, no GPU needed): the properties the
+performance of the streaming kernels rests on, which the optimiser has been seen to drop silently."""
+import os
+import re
+import subprocess
+import tempfile
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def asm():
+    from paper_2006_07405_amd import build as B
+    flags = [f for f in B.FLAGS if f not in ("-shared", "-fPIC")]
+    with tempfile.TemporaryDirectory() as d:
+        out = os.path.join(d, "k.s")
+        subprocess.check_call(["/opt/rocm/bin/hipcc"] + flags + ["--cuda-device-only", "-S", "-o", out, B.SOURCES[0]],
+                              stderr=subprocess.DEVNULL)
+        text = open(out).read()
+    kernels = {}
+    for m in re.finditer(r"^(_ZN5a2sgd\w+):.*?s_endpgm", text, flags=re.S | re.M):
+        kernels[m.group(1)] = m.group(0)
+    assert kernels
+    return text, kernels
+
+
+def test_no_scratch_and_no_packed_fp32(asm):
+    text, kernels = asm
+    sizes = re.findall(r"\.private_segment_fixed_size:\s*(\d+)", text)
+    assert sizes and all(s == "0" for s in sizes), "a kernel spills to scratch memory"
+    assert not re.search(r"v_pk_(add|mul|fma)_f32", text)
+
+
+def test_streaming_apply_stores_are_all_non_temporal(asm):
+    _, kernels = asm
+    # k_apply<MODE, HAS_E, NT, ...>: Lb1 in third place marks the streaming instantiations
+    streaming = {k: v for k, v in kernels.items() if re.match(r"_ZN5a2sgd7k_applyILi[01]ELb[01]ELb1E", k)}
+    assert len(streaming) >= 16
+    for name, body in streaming.items():
+        stores = re.findall(r"global_store_dwordx4[^\n]*", body)
+        assert stores, name
+        bad = [s for s in stores if not s.rstrip().endswith(" nt")]
+        assert not bad, f"{name}: {len(bad)} of {len(stores)} 128-bit stores lost the non-temporal hint"
+
+
+def test_streaming_reduction_loads_are_non_temporal_and_batched(asm):
+    _, kernels = asm
+    name = next(k for k in kernels if re.match(r"_ZN5a2sgd16k_local_partialsILb1ELb1E", k))
+    body = kernels[name]
+    loads = re.findall(r"global_load_dwordx4[^\n]*", body)
+    assert len(loads) >= 8 and all(l.rstrip().endswith(" nt") for l in loads)
+    # in the main loop the eight loads of a tile are issued before the first wait on any of them
+    loop = body[body.index("global_load_dwordx4"):]
+    first_wait = loop.index("s_waitcnt vmcnt")
+    assert loop[:first_wait].count("global_load_dwordx4") >= 8
