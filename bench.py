@@ -35,7 +35,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--blocks-per-worker", type=int, default=0)
+    ap.add_argument("--n", type=int, default=0, help="override n (config 1 only: one flat tensor)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--single-call", action="store_true",
+                    help="time a2sgd_step (one call per step; a single cooperative launch when the model fits the "
+                         "caches) instead of the three calls with events between them")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain copy of n floats (for scaling rocprofv3 HBM counters)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28, help="parameters in the CPU-baseline sample")
@@ -52,6 +56,9 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     wl = workloads.FULL[args.config]()
+    if args.n:
+        assert args.config == 1, "--n applies to the flat workload of config 1"
+        wl = workloads.config1(n=args.n)
     n, P = wl.n, wl.num_workers
     # the big buffers are allocated before anything else touches the device heap, then filled in place
     g = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(P)]
@@ -64,6 +71,9 @@ def main() -> int:
     ws = A.alloc_workspace(plan)
 
     def step(ev=None):
+        if args.single_call:
+            A.a2sgd_step(plan, g, e, w, wl.eta, ws)
+            return
         if ev is not None:
             ev[0].record()
         A.a2sgd_local_averages(plan, g, e, ws)
@@ -94,12 +104,17 @@ def main() -> int:
     t1 = time.perf_counter()
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    ms_reduce = sum(ev[0].elapsed_time(ev[1]) for ev in events) / args.steps
-    ms_global = sum(ev[1].elapsed_time(ev[2]) for ev in events) / args.steps
-    ms_apply = sum(ev[2].elapsed_time(ev[3]) for ev in events) / args.steps
     bytes_reduce = 8 * n * P
     bytes_apply = 12 * n * P + 8 * n
     bytes_step = bytes_reduce + bytes_apply
+    if args.single_call:  # no events inside the step: the roofline entry is the whole step
+        ms_reduce = ms_global = None
+        ms_apply = ms_per_step
+        bytes_apply = bytes_step
+    else:
+        ms_reduce = sum(ev[0].elapsed_time(ev[1]) for ev in events) / args.steps
+        ms_global = sum(ev[1].elapsed_time(ev[2]) for ev in events) / args.steps
+        ms_apply = sum(ev[2].elapsed_time(ev[3]) for ev in events) / args.steps
     achieved = bytes_apply / (ms_apply * 1e-3) / 1e9
     stats, gmu = A.a2sgd_read_stats(plan, ws)
 
@@ -122,11 +137,12 @@ def main() -> int:
         "step_hbm_gbps": bytes_step / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "kernels_ms": {"local_averages": ms_reduce, "global_average": ms_global, "apply_and_update_error": ms_apply},
-        "local_averages_gbps": bytes_reduce / (ms_reduce * 1e-3) / 1e9,
-        "roofline": {"kernel": "k_apply (a2sgd_apply_and_update_error)", "bound": "hbm", "achieved": achieved,
+        "local_averages_gbps": None if ms_reduce is None else bytes_reduce / (ms_reduce * 1e-3) / 1e9,
+        "roofline": {"kernel": "a2sgd_step (one call)" if args.single_call else "k_apply (a2sgd_apply_and_update_error)",
+                     "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "algorithmic_bytes_per_launch": bytes_apply,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(f"config{args.config}")},
+                     "traffic": None if args.single_call else MEASURED_TRAFFIC_BYTES.get(f"config{args.config}")},
         "result_check": {"gmu_pos": gmu[0], "gmu_neg": gmu[1], "n_pos_worker0": stats[0].n_pos},
     }
 

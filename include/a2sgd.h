@@ -112,7 +112,14 @@ a2sgd_status_t a2sgd_global_average(const a2sgd_plan_t *plan, void *workspace, a
 a2sgd_status_t a2sgd_apply_and_update_error(const a2sgd_plan_t *plan, const float *const *g, float *const *e,
                                             float *w, float eta, void *workspace, a2sgd_stream_t stream);
 
-/* The three calls above, in order, on one stream: one whole step of Algorithm 1's loop body (lines 3-7). */
+/* One whole step of Algorithm 1's loop body (lines 3-7) on one stream: the same result as the three calls above
+ * in order (to the tolerance of the sums' grouping: the counts are identical, the fp64 sums are combined in
+ * another fixed order).  When g, e and w together are small enough to stay in the on-chip caches (below 192 MiB)
+ * the step is ONE kernel launch with a grid-wide barrier inside; larger models run the three passes.  The
+ * barrier's cell is library-owned device memory, one of 64 cells handed out to plans in turn: calls with the
+ * same plan must not overlap (they share the workspace anyway), and at most 64 plans may have a step in flight
+ * on one GPU at once.  The barrier's wait is bounded; should it ever run out, the step's outputs are invalid,
+ * a2sgd_read_stats returns A2SGD_ERR_DEVICE, and that cell refuses further steps. */
 a2sgd_status_t a2sgd_step(const a2sgd_plan_t *plan, const float *const *g, float *const *e, float *w, float eta,
                           void *workspace, a2sgd_stream_t stream);
 

@@ -1,5 +1,6 @@
 // Host side of the C ABI declared in include/a2sgd.h: plan construction, argument validation, and the
 // sequencing of the kernels of one step.  No device memory is allocated here.
+#include <atomic>
 #include <new>
 
 #include "a2sgd_internal.h"
@@ -14,6 +15,7 @@ constexpr uint64_t kMaxN = 1ull << 40;
 // that is open at once and HBM efficiency drops.  The reduction keeps 2 workgroups of 256 threads per CU.
 constexpr uint32_t kComputeUnits = 256;
 constexpr uint32_t kReduceBlocksPerCU = 2;
+constexpr uint32_t kFusedGridMax = 256;
 
 // The apply pass runs single-wavefront workgroups and caps how many share a CU through its dynamic-LDS request
 // (160 KiB per CU; the request sits in the middle of the range that yields the wanted count).  A wavefront
@@ -29,6 +31,9 @@ uint32_t apply_lds_bytes(uint32_t P)
 // Above this many bytes of g + e + w the step cannot live in the 256 MiB last-level cache between its two
 // passes, and every load and store is issued as non-temporal.
 constexpr uint64_t kStreamingBytes = 192ull << 20;
+
+std::atomic<uint32_t> g_next_slot{0};
+std::atomic<uint32_t> g_next_token{1};
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -116,7 +121,17 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
     pl->streaming = (2ull * pl->P + 1) * 4ull * pl->n > kStreamingBytes;
     pl->apply.up = pl->P >= 8 ? 8 : pl->P >= 4 ? 4 : pl->P >= 2 ? 2 : 1;
     pl->apply.lds_bytes = pl->streaming ? apply_lds_bytes(pl->P) : 0;
-    pl->workspace_bytes = kHeaderBytes + 5ull * 8ull * pl->P * pl->B;
+    // Single-launch step while everything fits the caches: one workgroup of kFusedBlock threads per 4096
+    // elements, at most one per two CUs, all resident at once (the kernel's grid-wide barrier relies on that).
+    pl->barrier_slot = g_next_slot.fetch_add(1) % kBarrierSlots;
+    pl->last_token = 0;
+    pl->fused_grid = 0;
+    if (!pl->streaming) {
+        const uint64_t want = (pl->n + 4 * kFusedBlock - 1) / (4 * kFusedBlock);
+        pl->fused_grid = static_cast<uint32_t>(want < kFusedGridMax ? want : kFusedGridMax);
+    }
+    const uint32_t rows = pl->B > pl->fused_grid ? pl->B : pl->fused_grid;
+    pl->workspace_bytes = kHeaderBytes + 5ull * 8ull * pl->P * rows;
     *out_plan = pl;
     return A2SGD_OK;
 }
@@ -142,6 +157,7 @@ a2sgd_status_t a2sgd_local_averages(const a2sgd_plan_t *plan, const float *const
         return st;
     PtrTable tab;
     fill_table(tab, plan->P, g, has_e ? e : nullptr);
+    plan->last_token = 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if ((st = dev(launch_local_partials(*plan, tab, has_e, workspace, s))) != A2SGD_OK)
         return st;
@@ -186,6 +202,15 @@ a2sgd_status_t a2sgd_step(const a2sgd_plan_t *plan, const float *const *g, float
         return st;
     if ((st = check_buffer(workspace)) != A2SGD_OK)
         return st;
+    if (plan->fused_grid != 0) {
+        PtrTable tab;
+        fill_table(tab, plan->P, g, has_e ? e : nullptr);
+        uint32_t token = g_next_token.fetch_add(1);
+        if (token == 0)
+            token = g_next_token.fetch_add(1);
+        plan->last_token = token;
+        return dev(launch_fused_step(*plan, tab, has_e, w, eta, workspace, token, static_cast<hipStream_t>(stream)));
+    }
     if ((st = a2sgd_local_averages(plan, g, e, workspace, stream)) != A2SGD_OK)
         return st;
     if ((st = a2sgd_global_average(plan, workspace, stream)) != A2SGD_OK)
@@ -204,6 +229,8 @@ a2sgd_status_t a2sgd_read_stats(const a2sgd_plan_t *plan, const void *workspace,
         return A2SGD_ERR_DEVICE;
     if (hipStreamSynchronize(s) != hipSuccess)
         return A2SGD_ERR_DEVICE;
+    if (plan->last_token != 0 && hdr.failed_token == plan->last_token)
+        return A2SGD_ERR_DEVICE;  // the last single-launch step gave up at its grid barrier; outputs are invalid
     if (out_workers)
         for (uint32_t p = 0; p < plan->P; ++p)
             out_workers[p] = hdr.workers[p];

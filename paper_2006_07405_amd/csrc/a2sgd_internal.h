@@ -14,6 +14,8 @@ constexpr uint32_t kMaxWorkers = A2SGD_MAX_WORKERS;
 constexpr int kBlock = 256;           // threads per workgroup: 4 wavefronts of 64
 constexpr int kReduceUnroll = 4;      // float4 loads per array per thread per tile in the reduction
 constexpr uint32_t kMaxBlocksPerWorker = 65536;
+constexpr int kFusedBlock = 512;       // threads per workgroup of the single-launch step
+constexpr uint32_t kBarrierSlots = 64;  // grid-barrier cells of the single-launch step, one per plan (mod 64)
 
 // Device workspace, in this order:
 //   WsHeader                                   (kHeaderBytes, padded)
@@ -22,7 +24,8 @@ constexpr uint32_t kMaxBlocksPerWorker = 65536;
 //   uint64_t n_pos [P][B], n_neg [P][B], n_zero [P][B]
 struct WsHeader {
     float gmu_pos, gmu_neg;  // Algorithm 1 line 5
-    uint32_t pad[2];
+    uint32_t failed_token;   // set to the launch's token by a single-launch step that could not complete
+    uint32_t pad;
     a2sgd_worker_stats_t workers[kMaxWorkers];  // Algorithm 1 line 3, per worker
     float neg_mu_pos[kMaxWorkers];  // -mu_pos and mu_neg of every worker again, packed for the apply pass
     float mu_neg[kMaxWorkers];
@@ -73,6 +76,9 @@ struct a2sgd_plan {
     uint32_t B;           // blocks per worker in the first-level reduction
     bool streaming;       // footprint exceeds the on-chip caches: use non-temporal loads and stores
     a2sgd::ApplyGeom apply;
+    uint32_t fused_grid;  // workgroups of the single-launch step; 0 = a2sgd_step runs the three passes
+    uint32_t barrier_slot;
+    mutable uint32_t last_token;  // token of the last single-launch step enqueued with this plan; 0 = none
     size_t workspace_bytes;
 };
 
@@ -84,6 +90,8 @@ hipError_t launch_local_finalize(const a2sgd_plan_t &pl, void *ws, hipStream_t s
 hipError_t launch_global_average(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
 hipError_t launch_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
                         hipStream_t s);
+hipError_t launch_fused_step(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
+                             uint32_t token, hipStream_t s);
 hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, uint64_t *mask, hipStream_t s);
 hipError_t launch_dense_step(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eta, hipStream_t s);
 

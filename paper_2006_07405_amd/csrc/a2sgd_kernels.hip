@@ -291,16 +291,15 @@ __device__ __forceinline__ uint32_t opaque_zero()
 // Body of the apply pass for one workgroup.  Thread t owns the float4 groups base + it * BLOCK (it < ITEMS) of
 // every worker and of w.  The g and e loads of UP workers x ITEMS groups are all issued before the first use:
 // the pass runs fastest with few wavefronts per compute unit, each with many loads in flight.  FULL = every
-// group of the workgroup is in range (all workgroups but the last).  lz is opaque_zero().
+// group of the workgroup is in range (all workgroups but the last).  neg_mu_pos[p] = -mu_pos of worker p and
+// mu_neg[p] are read where the caller keeps them (the workspace header, or LDS in the single-launch step).
 template <int MODE, bool HAS_E, bool NT, int UP, int ITEMS, int BLOCK, bool FULL>
 __device__ __forceinline__ void apply_body(const PtrTable &tab, float *__restrict__ w, const uint64_t nvec,
                                            const uint64_t base, const uint32_t P, const float eta_over_P,
-                                           const WsHeader *__restrict__ hdr, const uint32_t lz)
+                                           const float *neg_mu_pos, const float *mu_neg, const float gmu_pos,
+                                           const float neg_gmu_neg)
 {
     vf4 *w4 = reinterpret_cast<vf4 *>(w);
-    const float *neg_mu_pos = hdr->neg_mu_pos + lz, *mu_neg = hdr->mu_neg + lz;
-    const float gmu_pos = (&hdr->gmu_pos)[lz];
-    const float neg_gmu_neg = -(&hdr->gmu_neg)[lz];
     vf4 wv[ITEMS], acc[ITEMS];
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
@@ -391,20 +390,23 @@ __global__ __launch_bounds__(BLOCK) void k_apply(const PtrTable tab, float *__re
 {
     const uint32_t tid = threadIdx.x;
     const uint32_t lz = opaque_zero();
+    const float *neg_mu_pos = hdr->neg_mu_pos + lz, *mu_neg = hdr->mu_neg + lz;
+    const float gmu_pos = (&hdr->gmu_pos)[lz];  // vector loads, issued ahead of the big ones
+    const float neg_gmu_neg = -(&hdr->gmu_neg)[lz];
     const uint64_t nvec = n >> 2;
     constexpr uint64_t kSpan = static_cast<uint64_t>(BLOCK) * ITEMS;
 #pragma unroll
     for (int sq = 0; sq < SEQ; ++sq) {
         const uint64_t first = (static_cast<uint64_t>(blockIdx.x) * SEQ + sq) * kSpan;
         if (first + kSpan <= nvec)
-            apply_body<MODE, HAS_E, NT, UP, ITEMS, BLOCK, true>(tab, w, nvec, first + tid, P, eta_over_P, hdr, lz);
+            apply_body<MODE, HAS_E, NT, UP, ITEMS, BLOCK, true>(tab, w, nvec, first + tid, P, eta_over_P, neg_mu_pos,
+                                                                mu_neg, gmu_pos, neg_gmu_neg);
         else if (first < nvec)
-            apply_body<MODE, HAS_E, NT, UP, ITEMS, BLOCK, false>(tab, w, nvec, first + tid, P, eta_over_P, hdr,
-                                                                 lz);
+            apply_body<MODE, HAS_E, NT, UP, ITEMS, BLOCK, false>(tab, w, nvec, first + tid, P, eta_over_P, neg_mu_pos,
+                                                                 mu_neg, gmu_pos, neg_gmu_neg);
     }
     if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
         const uint64_t k = (nvec << 2) + tid;
-        const float gmu_pos = hdr->gmu_pos, neg_gmu_neg = -hdr->gmu_neg;
         float acc = 0.0f;
         for (uint32_t p = 0; p < P; ++p) {
             float v = tab.g[p][k];
@@ -415,6 +417,264 @@ __global__ __launch_bounds__(BLOCK) void k_apply(const PtrTable tab, float *__re
                 tab.e[p][k] = v;
         }
         w[k] -= eta_over_P * acc;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Single-launch step for models whose g, e and w fit the on-chip caches (Algorithm 1 lines 3-7 in one kernel)
+// ---------------------------------------------------------------------------------------------------------
+
+// Grid-wide barrier for the single-launch step.  The cells live in device memory that the loader zeroes, one
+// per plan slot, so neither the caller nor the plan has to allocate or initialise anything.  It is a
+// sense-reversing barrier: the last workgroup to arrive clears the arrival count and advances the generation,
+// which leaves the cell ready for the next launch.  It is only used with grids that are resident all at once
+// (at most 2 workgroups of 256 threads per compute unit), so every arrival is certain; the wait is bounded all
+// the same, and a wait that runs out marks the cell as failed for good: later launches on it exit at once and
+// report through the workspace header instead of computing on a cell whose count can no longer be trusted.
+struct GridBarrier {
+    uint32_t arrive, generation, failed, pad;
+};
+static __device__ GridBarrier g_barriers[kBarrierSlots];
+constexpr uint32_t kBarrierSpinLimit = 1u << 21;  // polls of about a microsecond each
+
+// Device-scope relaxed atomic accessors.  They go to the memory side of the chip, past the XCD's own L2, which
+// is what lets workgroups on different XCDs exchange a few words without flushing or invalidating that cache.
+template <class T>
+__device__ __forceinline__ void store_device(T *p, T v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <class T>
+__device__ __forceinline__ T load_device(const T *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Waits until every vector-memory operation of this wavefront, stores included, has been acknowledged
+// (s_waitcnt with vmcnt = 0 and the other counters left at their maxima, gfx9 encoding).
+__device__ __forceinline__ void wait_vector_memory()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+}
+
+// Called by every thread of every workgroup.  Returns false if the wait ran out (or the cell is marked failed).
+// Only thread 0 talks to the cell.  Everything that crosses this barrier (the partial records) is written with
+// store_device and read with load_device, so no cache-wide fence is needed: a device-scope fence on this chip
+// writes back or invalidates the XCD's whole L2, which costs tens of microseconds when every workgroup does
+// it.  What is needed is order: every wavefront waits for its record stores to be acknowledged before its
+// workgroup arrives, and the records are read only after the generation was seen to move.
+__device__ __forceinline__ bool grid_barrier(GridBarrier *bar, const uint32_t G)
+{
+    __shared__ uint32_t s_ok;
+    wait_vector_memory();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t ok = 1;
+        const uint32_t gen = load_device(&bar->generation);
+        const uint32_t old = __hip_atomic_fetch_add(&bar->arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old == G - 1) {
+            store_device(&bar->arrive, 0u);
+            wait_vector_memory();  // the reset has landed before anyone is released
+            __hip_atomic_fetch_add(&bar->generation, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            uint32_t polls = 0;
+            while (load_device(&bar->generation) == gen) {
+                if (++polls > kBarrierSpinLimit) {
+                    store_device(&bar->failed, 1u);
+                    ok = 0;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+        }
+        s_ok = ok;
+    }
+    __syncthreads();
+    return s_ok != 0;
+}
+
+constexpr int kFusedUnroll = 4;  // float4 groups per thread per loop trip in the reduction phase
+// kFusedBlock threads per workgroup (a2sgd_internal.h): large workgroups keep the number of partial records,
+// which every workgroup reads back from the memory side after the barrier, small.
+
+// grid = G workgroups, few enough to be resident all at once.  Workgroup b owns one contiguous slice of the
+// float4 groups of every worker and of w in BOTH phases, so what it read for the sums is what it re-reads for
+// the update, from the L2 of its own XCD.  Phase 1 writes one partial record per (worker, workgroup); after the
+// grid-wide barrier every workgroup combines the G records of each worker in the same fixed order, so all of
+// them hold bit-identical means without a second barrier; phase 3 is the apply pass on the slice.  Workgroup 0
+// also writes the header that a2sgd_read_stats reads.  The last n % 4 elements belong to the last workgroup.
+template <int MODE, bool HAS_E, int UP>
+__global__ __launch_bounds__(kFusedBlock) void k_fused_step(const PtrTable tab, float *__restrict__ w, const uint64_t n,
+                                                       const uint32_t P, const float eta_over_P, const Partials part,
+                                                       WsHeader *__restrict__ hdr, const uint32_t slot,
+                                                       const uint32_t token)
+{
+    GridBarrier *bar = &g_barriers[slot];
+    __shared__ uint32_t s_cell_failed;
+    if (threadIdx.x == 0)
+        s_cell_failed = __hip_atomic_load(&bar->failed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s_cell_failed != 0) {  // the same for every thread of the workgroup
+        if (threadIdx.x == 0)
+            hdr->failed_token = token;
+        return;
+    }
+    __shared__ double sh_pos[kMaxWorkers][kFusedBlock / 64], sh_neg[kMaxWorkers][kFusedBlock / 64];
+    __shared__ uint64_t sh_cp[kMaxWorkers][kFusedBlock / 64], sh_cn[kMaxWorkers][kFusedBlock / 64],
+        sh_cz[kMaxWorkers][kFusedBlock / 64];
+    __shared__ float s_neg_mu_pos[kMaxWorkers], s_mu_neg[kMaxWorkers], s_gmu[2];
+
+    const uint32_t G = gridDim.x, b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint64_t nvec = n >> 2;
+    const uint64_t q = nvec / G, r = nvec % G;
+    const uint64_t lo = b * q + (b < r ? b : r), hi = lo + q + (b < r ? 1 : 0);
+    const bool owns_tail = (b == G - 1) && tid < (n & 3);
+    const uint64_t tail = (nvec << 2) + tid;
+
+    // ---- phase 1: sums and counts of this slice, per worker
+    for (uint32_t p = 0; p < P; ++p) {
+        const float *__restrict__ g = tab.g[p];
+        const float *__restrict__ e = HAS_E ? tab.e[p] : nullptr;
+        const vf4 *g4 = reinterpret_cast<const vf4 *>(g), *e4 = reinterpret_cast<const vf4 *>(e);
+        LaneAcc acc;
+        for (uint64_t i0 = lo + tid; i0 < hi; i0 += static_cast<uint64_t>(kFusedBlock) * kFusedUnroll) {
+            vf4 gv[kFusedUnroll], ev[kFusedUnroll];
+#pragma unroll
+            for (int u = 0; u < kFusedUnroll; ++u)
+                if (i0 + u * kFusedBlock < hi) {
+                    gv[u] = g4[i0 + u * kFusedBlock];
+                    if (HAS_E)
+                        ev[u] = e4[i0 + u * kFusedBlock];
+                }
+#pragma unroll
+            for (int u = 0; u < kFusedUnroll; ++u)
+                if (i0 + u * kFusedBlock < hi)
+                    acc.add4(HAS_E ? gv[u] + ev[u] : gv[u]);
+            acc.flush();
+        }
+        if (owns_tail) {
+            acc.add(HAS_E ? g[tail] + e[tail] : g[tail]);
+            acc.flush();
+        }
+        const double wp = wave_sum(acc.s_pos), wn = wave_sum(acc.s_neg);
+        // the counts are wavefront totals held by the lanes that were active; lane 0 is active whenever any is
+        if (lane == 0) {
+            sh_pos[p][wave] = wp;
+            sh_neg[p][wave] = wn;
+            sh_cp[p][wave] = acc.c_pos;
+            sh_cn[p][wave] = acc.c_neg;
+            sh_cz[p][wave] = acc.c_zero;
+        }
+    }
+    __syncthreads();
+    if (tid < P) {
+        double sp = 0.0, sn = 0.0;
+        uint64_t cp = 0, cn = 0, cz = 0;
+#pragma unroll
+        for (int k = 0; k < kFusedBlock / 64; ++k) {
+            sp += sh_pos[tid][k];
+            sn += sh_neg[tid][k];
+            cp += sh_cp[tid][k];
+            cn += sh_cn[tid][k];
+            cz += sh_cz[tid][k];
+        }
+        const size_t slot = static_cast<size_t>(tid) * G + b;
+        store_device(part.s_pos + slot, sp);
+        store_device(part.s_neg + slot, sn);
+        store_device(part.n_pos + slot, cp);
+        store_device(part.n_neg + slot, cn);
+        store_device(part.n_zero + slot, cz);
+    }
+    if (!grid_barrier(bar, G)) {  // uniform per workgroup
+        if (tid == 0)
+            hdr->failed_token = token;
+        return;
+    }
+
+    // ---- phase 2: every workgroup combines the G records of each worker, all in the same order
+    for (uint32_t p = 0; p < P; ++p) {
+        const size_t row = static_cast<size_t>(p) * G;
+        double sp = 0.0, sn = 0.0;
+        uint64_t cp = 0, cn = 0, cz = 0;
+        for (uint32_t j = tid; j < G; j += kFusedBlock) {
+            sp += load_device(part.s_pos + row + j);
+            sn += load_device(part.s_neg + row + j);
+            cp += load_device(part.n_pos + row + j);
+            cn += load_device(part.n_neg + row + j);
+            cz += load_device(part.n_zero + row + j);
+        }
+        sp = wave_sum(sp);
+        sn = wave_sum(sn);
+        cp = wave_sum(cp);
+        cn = wave_sum(cn);
+        cz = wave_sum(cz);
+        if (lane == 0) {
+            sh_pos[p][wave] = sp;
+            sh_neg[p][wave] = sn;
+            sh_cp[p][wave] = cp;
+            sh_cn[p][wave] = cn;
+            sh_cz[p][wave] = cz;
+        }
+    }
+    __syncthreads();
+    if (tid < P) {
+        double tp = 0.0, tn = 0.0;
+        uint64_t np = 0, nn = 0, nz = 0;
+#pragma unroll
+        for (int k = 0; k < kFusedBlock / 64; ++k) {
+            tp += sh_pos[tid][k];
+            tn += sh_neg[tid][k];
+            np += sh_cp[tid][k];
+            nn += sh_cn[tid][k];
+            nz += sh_cz[tid][k];
+        }
+        a2sgd_worker_stats_t st;
+        st.mu_pos = np ? static_cast<float>(tp / static_cast<double>(np)) : 0.0f;
+        st.mu_neg = nn ? static_cast<float>(tn / static_cast<double>(nn)) : 0.0f;
+        st.n_pos = np;
+        st.n_neg = nn;
+        st.n_zero = nz;
+        st.n_nan = n - np - nn;
+        s_neg_mu_pos[tid] = -st.mu_pos;
+        s_mu_neg[tid] = st.mu_neg;
+        if (b == 0) {
+            hdr->workers[tid] = st;
+            hdr->neg_mu_pos[tid] = -st.mu_pos;
+            hdr->mu_neg[tid] = st.mu_neg;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {  // Algorithm 1 line 5
+        double sp = 0.0, sn = 0.0;
+        for (uint32_t p = 0; p < P; ++p) {
+            sp -= static_cast<double>(s_neg_mu_pos[p]);
+            sn += static_cast<double>(s_mu_neg[p]);
+        }
+        s_gmu[0] = static_cast<float>(sp / static_cast<double>(P));
+        s_gmu[1] = static_cast<float>(sn / static_cast<double>(P));
+        if (b == 0) {
+            hdr->gmu_pos = s_gmu[0];
+            hdr->gmu_neg = s_gmu[1];
+        }
+    }
+    __syncthreads();
+    const float gmu_pos = s_gmu[0], neg_gmu_neg = -s_gmu[1];
+
+    // ---- phase 3: error write-back and weight update on the same slice (bounds: hi instead of nvec)
+    for (uint64_t i = lo + tid; i < hi; i += 2 * kFusedBlock)
+        apply_body<MODE, HAS_E, false, UP, 2, kFusedBlock, false>(tab, w, hi, i, P, eta_over_P, s_neg_mu_pos, s_mu_neg,
+                                                             gmu_pos, neg_gmu_neg);
+    if (owns_tail) {
+        float acc = 0.0f;
+        for (uint32_t p = 0; p < P; ++p) {
+            float v = tab.g[p][tail];
+            if (HAS_E)
+                v += tab.e[p][tail];
+            acc += apply1<MODE>(v, s_neg_mu_pos[p], s_mu_neg[p], gmu_pos, neg_gmu_neg);
+            if (HAS_E)
+                tab.e[p][tail] = v;
+        }
+        w[tail] -= eta_over_P * acc;
     }
 }
 
@@ -573,6 +833,33 @@ hipError_t launch_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e,
     A2SGD_APPLY_CASE(true, false, false)
 #undef A2SGD_APPLY_CASE
     return hipErrorInvalidValue;
+}
+
+template <int MODE, bool HAS_E>
+static hipError_t launch_fused_inst(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eop, void *ws,
+                                    uint32_t token, hipStream_t s)
+{
+    const dim3 grid(pl.fused_grid), block(kFusedBlock);
+    const Partials part = partials_of(ws, pl.P, pl.fused_grid);
+    WsHeader *hdr = static_cast<WsHeader *>(ws);
+    switch (pl.apply.up) {
+    case 8: k_fused_step<MODE, HAS_E, 8><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, pl.barrier_slot, token); break;
+    case 4: k_fused_step<MODE, HAS_E, 4><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, pl.barrier_slot, token); break;
+    case 2: k_fused_step<MODE, HAS_E, 2><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, pl.barrier_slot, token); break;
+    default: k_fused_step<MODE, HAS_E, 1><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, pl.barrier_slot, token); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_fused_step(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
+                             uint32_t token, hipStream_t s)
+{
+    const float eop = static_cast<float>(static_cast<double>(eta) / static_cast<double>(pl.P));
+    if (pl.mode == A2SGD_MODE_ALG1_LITERAL)
+        return has_e ? launch_fused_inst<A2SGD_MODE_ALG1_LITERAL, true>(pl, tab, w, eop, ws, token, s)
+                     : launch_fused_inst<A2SGD_MODE_ALG1_LITERAL, false>(pl, tab, w, eop, ws, token, s);
+    return has_e ? launch_fused_inst<A2SGD_MODE_RETAINED_ERROR, true>(pl, tab, w, eop, ws, token, s)
+                 : launch_fused_inst<A2SGD_MODE_RETAINED_ERROR, false>(pl, tab, w, eop, ws, token, s);
 }
 
 hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, uint64_t *mask, hipStream_t s)

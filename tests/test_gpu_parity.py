@@ -60,6 +60,30 @@ def test_worker_counts(A, P):
     check_against_oracle(A, g, e, w, 0.05, 1, split_calls=False)
 
 
+@pytest.mark.parametrize("n", [1, 3, 4, 5, 255, 1023, 1024, 1025, 4099, 65_539, 524_288, 1_048_577, 3_000_001])
+def test_single_launch_step(A, n):
+    """a2sgd_step on cache-resident sizes takes the single-launch route (one cooperative kernel)."""
+    for P, mode, with_e in ((1, 0, True), (4, 0, True), (5, 1, True), (3, 1, False)):
+        print(f"case n={n} P={P} mode={mode} e={with_e}", flush=True)
+        g, e, w = make_case(n * 7 + P, n, P)
+        check_against_oracle(A, g, e if with_e else None, w, 0.1, mode, split_calls=False, want_mask=False)
+
+
+def test_single_launch_step_many_workers(A):
+    for P in (16, 33, 64):
+        g, e, w = make_case(P, 50_003, P)
+        check_against_oracle(A, g, e, w, 0.1, 0, split_calls=False, want_mask=False)
+    g, e, w = make_case(5, 10_007, 2)
+    g[1][[0, 77, 10_006]] = np.nan
+    check_against_oracle(A, g, e, w, 0.1, 0, split_calls=False, want_mask=False)
+    # both routes give the same counts and means on the same inputs
+    g, e, w = make_case(6, 700_001, 4)
+    a = gpu_step(A, g, e, w, 0.1, 0, split_calls=True)
+    b = gpu_step(A, g, e, w, 0.1, 0, split_calls=False)
+    assert [(s.n_pos, s.n_neg, s.n_zero) for s in a[0]] == [(s.n_pos, s.n_neg, s.n_zero) for s in b[0]]
+    assert all(abs(x.mu_pos - y.mu_pos) <= 1e-6 * y.mu_pos for x, y in zip(a[0], b[0]))
+
+
 def test_literal_mode_without_error_buffer(A):
     g, _, w = make_case(5, 70_001, 4)
     (stats, gmu, e_new, w_new, _), ref = check_against_oracle(A, g, None, w, 0.1, 1)
