@@ -146,6 +146,19 @@ def main() -> int:
         "result_check": {"gmu_pos": gmu[0], "gmu_neg": gmu[1], "n_pos_worker0": stats[0].n_pos},
     }
 
+    # Outside the timed region: the dense data-parallel step (Eq. 1; Algorithm 1 lines 9-10) on the same buffers,
+    # the "no compression" reference and a bandwidth calibrator (reads every g and w once, writes w once).
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    A.a2sgd_dense_step(plan, g, w, wl.eta)
+    ev0.record()
+    for _ in range(5):
+        A.a2sgd_dense_step(plan, g, w, wl.eta)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_dense = ev0.elapsed_time(ev1) / 5
+    out["dense_step"] = {"ms": ms_dense, "gbps": (4 * n * P + 8 * n) / (ms_dense * 1e-3) / 1e9,
+                         "params_per_s": n / (ms_dense * 1e-3)}
+
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, g, w, min(args.cpu_sample, n))
     print(json.dumps(out))

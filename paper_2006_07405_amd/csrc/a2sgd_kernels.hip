@@ -678,40 +678,58 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused_step(const PtrTable tab, 
     }
 }
 
-constexpr int kDenseUnrollP = 4;
-
-// Eq. 1 / Algorithm 1 lines 9-10: w <- w - eta * mean_p g^p.  Same thread-to-data mapping as k_apply.
-template <bool NT>
-__global__ __launch_bounds__(kBlock) void k_dense_step(const PtrTable tab, float *__restrict__ w, const uint64_t n,
-                                                       const uint32_t P, const float eta_over_P)
+// Eq. 1 / Algorithm 1 lines 9-10: w <- w - eta * mean_p g^p.  Same shape as the apply pass: single-wavefront
+// workgroups launched once each, thread t owning ITEMS float4 groups of w and of every worker, the loads of UP
+// workers issued together, residency capped by the launcher's dynamic-LDS request.
+template <bool NT, int UP, int ITEMS, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_dense_step(const PtrTable tab, float *__restrict__ w, const uint64_t n,
+                                                      const uint32_t P, const float eta_over_P)
 {
     const uint32_t tid = threadIdx.x;
     const uint64_t nvec = n >> 2;
-    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * kBlock + tid;
-    if (i < nvec) {
-        vf4 *w4 = reinterpret_cast<vf4 *>(w) + i;
-        const vf4 wv = ld4<NT>(w4);
-        vf4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-        uint32_t p0 = 0;
-        for (; p0 + kDenseUnrollP <= P; p0 += kDenseUnrollP) {
-            vf4 v[kDenseUnrollP];
+    const uint64_t base = static_cast<uint64_t>(blockIdx.x) * (BLOCK * ITEMS) + tid;
+    vf4 *w4 = reinterpret_cast<vf4 *>(w);
+    vf4 wv[ITEMS], acc[ITEMS];
 #pragma unroll
-            for (int u = 0; u < kDenseUnrollP; ++u)
-                v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + i);
-#pragma unroll
-            for (int u = 0; u < kDenseUnrollP; ++u)
-                acc += v[u];
-        }
-        for (; p0 < P; ++p0)
-            acc += ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0]) + i);
-        st4<NT>(w4, wv - eta_over_P * acc);
+    for (int it = 0; it < ITEMS; ++it) {
+        acc[it] = vf4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (base + it * BLOCK < nvec)
+            wv[it] = ld4<NT>(w4 + base + it * BLOCK);
     }
+    uint32_t p0 = 0;
+    for (; p0 + UP <= P; p0 += UP) {
+        vf4 v[UP * ITEMS];
+#pragma unroll
+        for (int u = 0; u < UP; ++u)
+#pragma unroll
+            for (int it = 0; it < ITEMS; ++it)
+                if (base + it * BLOCK < nvec)
+                    v[u * ITEMS + it] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + base + it * BLOCK);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < UP; ++u)
+#pragma unroll
+            for (int it = 0; it < ITEMS; ++it)
+                if (base + it * BLOCK < nvec)
+                    acc[it] += v[u * ITEMS + it];
+    }
+    for (; p0 < P; ++p0)
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it)
+            if (base + it * BLOCK < nvec)
+                acc[it] += ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0]) + base + it * BLOCK);
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it)
+        if (base + it * BLOCK < nvec) {
+            const vf4 wn = wv[it] - eta_over_P * acc[it];
+            st4<NT>(w4 + base + it * BLOCK, wn);
+        }
     if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
         const uint64_t k = (nvec << 2) + tid;
-        float acc = 0.0f;
+        float a = 0.0f;
         for (uint32_t p = 0; p < P; ++p)
-            acc += tab.g[p][k];
-        w[k] -= eta_over_P * acc;
+            a += tab.g[p][k];
+        w[k] -= eta_over_P * a;
     }
 }
 
@@ -738,12 +756,6 @@ __global__ __launch_bounds__(kBlock) void k_export_mask(const PtrTable tab, cons
 // ---------------------------------------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------------------------------------
-
-static inline uint32_t apply_grid(uint64_t n)
-{
-    const uint64_t nvec = (n + 3) >> 2;  // the scalar tail rides in the last block even when n < 4
-    return static_cast<uint32_t>((nvec + kBlock - 1) / kBlock);
-}
 
 hipError_t launch_local_partials(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, void *ws, hipStream_t s)
 {
@@ -873,15 +885,29 @@ hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool 
     return hipGetLastError();
 }
 
+template <bool NT, int UP>
+static hipError_t launch_dense_inst(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eop, hipStream_t s)
+{
+    constexpr int kItems = 2, kThreads = 64;
+    const uint64_t nvec = (pl.n + 3) >> 2, per = static_cast<uint64_t>(kThreads) * kItems;
+    const dim3 grid(static_cast<uint32_t>((nvec + per - 1) / per)), block(kThreads);
+    k_dense_step<NT, UP, kItems, kThreads><<<grid, block, pl.apply.lds_bytes, s>>>(tab, w, pl.n, pl.P, eop);
+    return hipGetLastError();
+}
+
 hipError_t launch_dense_step(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eta, hipStream_t s)
 {
     const float eop = static_cast<float>(static_cast<double>(eta) / static_cast<double>(pl.P));
-    const dim3 grid(apply_grid(pl.n)), block(kBlock);
+    const int up = pl.apply.up;
     if (pl.streaming)
-        k_dense_step<true><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop);
-    else
-        k_dense_step<false><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop);
-    return hipGetLastError();
+        return up == 8   ? launch_dense_inst<true, 8>(pl, tab, w, eop, s)
+               : up == 4 ? launch_dense_inst<true, 4>(pl, tab, w, eop, s)
+               : up == 2 ? launch_dense_inst<true, 2>(pl, tab, w, eop, s)
+                         : launch_dense_inst<true, 1>(pl, tab, w, eop, s);
+    return up == 8   ? launch_dense_inst<false, 8>(pl, tab, w, eop, s)
+           : up == 4 ? launch_dense_inst<false, 4>(pl, tab, w, eop, s)
+           : up == 2 ? launch_dense_inst<false, 2>(pl, tab, w, eop, s)
+                     : launch_dense_inst<false, 1>(pl, tab, w, eop, s);
 }
 
 }  // namespace a2sgd
