@@ -18,11 +18,17 @@ __device__ __forceinline__ vf4 ld4(const vf4 *p)
     return *p;
 }
 
+// Streaming store: non-temporal and written through at device scope (sc1), so the line does not linger in the
+// XCD's write-back L2.  Measured on the apply pass's mix of 9 read and 5 write streams: 4.5 % faster than the
+// non-temporal hint alone, 14 % faster than plain stores.  The instruction is spelled out because the compiler
+// offers no builtin for the scope bit on a 128-bit store (and its non-temporal metadata has been seen to get
+// lost on the way through the optimiser).  A store reads its data registers when it issues, so nothing has to
+// be waited for afterwards.
 template <bool NT>
 __device__ __forceinline__ void st4(vf4 *p, vf4 v)
 {
     if (NT)
-        __builtin_nontemporal_store(v, p);
+        asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
     else
         *p = v;
 }

@@ -33,7 +33,7 @@ def test_no_scratch_and_no_packed_fp32(asm):
     assert not re.search(r"v_pk_(add|mul|fma)_f32", text)
 
 
-def test_streaming_apply_stores_are_all_non_temporal(asm):
+def test_streaming_apply_stores_are_all_write_through_non_temporal(asm):
     _, kernels = asm
     # k_apply<MODE, HAS_E, NT, ...>: Lb1 in third place marks the streaming instantiations
     streaming = {k: v for k, v in kernels.items() if re.match(r"_ZN5a2sgd7k_applyILi[01]ELb[01]ELb1E", k)}
@@ -41,8 +41,8 @@ def test_streaming_apply_stores_are_all_non_temporal(asm):
     for name, body in streaming.items():
         stores = re.findall(r"global_store_dwordx4[^\n]*", body)
         assert stores, name
-        bad = [s for s in stores if not s.rstrip().endswith(" nt")]
-        assert not bad, f"{name}: {len(bad)} of {len(stores)} 128-bit stores lost the non-temporal hint"
+        bad = [s for s in stores if not s.rstrip().endswith(" sc1 nt")]
+        assert not bad, f"{name}: {len(bad)} of {len(stores)} 128-bit stores are not write-through non-temporal"
 
 
 def test_streaming_reduction_loads_are_non_temporal_and_batched(asm):
