@@ -144,3 +144,67 @@ void a2sgd_oracle_dense_step(const float *const *g, uint32_t P, uint64_t m, floa
         w_new[i] = (float)((double)w[i] - (double)eta * (s / (double)P));
     }
 }
+
+/* Algorithm 1 lines 4, 6 and 7 as each worker runs them on its OWN replica of the model: the same error and
+ * rebuilt gradient as a2sgd_oracle_apply_chunk, but w[p] <- w[p] - eta * u^p per worker, with no averaging over
+ * the workers (line 7 as printed; the replicas drift apart, which is why the algorithm ends with a
+ * synchronisation step). */
+void a2sgd_oracle_apply_chunk_replicas(const float *const *g, const float *const *e, uint32_t P, uint64_t m,
+                                       const float *mu_pos, const float *mu_neg, float gmu_pos, float gmu_neg,
+                                       float eta, int mode, float *const *e_new, const float *const *w,
+                                       float *const *w_new)
+{
+    for (uint32_t p = 0; p < P; ++p) {
+        for (uint64_t i = 0; i < m; ++i) {
+            float v = fold(g[p], e ? e[p] : NULL, i);
+            double err, glob;
+            if (v >= 0.0f) {
+                err = (double)v - (double)mu_pos[p];
+                glob = (double)gmu_pos;
+            } else if (v < 0.0f) {
+                err = (double)v + (double)mu_neg[p];
+                glob = -(double)gmu_neg;
+            } else {
+                err = (double)v;
+                glob = (double)v;
+            }
+            e_new[p][i] = (float)err;
+            double u = (mode == A2SGD_ORACLE_ALG1_LITERAL) ? err + glob : glob;
+            w_new[p][i] = (float)((double)w[p][i] - (double)eta * u);
+        }
+    }
+}
+
+/* Final synchronisation on replicas (Algorithm 1 lines 9-10): every replica takes the same dense averaged
+ * gradient, w[p] <- w[p] - eta * (1/P) sum_q g^q. */
+void a2sgd_oracle_dense_step_replicas(const float *const *g, uint32_t P, uint64_t m, float eta,
+                                      const float *const *w, float *const *w_new)
+{
+    for (uint64_t i = 0; i < m; ++i) {
+        double s = 0.0;
+        for (uint32_t p = 0; p < P; ++p)
+            s += (double)g[p][i];
+        for (uint32_t p = 0; p < P; ++p)
+            w_new[p][i] = (float)((double)w[p][i] - (double)eta * (s / (double)P));
+    }
+}
+
+/* How far the replicas have drifted: with wbar_i = (1/P) sum_p w[p][i], per worker the largest |w[p][i] - wbar_i|
+ * and the sum of squares of those deviations, accumulated over chunks (max_abs[p] and sum_sq[p] are updated in
+ * place; start them at 0). */
+void a2sgd_oracle_replica_drift(const float *const *w, uint32_t P, uint64_t m, double *max_abs, long double *sum_sq)
+{
+    for (uint64_t i = 0; i < m; ++i) {
+        double s = 0.0;
+        for (uint32_t p = 0; p < P; ++p)
+            s += (double)w[p][i];
+        double mean = s / (double)P;
+        for (uint32_t p = 0; p < P; ++p) {
+            double d = (double)w[p][i] - mean;
+            double a = fabs(d);
+            if (a > max_abs[p] || a != a)
+                max_abs[p] = a;
+            sum_sq[p] += (long double)d * (long double)d;
+        }
+    }
+}

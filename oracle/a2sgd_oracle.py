@@ -58,6 +58,14 @@ def _bind(path: str):
     L.a2sgd_oracle_apply_chunk.restype = None
     L.a2sgd_oracle_dense_step.argtypes = [_FPP, C.c_uint32, C.c_uint64, C.c_float, _FP, _FP]
     L.a2sgd_oracle_dense_step.restype = None
+    L.a2sgd_oracle_apply_chunk_replicas.argtypes = [_FPP, _FPP, C.c_uint32, C.c_uint64, _FP, _FP, C.c_float,
+                                                    C.c_float, C.c_float, C.c_int, _FPP, _FPP, _FPP]
+    L.a2sgd_oracle_apply_chunk_replicas.restype = None
+    L.a2sgd_oracle_dense_step_replicas.argtypes = [_FPP, C.c_uint32, C.c_uint64, C.c_float, _FPP, _FPP]
+    L.a2sgd_oracle_dense_step_replicas.restype = None
+    L.a2sgd_oracle_replica_drift.argtypes = [_FPP, C.c_uint32, C.c_uint64, C.POINTER(C.c_double),
+                                             C.POINTER(C.c_longdouble)]
+    L.a2sgd_oracle_replica_drift.restype = None
     return L
 
 
@@ -200,3 +208,54 @@ def dense_step(g: Sequence[np.ndarray], w: np.ndarray, eta: float) -> np.ndarray
     out = np.empty_like(w)
     lib().a2sgd_oracle_dense_step(_fpp(g), len(g), w.shape[0], C.c_float(eta), _fp(w), _fp(out))
     return out
+
+
+def local_stats(g: Sequence[np.ndarray], e: Optional[Sequence[Optional[np.ndarray]]], chunk: int = 1 << 22):
+    """Pass A for every worker of in-memory arrays: ([WorkerStats] * P, (gmu_pos, gmu_neg))."""
+    workers = []
+    n = int(np.asarray(g[0]).shape[0])
+    for p in range(len(g)):
+        acc = LocalAccumulator()
+        for lo in range(0, n, chunk):
+            hi = min(n, lo + chunk)
+            acc.feed(g[p][lo:hi], e[p][lo:hi] if (e is not None and e[p] is not None) else None)
+        workers.append(acc.stats())
+    return workers, global_means(workers)
+
+
+def step_replicas(g: Sequence[np.ndarray], e: Optional[Sequence[Optional[np.ndarray]]], w: Sequence[np.ndarray],
+                  eta: float, mode: int = RETAINED_ERROR):
+    """One step with one weight vector per worker (Algorithm 1 line 7 as printed).  Returns
+    (workers, (gmu_pos, gmu_neg), e_new list, w_new list)."""
+    P = len(g)
+    g = [_f32(x) for x in g]
+    m = g[0].shape[0]
+    e_arr = [(_f32(x) if x is not None else None) for x in e] if e is not None else None
+    w = [_f32(x) for x in w]
+    workers, (gp, gn) = local_stats(g, e_arr)
+    e_new = [np.empty(m, dtype=np.float32) for _ in range(P)]
+    w_new = [np.empty(m, dtype=np.float32) for _ in range(P)]
+    mp = np.array([s.mu_pos for s in workers], dtype=np.float32)
+    mn = np.array([s.mu_neg for s in workers], dtype=np.float32)
+    lib().a2sgd_oracle_apply_chunk_replicas(_fpp(g), _fpp(e_arr) if e_arr is not None else _FPP(), P, m, _fp(mp),
+                                            _fp(mn), C.c_float(gp), C.c_float(gn), C.c_float(eta), int(mode),
+                                            _fpp(e_new), _fpp(w), _fpp(w_new))
+    return workers, (gp, gn), e_new, w_new
+
+
+def dense_step_replicas(g: Sequence[np.ndarray], w: Sequence[np.ndarray], eta: float) -> List[np.ndarray]:
+    g = [_f32(x) for x in g]
+    w = [_f32(x) for x in w]
+    out = [np.empty_like(x) for x in w]
+    lib().a2sgd_oracle_dense_step_replicas(_fpp(g), len(g), g[0].shape[0], C.c_float(eta), _fpp(w), _fpp(out))
+    return out
+
+
+def replica_drift(w: Sequence[np.ndarray]):
+    """(max_abs[P], rms[P]) of w[p] - mean_p w[p]."""
+    w = [_f32(x) for x in w]
+    P, m = len(w), w[0].shape[0]
+    mx = (C.c_double * P)(*([0.0] * P))
+    sq = (C.c_longdouble * P)(*([0.0] * P))
+    lib().a2sgd_oracle_replica_drift(_fpp(w), P, m, mx, sq)
+    return [float(x) for x in mx], [float(np.sqrt(float(x) / m)) for x in sq]

@@ -446,12 +446,59 @@ def test_chunk_split_invariance():
 
 
 # ---------------------------------------------------------------------------------------------------------
+# per-replica weights (Algorithm 1 line 7 as printed) and the final synchronisation on replicas
+# ---------------------------------------------------------------------------------------------------------
+def check_replicas():
+    rng = np.random.default_rng(91)
+    n, P = 30_011, 4
+    g, e, w = random_case(rng, n, P)
+    wr = [(w + (rng.standard_normal(n) * 1e-3).astype(f32)) for _ in range(P)]
+    for mode in (O.RETAINED_ERROR, O.ALG1_LITERAL):
+        shared = O.step(g, e, np.mean(np.stack(wr).astype(np.float64), axis=0).astype(f32), 0.1, mode)
+        workers, gmu, e_new, w_new = O.step_replicas(g, e, wr, 0.1, mode)
+        assert workers == shared.workers and gmu == (shared.gmu_pos, shared.gmu_neg)
+        assert all(np.array_equal(a, b) for a, b in zip(e_new, shared.e_new))
+        # the mean of the replicas moves like the shared weight vector (no update depends on w)
+        mean_new = np.mean(np.stack(w_new).astype(np.float64), axis=0)
+        mean_old = np.mean(np.stack(wr).astype(np.float64), axis=0)
+        assert np.allclose(mean_new - mean_old, shared.w_new.astype(np.float64) - mean_old.astype(f32), rtol=0, atol=2e-8)
+        # each replica separately: retained mode moves it by one of two values
+        for p in range(P):
+            step_p = (wr[p].astype(np.float64) - w_new[p]) / np.float64(f32(0.1))
+            if mode == O.RETAINED_ERROR:
+                want = np.where(shared.mask[p] == 1, np.float64(gmu[0]), -np.float64(gmu[1]))
+                assert np.allclose(step_p, want, rtol=0, atol=1e-7)
+    # P = 1: the replica path is the shared path
+    r1 = O.step([g[0]], [e[0]], wr[0], 0.1)
+    _, _, e1, w1 = O.step_replicas([g[0]], [e[0]], [wr[0]], 0.1)
+    assert np.array_equal(w1[0], r1.w_new) and np.array_equal(e1[0], r1.e_new[0])
+    # final synchronisation: every replica takes the dense averaged gradient; drift is unchanged by it
+    d0 = O.replica_drift(wr)
+    ws = O.dense_step_replicas(g, wr, 0.1)
+    for p in range(P):
+        ref = wr[p].astype(np.float64) - np.float64(f32(0.1)) * np.mean(np.stack(g).astype(np.float64), axis=0)
+        assert np.allclose(ws[p], ref, rtol=0, atol=4e-9)
+    d1 = O.replica_drift(ws)
+    assert np.allclose(d0[0], d1[0], rtol=0, atol=1e-8) and np.allclose(d0[1], d1[1], rtol=1e-5)
+    # drift against numpy
+    W = np.stack(wr).astype(np.float64)
+    dev = W - W.mean(axis=0)
+    assert np.allclose(d0[0], np.abs(dev).max(axis=1), rtol=1e-12) and np.allclose(d0[1], np.sqrt((dev ** 2).mean(axis=1)), rtol=1e-10)
+    same = O.replica_drift([wr[0]] * 3)
+    assert same[0] == [0.0] * 3 and same[1] == [0.0] * 3
+
+
+def test_replicas():
+    check_replicas()
+
+
+# ---------------------------------------------------------------------------------------------------------
 # mutation battery: every planted mistake must trip at least one pin
 # ---------------------------------------------------------------------------------------------------------
 PINS = [check_worked_example, check_brute_force, check_means_against_fsum, check_reconstruction_and_zero_sum,
         check_nan_handling, check_p1_literal_is_plain_sgd, check_p1_retained_is_local_encoding,
         check_theorem1_form, check_same_sign_and_two_valued, check_identical_workers,
-        check_power_of_two_scaling, check_permutation_and_sign_flip, check_closed_forms]
+        check_power_of_two_scaling, check_permutation_and_sign_flip, check_closed_forms, check_replicas]
 
 MUTANTS = [
     ("zero_in_negative_group", "if (v >= 0.0f) {\n            acc->n_pos", "if (v > 0.0f) {\n            acc->n_pos"),
@@ -460,17 +507,28 @@ MUTANTS = [
      "(float)(acc->s_neg / (long double)acc->n_pos)"),
     ("global_mean_not_divided", "*gmu_pos = (float)(sp / (double)P);", "*gmu_pos = (float)(sp);"),
     ("global_means_swapped", "sn += (double)mu_neg[p];", "sn += (double)mu_pos[p];"),
-    ("error_sign_neg_group", "err = (double)v + (double)mu_neg[p];", "err = (double)v - (double)mu_neg[p];"),
-    ("error_uses_global_mean", "err = (double)v - (double)mu_pos[p];", "err = (double)v - (double)gmu_pos;"),
-    ("update_sign_neg_group", "glob = -(double)gmu_neg;", "glob = (double)gmu_neg;"),
+    ("error_sign_neg_group", "err = (double)v + (double)mu_neg[p]; /* v - enc", "err = (double)v - (double)mu_neg[p]; /* v - enc"),
+    ("error_uses_global_mean", "err = (double)v - (double)mu_pos[p]; /* v - enc", "err = (double)v - (double)gmu_pos; /* v - enc"),
+    ("update_sign_neg_group", "glob = -(double)gmu_neg;\n            } else { /* NaN", "glob = (double)gmu_neg;\n            } else { /* NaN"),
+    ("replica_error_sign_neg_group", "err = (double)v + (double)mu_neg[p];\n", "err = (double)v - (double)mu_neg[p];\n"),
+    ("replica_update_sign_neg_group", "glob = -(double)gmu_neg;\n            } else {\n", "glob = (double)gmu_neg;\n            } else {\n"),
     ("update_not_averaged", "double U = usum / (double)P;", "double U = usum;"),
     ("weight_update_sign", "(double)w[i] - (double)eta * U", "(double)w[i] + (double)eta * U"),
-    ("literal_drops_error", "? err + glob : glob", "? glob : glob"),
-    ("retained_adds_error", "? err + glob : glob", "? err + glob : err + glob"),
+    ("literal_drops_error", "usum += (mode == A2SGD_ORACLE_ALG1_LITERAL) ? err + glob : glob;", "usum += glob;"),
+    ("retained_adds_error", "usum += (mode == A2SGD_ORACLE_ALG1_LITERAL) ? err + glob : glob;", "usum += err + glob;"),
     ("fold_drops_error", "float v = g[i] + e[i];", "float v = g[i];"),
     ("mask_strict", "mask[p][i] = (uint8_t)(v >= 0.0f);", "mask[p][i] = (uint8_t)(v > 0.0f);"),
-    ("apply_strict_compare", "if (v >= 0.0f) {\n                err", "if (v > 0.0f) {\n                err"),
-    ("dense_not_averaged", "(s / (double)P)", "(s)"),
+    ("apply_strict_compare", "if (v >= 0.0f) {\n                err = (double)v - (double)mu_pos[p]; /* v",
+     "if (v > 0.0f) {\n                err = (double)v - (double)mu_pos[p]; /* v"),
+    ("dense_not_averaged", "w_new[i] = (float)((double)w[i] - (double)eta * (s / (double)P));",
+     "w_new[i] = (float)((double)w[i] - (double)eta * (s));"),
+    ("replica_update_sign", "w_new[p][i] = (float)((double)w[p][i] - (double)eta * u);",
+     "w_new[p][i] = (float)((double)w[p][i] + (double)eta * u);"),
+    ("replica_literal_drops_error", "double u = (mode == A2SGD_ORACLE_ALG1_LITERAL) ? err + glob : glob;",
+     "double u = glob;"),
+    ("replica_dense_not_averaged", "w_new[p][i] = (float)((double)w[p][i] - (double)eta * (s / (double)P));",
+     "w_new[p][i] = (float)((double)w[p][i] - (double)eta * s);"),
+    ("drift_mean_not_divided", "double mean = s / (double)P;", "double mean = s;"),
 ]
 
 
