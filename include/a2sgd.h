@@ -138,6 +138,32 @@ a2sgd_status_t a2sgd_export_mask(const a2sgd_plan_t *plan, const float *const *g
 a2sgd_status_t a2sgd_dense_step(const a2sgd_plan_t *plan, const float *const *g, float *w, float eta,
                                 a2sgd_stream_t stream);
 
+/* ---- One weight vector per worker: Algorithm 1 as each worker runs it on its own replica ------------------
+ * `w` is a HOST array of P DEVICE pointers, like g and e; w^p is updated in place.  The same workspace serves. */
+
+/* Algorithm 1 lines 4, 6 and 7 exactly as printed for worker p: e^p as in a2sgd_apply_and_update_error, and
+ * w^p_i <- w^p_i - eta * u^p_i with that worker's own rebuilt update, no averaging over the workers.  The mean
+ * of the P replicas then moves exactly as the single w of a2sgd_apply_and_update_error does.  Reads g, e, w^p
+ * once, writes e and w^p once: 20 bytes per element and worker. */
+a2sgd_status_t a2sgd_apply_and_update_error_replicas(const a2sgd_plan_t *plan, const float *const *g, float *const *e,
+                                                     float *const *w, float eta, void *workspace,
+                                                     a2sgd_stream_t stream);
+
+/* a2sgd_local_averages, a2sgd_global_average and a2sgd_apply_and_update_error_replicas, in order. */
+a2sgd_status_t a2sgd_step_replicas(const a2sgd_plan_t *plan, const float *const *g, float *const *e, float *const *w,
+                                   float eta, void *workspace, a2sgd_stream_t stream);
+
+/* The synchronisation step that ends Algorithm 1 (lines 9-10): every replica takes the dense averaged gradient,
+ * w^p_i <- w^p_i - eta * (1/P) * sum_q g^q_i. */
+a2sgd_status_t a2sgd_dense_step_replicas(const a2sgd_plan_t *plan, const float *const *g, float *const *w, float eta,
+                                         a2sgd_stream_t stream);
+
+/* How far the replicas have drifted apart: with wbar_i = (1/P) sum_p w^p_i, out_max_abs[p] = max_i |w^p_i -
+ * wbar_i| and out_rms[p] = sqrt((1/n) sum_i (w^p_i - wbar_i)^2), both host arrays of P doubles (either may be
+ * NULL).  Overwrites the workspace's partial records; synchronises `stream`.  A diagnostic, not on the step. */
+a2sgd_status_t a2sgd_replica_drift(const a2sgd_plan_t *plan, const float *const *w, void *workspace,
+                                   a2sgd_stream_t stream, double *out_max_abs, double *out_rms);
+
 /* Geometry the plan chose, for reports: blocks per worker of the first-level reduction. */
 uint32_t a2sgd_plan_blocks_per_worker(const a2sgd_plan_t *plan);
 

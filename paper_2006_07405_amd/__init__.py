@@ -4,4 +4,6 @@ from .binding import (A2SGD_MAX_WORKERS, A2SGD_MODE_ALG1_LITERAL, A2SGD_MODE_RET
                       A2SGD_ERR_INVALID_ARG, A2SGD_ERR_ALIGNMENT, A2SGD_ERR_DEVICE, A2SGD_ERR_NOMEM, A2sgdError,
                       Plan, WorkerStats, a2sgd_plan, a2sgd_workspace_bytes, a2sgd_plan_blocks_per_worker,
                       alloc_workspace, a2sgd_local_averages, a2sgd_global_average, a2sgd_apply_and_update_error,
-                      a2sgd_step, a2sgd_read_stats, a2sgd_export_mask, a2sgd_dense_step, raw, LIB_PATH)
+                      a2sgd_step, a2sgd_read_stats, a2sgd_export_mask, a2sgd_dense_step,
+                      a2sgd_apply_and_update_error_replicas, a2sgd_step_replicas, a2sgd_dense_step_replicas,
+                      a2sgd_replica_drift, raw, LIB_PATH)

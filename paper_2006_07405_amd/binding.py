@@ -55,11 +55,16 @@ def _load():
     L.a2sgd_read_stats.argtypes = [vp, vp, vp, C.POINTER(a2sgd_worker_stats_t), C.POINTER(a2sgd_global_stats_t)]
     L.a2sgd_export_mask.argtypes = [vp, tab, tab, vp, vp]
     L.a2sgd_dense_step.argtypes = [vp, tab, vp, C.c_float, vp]
+    L.a2sgd_apply_and_update_error_replicas.argtypes = [vp, tab, tab, tab, C.c_float, vp, vp]
+    L.a2sgd_step_replicas.argtypes = [vp, tab, tab, tab, C.c_float, vp, vp]
+    L.a2sgd_dense_step_replicas.argtypes = [vp, tab, tab, C.c_float, vp]
+    L.a2sgd_replica_drift.argtypes = [vp, tab, vp, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     L.a2sgd_status_string.argtypes = [C.c_int]
     L.a2sgd_status_string.restype = C.c_char_p
     for name in ("a2sgd_plan", "a2sgd_plan_destroy", "a2sgd_local_averages", "a2sgd_global_average",
                  "a2sgd_apply_and_update_error", "a2sgd_step", "a2sgd_read_stats", "a2sgd_export_mask",
-                 "a2sgd_dense_step"):
+                 "a2sgd_dense_step", "a2sgd_apply_and_update_error_replicas", "a2sgd_step_replicas",
+                 "a2sgd_dense_step_replicas", "a2sgd_replica_drift"):
         getattr(L, name).restype = C.c_int
     return L
 
@@ -195,3 +200,29 @@ def a2sgd_export_mask(plan: Plan, g, e, mask: torch.Tensor, stream=None) -> None
 def a2sgd_dense_step(plan: Plan, g, w: torch.Tensor, eta: float, stream=None) -> None:
     _check(raw.a2sgd_dense_step(plan.handle, _table(plan, g, "g"), _dev_ptr(w, plan.n, torch.float32, "w"),
                                 C.c_float(eta), _stream(stream)), "a2sgd_dense_step")
+
+
+def a2sgd_apply_and_update_error_replicas(plan: Plan, g, e, w, eta: float, workspace: torch.Tensor, stream=None) -> None:
+    _check(raw.a2sgd_apply_and_update_error_replicas(plan.handle, _table(plan, g, "g"), _table(plan, e, "e"),
+                                                     _table(plan, w, "w"), C.c_float(eta),
+                                                     _workspace(plan, workspace), _stream(stream)),
+           "a2sgd_apply_and_update_error_replicas")
+
+
+def a2sgd_step_replicas(plan: Plan, g, e, w, eta: float, workspace: torch.Tensor, stream=None) -> None:
+    _check(raw.a2sgd_step_replicas(plan.handle, _table(plan, g, "g"), _table(plan, e, "e"), _table(plan, w, "w"),
+                                   C.c_float(eta), _workspace(plan, workspace), _stream(stream)), "a2sgd_step_replicas")
+
+
+def a2sgd_dense_step_replicas(plan: Plan, g, w, eta: float, stream=None) -> None:
+    _check(raw.a2sgd_dense_step_replicas(plan.handle, _table(plan, g, "g"), _table(plan, w, "w"), C.c_float(eta),
+                                         _stream(stream)), "a2sgd_dense_step_replicas")
+
+
+def a2sgd_replica_drift(plan: Plan, w, workspace: torch.Tensor, stream=None):
+    """Returns (max_abs[P], rms[P]) of w^p - mean_p w^p.  Synchronises the stream."""
+    mx = (C.c_double * plan.num_workers)()
+    rms = (C.c_double * plan.num_workers)()
+    _check(raw.a2sgd_replica_drift(plan.handle, _table(plan, w, "w"), _workspace(plan, workspace), _stream(stream),
+                                   mx, rms), "a2sgd_replica_drift")
+    return list(mx), list(rms)

@@ -73,6 +73,12 @@ a2sgd_status_t check_buffer(const void *p)
     return aligned16(p) ? A2SGD_OK : A2SGD_ERR_ALIGNMENT;
 }
 
+void fill_replicas(ReplicaTable &t, uint32_t P, float *const *w)
+{
+    for (uint32_t p = 0; p < kMaxWorkers; ++p)
+        t.w[p] = p < P ? w[p] : nullptr;
+}
+
 void fill_table(PtrTable &t, uint32_t P, const float *const *g, const float *const *e)
 {
     for (uint32_t p = 0; p < kMaxWorkers; ++p) {
@@ -131,7 +137,9 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
         pl->fused_grid = static_cast<uint32_t>(want < kFusedGridMax ? want : kFusedGridMax);
     }
     const uint32_t rows = pl->B > pl->fused_grid ? pl->B : pl->fused_grid;
-    pl->workspace_bytes = kHeaderBytes + 5ull * 8ull * pl->P * rows;
+    const size_t partials = 5ull * 8ull * pl->P * rows;
+    const size_t drift = 2ull * 8ull * pl->P * (kDriftBlocks + 1);  // the drift diagnostic reuses the same region
+    pl->workspace_bytes = kHeaderBytes + (partials > drift ? partials : drift);
     *out_plan = pl;
     return A2SGD_OK;
 }
@@ -273,6 +281,92 @@ a2sgd_status_t a2sgd_dense_step(const a2sgd_plan_t *plan, const float *const *g,
     PtrTable tab;
     fill_table(tab, plan->P, g, nullptr);
     return dev(launch_dense_step(*plan, tab, w, eta, static_cast<hipStream_t>(stream)));
+}
+
+a2sgd_status_t a2sgd_apply_and_update_error_replicas(const a2sgd_plan_t *plan, const float *const *g, float *const *e,
+                                                     float *const *w, float eta, void *workspace,
+                                                     a2sgd_stream_t stream)
+{
+    bool has_e = false, has_w = false;
+    a2sgd_status_t st = check_g_e(plan, g, e, &has_e);
+    if (st != A2SGD_OK)
+        return st;
+    if ((st = check_table(w, plan->P, true, &has_w)) != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(workspace)) != A2SGD_OK)
+        return st;
+    PtrTable tab;
+    ReplicaTable wt;
+    fill_table(tab, plan->P, g, has_e ? e : nullptr);
+    fill_replicas(wt, plan->P, w);
+    return dev(launch_apply_replicas(*plan, tab, wt, has_e, eta, workspace, static_cast<hipStream_t>(stream)));
+}
+
+a2sgd_status_t a2sgd_step_replicas(const a2sgd_plan_t *plan, const float *const *g, float *const *e, float *const *w,
+                                   float eta, void *workspace, a2sgd_stream_t stream)
+{
+    bool has_e = false, has_w = false;
+    a2sgd_status_t st = check_g_e(plan, g, e, &has_e);
+    if (st != A2SGD_OK)
+        return st;
+    if ((st = check_table(w, plan->P, true, &has_w)) != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(workspace)) != A2SGD_OK)
+        return st;
+    if ((st = a2sgd_local_averages(plan, g, e, workspace, stream)) != A2SGD_OK)
+        return st;
+    if ((st = a2sgd_global_average(plan, workspace, stream)) != A2SGD_OK)
+        return st;
+    return a2sgd_apply_and_update_error_replicas(plan, g, e, w, eta, workspace, stream);
+}
+
+a2sgd_status_t a2sgd_dense_step_replicas(const a2sgd_plan_t *plan, const float *const *g, float *const *w, float eta,
+                                         a2sgd_stream_t stream)
+{
+    if (plan == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    bool has_g = false, has_w = false;
+    a2sgd_status_t st = check_table(g, plan->P, true, &has_g);
+    if (st != A2SGD_OK)
+        return st;
+    if ((st = check_table(w, plan->P, true, &has_w)) != A2SGD_OK)
+        return st;
+    PtrTable tab;
+    ReplicaTable wt;
+    fill_table(tab, plan->P, g, nullptr);
+    fill_replicas(wt, plan->P, w);
+    return dev(launch_dense_step_replicas(*plan, tab, wt, eta, static_cast<hipStream_t>(stream)));
+}
+
+a2sgd_status_t a2sgd_replica_drift(const a2sgd_plan_t *plan, const float *const *w, void *workspace,
+                                   a2sgd_stream_t stream, double *out_max_abs, double *out_rms)
+{
+    if (plan == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    bool has_w = false;
+    a2sgd_status_t st = check_table(w, plan->P, true, &has_w);
+    if (st != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(workspace)) != A2SGD_OK)
+        return st;
+    ReplicaTable wt;
+    fill_replicas(wt, plan->P, const_cast<float *const *>(w));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if ((st = dev(launch_replica_drift(*plan, wt, workspace, s))) != A2SGD_OK)
+        return st;
+    double res[2 * kMaxWorkers];
+    if (hipMemcpyAsync(res, static_cast<const char *>(workspace) + drift_result_offset(*plan),
+                       2 * sizeof(double) * plan->P, hipMemcpyDeviceToHost, s) != hipSuccess)
+        return A2SGD_ERR_DEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess)
+        return A2SGD_ERR_DEVICE;
+    for (uint32_t p = 0; p < plan->P; ++p) {
+        if (out_max_abs)
+            out_max_abs[p] = res[p];
+        if (out_rms)
+            out_rms[p] = res[plan->P + p];
+    }
+    return A2SGD_OK;
 }
 
 const char *a2sgd_status_string(a2sgd_status_t status)

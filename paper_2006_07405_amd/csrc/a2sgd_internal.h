@@ -57,6 +57,11 @@ struct PtrTable {
     const float *g[kMaxWorkers];
     float *e[kMaxWorkers];
 };
+// The P weight replicas, for the per-replica entry points only.
+struct ReplicaTable {
+    float *w[kMaxWorkers];
+};
+constexpr uint32_t kDriftBlocks = 256;  // workgroups per worker of the replica-drift reduction
 
 }  // namespace a2sgd
 
@@ -92,6 +97,13 @@ hipError_t launch_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e,
                         hipStream_t s);
 hipError_t launch_fused_step(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
                              uint32_t token, hipStream_t s);
+hipError_t launch_apply_replicas(const a2sgd_plan_t &pl, const PtrTable &tab, const ReplicaTable &wt, bool has_e,
+                                 float eta, void *ws, hipStream_t s);
+hipError_t launch_dense_step_replicas(const a2sgd_plan_t &pl, const PtrTable &tab, const ReplicaTable &wt, float eta,
+                                      hipStream_t s);
+// Writes 2 * P doubles (max_abs[P], then rms[P]) at ws + drift_result_offset(pl).
+hipError_t launch_replica_drift(const a2sgd_plan_t &pl, const ReplicaTable &wt, void *ws, hipStream_t s);
+size_t drift_result_offset(const a2sgd_plan_t &pl);
 hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, uint64_t *mask, hipStream_t s);
 hipError_t launch_dense_step(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eta, hipStream_t s);
 

@@ -22,13 +22,14 @@ __device__ __forceinline__ vf4 ld4(const vf4 *p)
 // XCD's write-back L2.  Measured on the apply pass's mix of 9 read and 5 write streams: 4.5 % faster than the
 // non-temporal hint alone, 14 % faster than plain stores.  The instruction is spelled out because the compiler
 // offers no builtin for the scope bit on a 128-bit store (and its non-temporal metadata has been seen to get
-// lost on the way through the optimiser).  A store reads its data registers when it issues, so nothing has to
-// be waited for afterwards.
+// lost on the way through the optimiser).  The s_nop belongs to the store: on this chip a vector instruction
+// must not overwrite the data registers of a store wider than 64 bits within 2 wait states of it, a hazard the
+// compiler pads by itself for its own stores but cannot see inside an asm statement.
 template <bool NT>
 __device__ __forceinline__ void st4(vf4 *p, vf4 v)
 {
     if (NT)
-        asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
+        asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
     else
         *p = v;
 }
@@ -739,6 +740,197 @@ __global__ __launch_bounds__(BLOCK) void k_dense_step(const PtrTable tab, float 
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// One weight vector per worker (Algorithm 1 line 7 as printed), the replica form of the final synchronisation
+// (lines 9-10), and the replica-drift diagnostic
+// ---------------------------------------------------------------------------------------------------------
+
+// Same shape as k_apply with one float4 group per thread; per worker it also loads and stores that worker's
+// own weights, w^p <- w^p - eta * u^p, and nothing is summed over the workers.
+template <int MODE, bool HAS_E, bool NT, int UP, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_apply_replicas(const PtrTable tab, const ReplicaTable wt, const uint64_t n,
+                                                          const uint32_t P, const float eta,
+                                                          const WsHeader *__restrict__ hdr)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lz = opaque_zero();
+    const float *neg_mu_pos = hdr->neg_mu_pos + lz, *mu_neg = hdr->mu_neg + lz;
+    const float gmu_pos = (&hdr->gmu_pos)[lz];
+    const float neg_gmu_neg = -(&hdr->gmu_neg)[lz];
+    const uint64_t nvec = n >> 2;
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * BLOCK + tid;
+    if (i < nvec) {
+        uint32_t p0 = 0;
+        for (; p0 + UP <= P; p0 += UP) {
+            vf4 v[UP], ev[UP], wv[UP];
+            float nmp[UP], mn[UP];
+#pragma unroll
+            for (int u = 0; u < UP; ++u) {
+                nmp[u] = neg_mu_pos[p0 + u];
+                mn[u] = mu_neg[p0 + u];
+            }
+#pragma unroll
+            for (int u = 0; u < UP; ++u)
+                v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + i);
+            if (HAS_E) {
+#pragma unroll
+                for (int u = 0; u < UP; ++u)
+                    ev[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0 + u]) + i);
+            }
+#pragma unroll
+            for (int u = 0; u < UP; ++u)
+                wv[u] = ld4<NT>(reinterpret_cast<const vf4 *>(wt.w[p0 + u]) + i);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < UP; ++u) {
+                const vf4 vv = HAS_E ? v[u] + ev[u] : v[u];
+                vf4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
+                const vf4 err = apply4<MODE>(vv, upd, nmp[u], mn[u], gmu_pos, neg_gmu_neg);
+                if (HAS_E)
+                    st4<NT>(reinterpret_cast<vf4 *>(tab.e[p0 + u]) + i, err);
+                const vf4 wn = wv[u] - eta * upd;
+                st4<NT>(reinterpret_cast<vf4 *>(wt.w[p0 + u]) + i, wn);
+            }
+        }
+        for (; p0 < P; ++p0) {
+            vf4 vv = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0]) + i);
+            if (HAS_E)
+                vv += ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0]) + i);
+            const vf4 wv = ld4<NT>(reinterpret_cast<const vf4 *>(wt.w[p0]) + i);
+            vf4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
+            const vf4 err = apply4<MODE>(vv, upd, neg_mu_pos[p0], mu_neg[p0], gmu_pos, neg_gmu_neg);
+            if (HAS_E)
+                st4<NT>(reinterpret_cast<vf4 *>(tab.e[p0]) + i, err);
+            const vf4 wn = wv - eta * upd;
+            st4<NT>(reinterpret_cast<vf4 *>(wt.w[p0]) + i, wn);
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
+        const uint64_t k = (nvec << 2) + tid;
+        for (uint32_t p = 0; p < P; ++p) {
+            float v = tab.g[p][k];
+            if (HAS_E)
+                v += tab.e[p][k];
+            const float u = apply1<MODE>(v, neg_mu_pos[p], mu_neg[p], gmu_pos, neg_gmu_neg);
+            if (HAS_E)
+                tab.e[p][k] = v;
+            wt.w[p][k] -= eta * u;
+        }
+    }
+}
+
+// Algorithm 1 lines 9-10 on replicas: the dense average of the gradients, applied to every w^p.
+template <bool NT, int UP, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_dense_step_replicas(const PtrTable tab, const ReplicaTable wt,
+                                                               const uint64_t n, const uint32_t P,
+                                                               const float eta_over_P)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint64_t nvec = n >> 2;
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * BLOCK + tid;
+    if (i < nvec) {
+        vf4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        uint32_t p0 = 0;
+        for (; p0 + UP <= P; p0 += UP) {
+            vf4 v[UP];
+#pragma unroll
+            for (int u = 0; u < UP; ++u)
+                v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + i);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < UP; ++u)
+                acc += v[u];
+        }
+        for (; p0 < P; ++p0)
+            acc += ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0]) + i);
+        const vf4 step = eta_over_P * acc;
+        p0 = 0;
+        for (; p0 + UP <= P; p0 += UP) {
+            vf4 wv[UP];
+#pragma unroll
+            for (int u = 0; u < UP; ++u)
+                wv[u] = ld4<NT>(reinterpret_cast<const vf4 *>(wt.w[p0 + u]) + i);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < UP; ++u) {
+                const vf4 wn = wv[u] - step;
+                st4<NT>(reinterpret_cast<vf4 *>(wt.w[p0 + u]) + i, wn);
+            }
+        }
+        for (; p0 < P; ++p0) {
+            const vf4 wn = ld4<NT>(reinterpret_cast<const vf4 *>(wt.w[p0]) + i) - step;
+            st4<NT>(reinterpret_cast<vf4 *>(wt.w[p0]) + i, wn);
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
+        const uint64_t k = (nvec << 2) + tid;
+        float a = 0.0f;
+        for (uint32_t p = 0; p < P; ++p)
+            a += tab.g[p][k];
+        for (uint32_t p = 0; p < P; ++p)
+            wt.w[p][k] -= eta_over_P * a;
+    }
+}
+
+// Replica drift, first level.  grid = (kDriftBlocks, P): block (b, p) strides over the elements and, for each,
+// forms the mean over all replicas in fp64 (p ascending) and worker p's deviation from it; the P blocks with
+// the same b read the same data, which the L2 serves.  Per block: max |deviation| and the fp64 sum of squares.
+__global__ __launch_bounds__(kBlock) void k_replica_drift(const ReplicaTable wt, const uint64_t n, const uint32_t P,
+                                                          double *__restrict__ max_part, double *__restrict__ sq_part)
+{
+    const uint32_t p = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
+    double mx = 0.0, sq = 0.0;
+    for (uint64_t i = static_cast<uint64_t>(b) * kBlock + tid; i < n; i += static_cast<uint64_t>(gridDim.x) * kBlock) {
+        double s = 0.0;
+        for (uint32_t q = 0; q < P; ++q)
+            s += static_cast<double>(wt.w[q][i]);
+        const double d = static_cast<double>(wt.w[p][i]) - s / static_cast<double>(P);
+        const double a = fabs(d);
+        mx = (a > mx || a != a) ? a : mx;
+        sq += d * d;
+    }
+    __shared__ double sh_mx[kBlock / 64], sh_sq[kBlock / 64];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const double o = __shfl_down(mx, off);
+        mx = (o > mx || o != o) ? o : mx;
+    }
+    sq = wave_sum(sq);
+    if ((tid & 63) == 0) {
+        sh_mx[tid >> 6] = mx;
+        sh_sq[tid >> 6] = sq;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double m = 0.0, t = 0.0;
+#pragma unroll
+        for (int k = 0; k < kBlock / 64; ++k) {
+            m = (sh_mx[k] > m || sh_mx[k] != sh_mx[k]) ? sh_mx[k] : m;
+            t += sh_sq[k];
+        }
+        max_part[static_cast<size_t>(p) * gridDim.x + b] = m;
+        sq_part[static_cast<size_t>(p) * gridDim.x + b] = t;
+    }
+}
+
+// Second level: one thread per worker walks that worker's records in index order.
+__global__ void k_replica_drift_finalize(const uint64_t n, const uint32_t P, const uint32_t B,
+                                         const double *__restrict__ max_part, const double *__restrict__ sq_part,
+                                         double *__restrict__ result)
+{
+    const uint32_t p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < P) {
+        double m = 0.0, t = 0.0;
+        for (uint32_t j = 0; j < B; ++j) {
+            const double x = max_part[static_cast<size_t>(p) * B + j];
+            m = (x > m || x != x) ? x : m;
+            t += sq_part[static_cast<size_t>(p) * B + j];
+        }
+        result[p] = m;
+        result[P + p] = sqrt(t / static_cast<double>(n));
+    }
+}
+
 // Test aid: pos(v) of Eq. 2 as one bit per element.  grid = (ceil(n / kBlock), P); a wavefront covers 64
 // consecutive elements, so its ballot is exactly one output word.
 template <bool HAS_E>
@@ -878,6 +1070,86 @@ hipError_t launch_fused_step(const a2sgd_plan_t &pl, const PtrTable &tab, bool h
                      : launch_fused_inst<A2SGD_MODE_ALG1_LITERAL, false>(pl, tab, w, eop, ws, token, s);
     return has_e ? launch_fused_inst<A2SGD_MODE_RETAINED_ERROR, true>(pl, tab, w, eop, ws, token, s)
                  : launch_fused_inst<A2SGD_MODE_RETAINED_ERROR, false>(pl, tab, w, eop, ws, token, s);
+}
+
+template <int MODE, bool HAS_E, bool NT>
+static hipError_t launch_apply_replicas_shape(const a2sgd_plan_t &pl, const PtrTable &tab, const ReplicaTable &wt,
+                                              float eta, const WsHeader *hdr, hipStream_t s)
+{
+    constexpr int kThreads = 64;
+    const uint64_t nvec = (pl.n + 3) >> 2;
+    const dim3 grid(static_cast<uint32_t>((nvec + kThreads - 1) / kThreads)), block(kThreads);
+    const uint32_t lds = pl.apply.lds_bytes;
+    // 3 loads per worker instead of 2: groups of 4 workers at most
+    if (pl.apply.up >= 4)
+        k_apply_replicas<MODE, HAS_E, NT, 4, kThreads><<<grid, block, lds, s>>>(tab, wt, pl.n, pl.P, eta, hdr);
+    else if (pl.apply.up == 2)
+        k_apply_replicas<MODE, HAS_E, NT, 2, kThreads><<<grid, block, lds, s>>>(tab, wt, pl.n, pl.P, eta, hdr);
+    else
+        k_apply_replicas<MODE, HAS_E, NT, 1, kThreads><<<grid, block, lds, s>>>(tab, wt, pl.n, pl.P, eta, hdr);
+    return hipGetLastError();
+}
+
+hipError_t launch_apply_replicas(const a2sgd_plan_t &pl, const PtrTable &tab, const ReplicaTable &wt, bool has_e,
+                                 float eta, void *ws, hipStream_t s)
+{
+    const WsHeader *hdr = static_cast<const WsHeader *>(ws);
+    const bool lit = pl.mode == A2SGD_MODE_ALG1_LITERAL;
+#define A2SGD_REPL_CASE(L, E, N)                                                                               \
+    if (lit == L && has_e == E && pl.streaming == N)                                                           \
+        return launch_apply_replicas_shape<L ? A2SGD_MODE_ALG1_LITERAL : A2SGD_MODE_RETAINED_ERROR, E, N>(      \
+            pl, tab, wt, eta, hdr, s);
+    A2SGD_REPL_CASE(false, true, true)
+    A2SGD_REPL_CASE(false, true, false)
+    A2SGD_REPL_CASE(false, false, true)
+    A2SGD_REPL_CASE(false, false, false)
+    A2SGD_REPL_CASE(true, true, true)
+    A2SGD_REPL_CASE(true, true, false)
+    A2SGD_REPL_CASE(true, false, true)
+    A2SGD_REPL_CASE(true, false, false)
+#undef A2SGD_REPL_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_dense_step_replicas(const a2sgd_plan_t &pl, const PtrTable &tab, const ReplicaTable &wt, float eta,
+                                      hipStream_t s)
+{
+    constexpr int kThreads = 64;
+    const float eop = static_cast<float>(static_cast<double>(eta) / static_cast<double>(pl.P));
+    const uint64_t nvec = (pl.n + 3) >> 2;
+    const dim3 grid(static_cast<uint32_t>((nvec + kThreads - 1) / kThreads)), block(kThreads);
+    const uint32_t lds = pl.apply.lds_bytes;
+    if (pl.streaming) {
+        if (pl.apply.up >= 4)
+            k_dense_step_replicas<true, 4, kThreads><<<grid, block, lds, s>>>(tab, wt, pl.n, pl.P, eop);
+        else
+            k_dense_step_replicas<true, 1, kThreads><<<grid, block, lds, s>>>(tab, wt, pl.n, pl.P, eop);
+    } else {
+        if (pl.apply.up >= 4)
+            k_dense_step_replicas<false, 4, kThreads><<<grid, block, lds, s>>>(tab, wt, pl.n, pl.P, eop);
+        else
+            k_dense_step_replicas<false, 1, kThreads><<<grid, block, lds, s>>>(tab, wt, pl.n, pl.P, eop);
+    }
+    return hipGetLastError();
+}
+
+size_t drift_result_offset(const a2sgd_plan_t &pl)
+{
+    return kHeaderBytes + 2ull * 8ull * pl.P * kDriftBlocks;
+}
+
+hipError_t launch_replica_drift(const a2sgd_plan_t &pl, const ReplicaTable &wt, void *ws, hipStream_t s)
+{
+    char *base = static_cast<char *>(ws) + kHeaderBytes;
+    double *max_part = reinterpret_cast<double *>(base);
+    double *sq_part = max_part + static_cast<size_t>(pl.P) * kDriftBlocks;
+    double *result = reinterpret_cast<double *>(static_cast<char *>(ws) + drift_result_offset(pl));
+    k_replica_drift<<<dim3(kDriftBlocks, pl.P), dim3(kBlock), 0, s>>>(wt, pl.n, pl.P, max_part, sq_part);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess)
+        return err;
+    k_replica_drift_finalize<<<dim3(1), dim3(64), 0, s>>>(pl.n, pl.P, kDriftBlocks, max_part, sq_part, result);
+    return hipGetLastError();
 }
 
 hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, uint64_t *mask, hipStream_t s)

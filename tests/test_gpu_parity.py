@@ -289,3 +289,59 @@ def test_runs_on_a_side_stream_and_respects_stream_order(A):
     s.synchronize()
     compare_stats(st, gmu, ref)
     assert_array_close(wd.cpu().numpy(), ref.w_new, "w")
+
+
+@pytest.mark.parametrize("n,P", [(1, 1), (5, 2), (1023, 3), (4099, 4), (65_539, 5), (300_001, 8), (70_001, 17)])
+def test_replicas(A, n, P):
+    """One weight vector per worker (Algorithm 1 line 7 as printed), the final synchronisation on replicas and the
+    drift diagnostic, against the oracle; and the mean of the replicas against the shared-weight path."""
+    g, e, w = make_case(n * 3 + P, n, P)
+    rng = np.random.default_rng(n + P)
+    wr = [(w + (rng.standard_normal(n) * 1e-3).astype(f32)) for _ in range(P)]
+    for mode in (0, 1):
+        plan = A.a2sgd_plan(n, P, mode)
+        ws = A.alloc_workspace(plan)
+        gd, ed, wd = [dev(x) for x in g], [dev(x) for x in e], [dev(x) for x in wr]
+        A.a2sgd_step_replicas(plan, gd, ed, wd, 0.1, ws)
+        stats, gmu = A.a2sgd_read_stats(plan, ws)
+        workers, gmu_ref, e_ref, w_ref = O.step_replicas(g, e, wr, 0.1, mode)
+        compare_stats(stats, gmu, O.StepResult(workers, gmu_ref[0], gmu_ref[1], [], np.empty(0, f32), []))
+        for p in range(P):
+            assert_array_close(ed[p].cpu().numpy(), e_ref[p], f"e[{p}]")
+            assert_array_close(wd[p].cpu().numpy(), w_ref[p], f"w[{p}]")
+        # the replica mean moves like the single weight vector of the shared path
+        w_mean0 = np.mean(np.stack(wr).astype(np.float64), axis=0).astype(f32)
+        _, _, _, w_shared, _ = gpu_step(A, g, e, w_mean0, 0.1, mode)
+        got = np.mean(np.stack([x.cpu().numpy() for x in wd]).astype(np.float64), axis=0)
+        assert np.allclose(got - w_mean0, w_shared.astype(np.float64) - w_mean0, rtol=0, atol=3e-8)
+        # drift diagnostic
+        mx, rms = A.a2sgd_replica_drift(plan, wd, ws)
+        mx_ref, rms_ref = O.replica_drift([x.cpu().numpy() for x in wd])
+        assert np.allclose(mx, mx_ref, rtol=1e-12, atol=0) and np.allclose(rms, rms_ref, rtol=1e-9, atol=1e-300)
+        # final synchronisation (Algorithm 1 lines 9-10) applied to every replica
+        before = [x.cpu().numpy() for x in wd]
+        A.a2sgd_dense_step_replicas(plan, gd, wd, 0.05)
+        ref = O.dense_step_replicas(g, before, 0.05)
+        for p in range(P):
+            assert_array_close(wd[p].cpu().numpy(), ref[p], f"dense w[{p}]")
+
+
+def test_replicas_full_size_config2(A):
+    """Config 2 shape (25.6 M parameters, 8 workers) on device-generated inputs: the replica mean against the
+    shared path, elementwise, and identical errors."""
+    wl = workloads.config2()
+    n, P = wl.n, wl.num_workers
+    plan = A.a2sgd_plan(n, P, 0)
+    ws = A.alloc_workspace(plan)
+    g = [wl.gradient(p, 0, device="cuda") for p in range(P)]
+    e1 = [wl.synthetic_error(p, device="cuda") for p in range(P)]
+    e2 = [x.clone() for x in e1]
+    w = wl.weights(device="cuda")
+    wr = [w.clone() for _ in range(P)]
+    A.a2sgd_step(plan, g, e1, w, wl.eta, ws)
+    A.a2sgd_step_replicas(plan, g, e2, wr, wl.eta, ws)
+    assert all(torch.equal(a, b) for a, b in zip(e1, e2))
+    mean = torch.stack([x.double() for x in wr]).mean(dim=0)
+    assert float((mean - w.double()).abs().max()) <= 1e-8
+    mx, rms = A.a2sgd_replica_drift(plan, wr, ws)
+    assert all(0 < r < m < 1e-2 for m, r in zip(mx, rms))

@@ -43,6 +43,11 @@ def test_streaming_apply_stores_are_all_write_through_non_temporal(asm):
         assert stores, name
         bad = [s for s in stores if not s.rstrip().endswith(" sc1 nt")]
         assert not bad, f"{name}: {len(bad)} of {len(stores)} 128-bit stores are not write-through non-temporal"
+        # every hand-written store is followed by its two wait states (store-data hazard)
+        lines = [l.strip() for l in body.splitlines() if l.strip() and not l.strip().startswith(";")]
+        for k, l in enumerate(lines):
+            if l.startswith("global_store_dwordx4") and l.endswith(" sc1 nt"):
+                assert lines[k + 1].startswith("s_nop 1"), f"{name}: store without its wait states"
 
 
 def test_streaming_reduction_loads_are_non_temporal_and_batched(asm):
