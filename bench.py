@@ -159,6 +159,21 @@ def main() -> int:
     out["dense_step"] = {"ms": ms_dense, "gbps": (4 * n * P + 8 * n) / (ms_dense * 1e-3) / 1e9,
                          "params_per_s": n / (ms_dense * 1e-3)}
 
+    # Also outside the timed region: the same step on the lazy error state (16nP + 8n bytes: the buffers keep v and
+    # the error is formed on the next read).  Same results bit for bit; a different contract for what e holds.
+    A.a2sgd_lazy_reset(plan, ws)
+    for _ in range(2):
+        A.a2sgd_lazy_step(plan, g, e, w, wl.eta, ws)
+    ev0.record()
+    for _ in range(5):
+        A.a2sgd_lazy_step(plan, g, e, w, wl.eta, ws)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_lazy = ev0.elapsed_time(ev1) / 5
+    A.a2sgd_lazy_materialize(plan, e, ws)
+    out["lazy_step"] = {"ms": ms_lazy, "gbps": (16 * n * P + 8 * n) / (ms_lazy * 1e-3) / 1e9,
+                        "params_per_s": n / (ms_lazy * 1e-3)}
+
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, g, w, min(args.cpu_sample, n))
     print(json.dumps(out))

@@ -164,6 +164,29 @@ a2sgd_status_t a2sgd_dense_step_replicas(const a2sgd_plan_t *plan, const float *
 a2sgd_status_t a2sgd_replica_drift(const a2sgd_plan_t *plan, const float *const *w, void *workspace,
                                    a2sgd_stream_t stream, double *out_max_abs, double *out_rms);
 
+/* ---- Lazy error state: the same step with 16nP + 8n bytes of traffic instead of 20nP + 8n ------------------
+ * Between lazy steps worker p's buffer s^p holds the folded vector v^p of the last step instead of the error,
+ * and the workspace carries that step's local means; the error is e^p_i = fl32(s^p_i - enc(s^p)_i) with those
+ * means (Eq. 2), and it is formed on the fly when the next step reads the buffer.  The reduction pass then reads
+ * g and s and writes the new v into s (12 bytes per element and worker); the apply pass only reads s for the
+ * sign groups and updates w (4 bytes per element and worker plus 8 per parameter); nothing else differs: w, the
+ * means and the counts are bit-identical to a2sgd_step's, and so are the errors once materialised.
+ * A workspace in lazy use carries state: between a2sgd_lazy_reset and a2sgd_lazy_materialize it must see no other
+ * calls than a2sgd_lazy_step and a2sgd_read_stats.  Both plan modes are supported; s is required. */
+
+/* Declares that the buffers that will be passed as s hold true errors (for a fresh run: zeros): clears the local
+ * means carried in the workspace.  Call once before the first a2sgd_lazy_step on a workspace. */
+a2sgd_status_t a2sgd_lazy_reset(const a2sgd_plan_t *plan, void *workspace, a2sgd_stream_t stream);
+
+/* One step of Algorithm 1's loop body (lines 3-7) on the lazy state. */
+a2sgd_status_t a2sgd_lazy_step(const a2sgd_plan_t *plan, const float *const *g, float *const *s, float *w, float eta,
+                               void *workspace, a2sgd_stream_t stream);
+
+/* Turns the lazy state back into true errors, in place: s^p <- fl32(s^p - enc(s^p)), and clears the carried
+ * means (so the buffers may go on as s, or be handed to a2sgd_step as e).  For checkpoints and hand-over. */
+a2sgd_status_t a2sgd_lazy_materialize(const a2sgd_plan_t *plan, float *const *s, void *workspace,
+                                      a2sgd_stream_t stream);
+
 /* Geometry the plan chose, for reports: blocks per worker of the first-level reduction. */
 uint32_t a2sgd_plan_blocks_per_worker(const a2sgd_plan_t *plan);
 

@@ -59,12 +59,16 @@ def _load():
     L.a2sgd_step_replicas.argtypes = [vp, tab, tab, tab, C.c_float, vp, vp]
     L.a2sgd_dense_step_replicas.argtypes = [vp, tab, tab, C.c_float, vp]
     L.a2sgd_replica_drift.argtypes = [vp, tab, vp, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    L.a2sgd_lazy_reset.argtypes = [vp, vp, vp]
+    L.a2sgd_lazy_step.argtypes = [vp, tab, tab, vp, C.c_float, vp, vp]
+    L.a2sgd_lazy_materialize.argtypes = [vp, tab, vp, vp]
     L.a2sgd_status_string.argtypes = [C.c_int]
     L.a2sgd_status_string.restype = C.c_char_p
     for name in ("a2sgd_plan", "a2sgd_plan_destroy", "a2sgd_local_averages", "a2sgd_global_average",
                  "a2sgd_apply_and_update_error", "a2sgd_step", "a2sgd_read_stats", "a2sgd_export_mask",
                  "a2sgd_dense_step", "a2sgd_apply_and_update_error_replicas", "a2sgd_step_replicas",
-                 "a2sgd_dense_step_replicas", "a2sgd_replica_drift"):
+                 "a2sgd_dense_step_replicas", "a2sgd_replica_drift", "a2sgd_lazy_reset", "a2sgd_lazy_step",
+                 "a2sgd_lazy_materialize"):
         getattr(L, name).restype = C.c_int
     return L
 
@@ -226,3 +230,18 @@ def a2sgd_replica_drift(plan: Plan, w, workspace: torch.Tensor, stream=None):
     _check(raw.a2sgd_replica_drift(plan.handle, _table(plan, w, "w"), _workspace(plan, workspace), _stream(stream),
                                    mx, rms), "a2sgd_replica_drift")
     return list(mx), list(rms)
+
+
+def a2sgd_lazy_reset(plan: Plan, workspace: torch.Tensor, stream=None) -> None:
+    _check(raw.a2sgd_lazy_reset(plan.handle, _workspace(plan, workspace), _stream(stream)), "a2sgd_lazy_reset")
+
+
+def a2sgd_lazy_step(plan: Plan, g, s, w: torch.Tensor, eta: float, workspace: torch.Tensor, stream=None) -> None:
+    _check(raw.a2sgd_lazy_step(plan.handle, _table(plan, g, "g"), _table(plan, s, "s"),
+                               _dev_ptr(w, plan.n, torch.float32, "w"), C.c_float(eta), _workspace(plan, workspace),
+                               _stream(stream)), "a2sgd_lazy_step")
+
+
+def a2sgd_lazy_materialize(plan: Plan, s, workspace: torch.Tensor, stream=None) -> None:
+    _check(raw.a2sgd_lazy_materialize(plan.handle, _table(plan, s, "s"), _workspace(plan, workspace),
+                                      _stream(stream)), "a2sgd_lazy_materialize")

@@ -369,6 +369,60 @@ a2sgd_status_t a2sgd_replica_drift(const a2sgd_plan_t *plan, const float *const 
     return A2SGD_OK;
 }
 
+a2sgd_status_t a2sgd_lazy_reset(const a2sgd_plan_t *plan, void *workspace, a2sgd_stream_t stream)
+{
+    if (plan == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    a2sgd_status_t st = check_buffer(workspace);
+    if (st != A2SGD_OK)
+        return st;
+    return dev(launch_lazy_reset(*plan, workspace, static_cast<hipStream_t>(stream)));
+}
+
+a2sgd_status_t a2sgd_lazy_step(const a2sgd_plan_t *plan, const float *const *g, float *const *s, float *w, float eta,
+                               void *workspace, a2sgd_stream_t stream)
+{
+    if (plan == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    bool has_g = false, has_s = false;
+    a2sgd_status_t st = check_table(g, plan->P, true, &has_g);
+    if (st != A2SGD_OK)
+        return st;
+    if ((st = check_table(s, plan->P, true, &has_s)) != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(w)) != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(workspace)) != A2SGD_OK)
+        return st;
+    PtrTable tab;
+    fill_table(tab, plan->P, g, s);
+    plan->last_token = 0;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    if ((st = dev(launch_lazy_partials(*plan, tab, workspace, hs))) != A2SGD_OK)
+        return st;
+    if ((st = dev(launch_local_finalize(*plan, workspace, hs))) != A2SGD_OK)
+        return st;
+    if ((st = dev(launch_global_average(*plan, workspace, hs))) != A2SGD_OK)
+        return st;
+    return dev(launch_lazy_apply(*plan, tab, w, eta, workspace, hs));
+}
+
+a2sgd_status_t a2sgd_lazy_materialize(const a2sgd_plan_t *plan, float *const *s, void *workspace,
+                                      a2sgd_stream_t stream)
+{
+    if (plan == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    bool has_s = false;
+    a2sgd_status_t st = check_table(s, plan->P, true, &has_s);
+    if (st != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(workspace)) != A2SGD_OK)
+        return st;
+    PtrTable tab;
+    fill_table(tab, plan->P, s, s);
+    return dev(launch_lazy_materialize(*plan, tab, workspace, static_cast<hipStream_t>(stream)));
+}
+
 const char *a2sgd_status_string(a2sgd_status_t status)
 {
     switch (status) {

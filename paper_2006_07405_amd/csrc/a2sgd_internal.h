@@ -104,6 +104,10 @@ hipError_t launch_dense_step_replicas(const a2sgd_plan_t &pl, const PtrTable &ta
 // Writes 2 * P doubles (max_abs[P], then rms[P]) at ws + drift_result_offset(pl).
 hipError_t launch_replica_drift(const a2sgd_plan_t &pl, const ReplicaTable &wt, void *ws, hipStream_t s);
 size_t drift_result_offset(const a2sgd_plan_t &pl);
+hipError_t launch_lazy_reset(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
+hipError_t launch_lazy_partials(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s);
+hipError_t launch_lazy_apply(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eta, void *ws, hipStream_t s);
+hipError_t launch_lazy_materialize(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s);
 hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, uint64_t *mask, hipStream_t s);
 hipError_t launch_dense_step(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eta, hipStream_t s);
 

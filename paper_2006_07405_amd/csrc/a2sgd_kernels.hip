@@ -931,6 +931,190 @@ __global__ void k_replica_drift_finalize(const uint64_t n, const uint32_t P, con
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Lazy error state: the buffer keeps the folded vector v of the last step, the header keeps that step's local
+// means, and e = v - enc(v) (Eq. 2, Algorithm 1 line 4) is formed when the buffer is next read
+// ---------------------------------------------------------------------------------------------------------
+
+// The pending error of one stored element: s - enc(s) with the carried means.  A NaN stays a NaN.
+__device__ __forceinline__ float pending_error(float s, float neg_mu_pos, float mu_neg)
+{
+    return s + (s >= 0.0f ? neg_mu_pos : mu_neg);
+}
+
+__device__ __forceinline__ vf4 pending_error4(vf4 s, float neg_mu_pos, float mu_neg)
+{
+    return vf4{pending_error(s.x, neg_mu_pos, mu_neg), pending_error(s.y, neg_mu_pos, mu_neg),
+               pending_error(s.z, neg_mu_pos, mu_neg), pending_error(s.w, neg_mu_pos, mu_neg)};
+}
+
+// Reduction pass on the lazy state.  Same grid, tiling and combination order as k_local_partials; each element
+// is e = pending error of the stored value, v = fl32(g + e), v is written back in place of the stored value and
+// enters the sums and counts.  tab.e holds the state buffers.  8 bytes read and 4 written per element-worker.
+template <bool NT>
+__global__ __launch_bounds__(kBlock) void k_lazy_partials(const PtrTable tab, const uint64_t n, const uint32_t B,
+                                                          const WsHeader *__restrict__ hdr, Partials out)
+{
+    const uint32_t p = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
+    const float *__restrict__ g = tab.g[p];
+    float *s = tab.e[p];
+    const vf4 *__restrict__ g4 = reinterpret_cast<const vf4 *>(g);
+    vf4 *s4 = reinterpret_cast<vf4 *>(s);
+    const float nmp = hdr->neg_mu_pos[p], mn = hdr->mu_neg[p];  // the means of the step that stored the values
+
+    const uint64_t nvec = n >> 2;
+    constexpr uint64_t kTile = static_cast<uint64_t>(kBlock) * kReduceUnroll;
+    const uint64_t ntile = nvec / kTile;
+
+    LaneAcc acc;
+    for (uint64_t t = b; t < ntile; t += B) {
+        const uint64_t base = t * kTile + tid;
+        vf4 gv[kReduceUnroll], sv[kReduceUnroll];
+#pragma unroll
+        for (int u = 0; u < kReduceUnroll; ++u)
+            gv[u] = ld4<NT>(g4 + base + u * kBlock);
+#pragma unroll
+        for (int u = 0; u < kReduceUnroll; ++u)
+            sv[u] = ld4<NT>(s4 + base + u * kBlock);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < kReduceUnroll; ++u) {
+            const vf4 v = gv[u] + pending_error4(sv[u], nmp, mn);
+            st4<NT>(s4 + base + u * kBlock, v);
+            acc.add4(v);
+        }
+        acc.flush();
+    }
+    for (uint64_t i = ntile * kTile + static_cast<uint64_t>(b) * kBlock + tid; i < nvec;
+         i += static_cast<uint64_t>(B) * kBlock) {
+        const vf4 v = ld4<NT>(g4 + i) + pending_error4(ld4<NT>(s4 + i), nmp, mn);
+        st4<NT>(s4 + i, v);
+        acc.add4(v);
+        acc.flush();
+    }
+    if (b == 0 && tid < (n & 3)) {
+        const uint64_t i = (nvec << 2) + tid;
+        const float v = g[i] + pending_error(s[i], nmp, mn);
+        s[i] = v;
+        acc.add(v);
+        acc.flush();
+    }
+
+    __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
+    __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
+    const double wp = wave_sum(acc.s_pos), wn = wave_sum(acc.s_neg);
+    const uint32_t lane = tid & 63, wave = tid >> 6;
+    if (lane == 0) {
+        sh_pos[wave] = wp;
+        sh_neg[wave] = wn;
+        sh_cp[wave] = acc.c_pos;
+        sh_cn[wave] = acc.c_neg;
+        sh_cz[wave] = acc.c_zero;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double sp = 0.0, sn = 0.0;
+        uint64_t cp = 0, cn = 0, cz = 0;
+#pragma unroll
+        for (int k = 0; k < kBlock / 64; ++k) {
+            sp += sh_pos[k];
+            sn += sh_neg[k];
+            cp += sh_cp[k];
+            cn += sh_cn[k];
+            cz += sh_cz[k];
+        }
+        const size_t slot = static_cast<size_t>(p) * B + b;
+        out.s_pos[slot] = sp;
+        out.s_neg[slot] = sn;
+        out.n_pos[slot] = cp;
+        out.n_neg[slot] = cn;
+        out.n_zero[slot] = cz;
+    }
+}
+
+// Apply pass on the lazy state: the buffers already hold v, so all that is left of Algorithm 1 lines 6-7 is to
+// read each worker's v for its sign group (and, in literal mode, its error) and update w.  Shape of k_apply:
+// single-wavefront workgroups launched once, one float4 group per thread, UP workers' loads issued together.
+template <int MODE, bool NT, int UP, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_lazy_apply(const PtrTable tab, float *__restrict__ w, const uint64_t n,
+                                                      const uint32_t P, const float eta_over_P,
+                                                      const WsHeader *__restrict__ hdr)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lz = opaque_zero();
+    const float *neg_mu_pos = hdr->neg_mu_pos + lz, *mu_neg = hdr->mu_neg + lz;
+    const float gmu_pos = (&hdr->gmu_pos)[lz];
+    const float neg_gmu_neg = -(&hdr->gmu_neg)[lz];
+    const uint64_t nvec = n >> 2;
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * BLOCK + tid;
+    if (i < nvec) {
+        vf4 *w4 = reinterpret_cast<vf4 *>(w) + i;
+        const vf4 wv = ld4<NT>(w4);
+        vf4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        uint32_t p0 = 0;
+        for (; p0 + UP <= P; p0 += UP) {
+            vf4 v[UP];
+            float nmp[UP], mn[UP];
+#pragma unroll
+            for (int u = 0; u < UP; ++u) {
+                nmp[u] = neg_mu_pos[p0 + u];
+                mn[u] = mu_neg[p0 + u];
+            }
+#pragma unroll
+            for (int u = 0; u < UP; ++u)
+                v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0 + u]) + i);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < UP; ++u)
+                (void)apply4<MODE>(v[u], acc, nmp[u], mn[u], gmu_pos, neg_gmu_neg);
+        }
+        for (; p0 < P; ++p0)
+            (void)apply4<MODE>(ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0]) + i), acc, neg_mu_pos[p0], mu_neg[p0],
+                               gmu_pos, neg_gmu_neg);
+        const vf4 wn = wv - eta_over_P * acc;
+        st4<NT>(w4, wn);
+    }
+    if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
+        const uint64_t k = (nvec << 2) + tid;
+        float a = 0.0f;
+        for (uint32_t p = 0; p < P; ++p) {
+            float v = tab.e[p][k];
+            a += apply1<MODE>(v, neg_mu_pos[p], mu_neg[p], gmu_pos, neg_gmu_neg);
+        }
+        w[k] -= eta_over_P * a;
+    }
+}
+
+// s <- pending error of s, in place, for every worker: grid = (blocks, P), grid-stride over float4 groups.
+template <bool NT>
+__global__ __launch_bounds__(kBlock) void k_lazy_materialize(const PtrTable tab, const uint64_t n,
+                                                             const WsHeader *__restrict__ hdr)
+{
+    const uint32_t p = blockIdx.y, tid = threadIdx.x;
+    float *s = tab.e[p];
+    vf4 *s4 = reinterpret_cast<vf4 *>(s);
+    const float nmp = hdr->neg_mu_pos[p], mn = hdr->mu_neg[p];
+    const uint64_t nvec = n >> 2;
+    for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * kBlock + tid; i < nvec;
+         i += static_cast<uint64_t>(gridDim.x) * kBlock) {
+        const vf4 e = pending_error4(ld4<NT>(s4 + i), nmp, mn);
+        st4<NT>(s4 + i, e);
+    }
+    if (blockIdx.x == 0 && tid < (n & 3)) {
+        const uint64_t i = (nvec << 2) + tid;
+        s[i] = pending_error(s[i], nmp, mn);
+    }
+}
+
+// Clears the carried means: from here on the buffers are read as true errors.
+__global__ void k_lazy_reset(WsHeader *__restrict__ hdr)
+{
+    for (uint32_t p = threadIdx.x; p < kMaxWorkers; p += blockDim.x) {
+        hdr->neg_mu_pos[p] = 0.0f;
+        hdr->mu_neg[p] = 0.0f;
+    }
+}
+
 // Test aid: pos(v) of Eq. 2 as one bit per element.  grid = (ceil(n / kBlock), P); a wavefront covers 64
 // consecutive elements, so its ballot is exactly one output word.
 template <bool HAS_E>
@@ -1150,6 +1334,72 @@ hipError_t launch_replica_drift(const a2sgd_plan_t &pl, const ReplicaTable &wt, 
         return err;
     k_replica_drift_finalize<<<dim3(1), dim3(64), 0, s>>>(pl.n, pl.P, kDriftBlocks, max_part, sq_part, result);
     return hipGetLastError();
+}
+
+hipError_t launch_lazy_reset(const a2sgd_plan_t &, void *ws, hipStream_t s)
+{
+    k_lazy_reset<<<dim3(1), dim3(64), 0, s>>>(static_cast<WsHeader *>(ws));
+    return hipGetLastError();
+}
+
+hipError_t launch_lazy_partials(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s)
+{
+    const dim3 grid(pl.B, pl.P), block(kBlock);
+    const Partials out = partials_of(ws, pl.P, pl.B);
+    const WsHeader *hdr = static_cast<const WsHeader *>(ws);
+    if (pl.streaming)
+        k_lazy_partials<true><<<grid, block, 0, s>>>(tab, pl.n, pl.B, hdr, out);
+    else
+        k_lazy_partials<false><<<grid, block, 0, s>>>(tab, pl.n, pl.B, hdr, out);
+    return hipGetLastError();
+}
+
+template <int MODE, bool NT>
+static hipError_t launch_lazy_apply_shape(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eop,
+                                          const WsHeader *hdr, hipStream_t s)
+{
+    constexpr int kThreads = 64;
+    const uint64_t nvec = (pl.n + 3) >> 2;
+    const dim3 grid(static_cast<uint32_t>((nvec + kThreads - 1) / kThreads)), block(kThreads);
+    // up + 1 loads in flight per thread, about half of what the eager apply pass has: about twice as many
+    // workgroups per CU (same 160 KiB of LDS, a smaller request)
+    const uint32_t lds = pl.apply.lds_bytes ? pl.apply.lds_bytes / 2 + 3 * 1024 : 0;
+    switch (pl.apply.up) {
+    case 8: k_lazy_apply<MODE, NT, 8, kThreads><<<grid, block, lds, s>>>(tab, w, pl.n, pl.P, eop, hdr); break;
+    case 4: k_lazy_apply<MODE, NT, 4, kThreads><<<grid, block, lds, s>>>(tab, w, pl.n, pl.P, eop, hdr); break;
+    case 2: k_lazy_apply<MODE, NT, 2, kThreads><<<grid, block, lds, s>>>(tab, w, pl.n, pl.P, eop, hdr); break;
+    default: k_lazy_apply<MODE, NT, 1, kThreads><<<grid, block, lds, s>>>(tab, w, pl.n, pl.P, eop, hdr); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_lazy_apply(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eta, void *ws, hipStream_t s)
+{
+    const float eop = static_cast<float>(static_cast<double>(eta) / static_cast<double>(pl.P));
+    const WsHeader *hdr = static_cast<const WsHeader *>(ws);
+    if (pl.mode == A2SGD_MODE_ALG1_LITERAL)
+        return pl.streaming ? launch_lazy_apply_shape<A2SGD_MODE_ALG1_LITERAL, true>(pl, tab, w, eop, hdr, s)
+                            : launch_lazy_apply_shape<A2SGD_MODE_ALG1_LITERAL, false>(pl, tab, w, eop, hdr, s);
+    return pl.streaming ? launch_lazy_apply_shape<A2SGD_MODE_RETAINED_ERROR, true>(pl, tab, w, eop, hdr, s)
+                        : launch_lazy_apply_shape<A2SGD_MODE_RETAINED_ERROR, false>(pl, tab, w, eop, hdr, s);
+}
+
+hipError_t launch_lazy_materialize(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s)
+{
+    const uint64_t nvec = (pl.n + 3) >> 2;
+    uint64_t blocks = (nvec + kBlock - 1) / kBlock;
+    if (blocks > 2048)
+        blocks = 2048;
+    const dim3 grid(static_cast<uint32_t>(blocks), pl.P), block(kBlock);
+    const WsHeader *hdr = static_cast<const WsHeader *>(ws);
+    if (pl.streaming)
+        k_lazy_materialize<true><<<grid, block, 0, s>>>(tab, pl.n, hdr);
+    else
+        k_lazy_materialize<false><<<grid, block, 0, s>>>(tab, pl.n, hdr);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess)
+        return err;
+    return launch_lazy_reset(pl, ws, s);
 }
 
 hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, uint64_t *mask, hipStream_t s)

@@ -345,3 +345,47 @@ def test_replicas_full_size_config2(A):
     assert float((mean - w.double()).abs().max()) <= 1e-8
     mx, rms = A.a2sgd_replica_drift(plan, wr, ws)
     assert all(0 < r < m < 1e-2 for m, r in zip(mx, rms))
+
+
+@pytest.mark.parametrize("n,P,mode", [(1, 1, 0), (7, 2, 0), (4099, 3, 1), (65_539, 4, 0), (300_001, 8, 1), (50_001, 17, 0),
+                                      (2_000_003, 4, 0)])
+def test_lazy_error_state(A, n, P, mode):
+    """Five steps on the lazy state (buffers hold v, the error is formed on the next read) against five eager
+    steps of the oracle and of the GPU: same w and statistics at every step, same errors once materialised."""
+    wl = workloads.config1(n=n, num_workers=P)
+    rng = np.random.default_rng(n)
+    e0 = [(rng.standard_normal(n) * 4e-4).astype(f32) for _ in range(P)]  # start from a nonzero true error
+    w0 = wl.weights().numpy()
+    plan = A.a2sgd_plan(n, P, mode)
+    ws_l, ws_e = A.alloc_workspace(plan), A.alloc_workspace(plan)
+    s = [dev(x) for x in e0]
+    w_l = dev(w0)
+    e_g = [dev(x) for x in e0]
+    w_g = dev(w0)
+    e_o, w_o = [x.copy() for x in e0], w0.copy()
+    A.a2sgd_lazy_reset(plan, ws_l)
+    for t in range(5):
+        g = [wl.gradient(p, t).numpy() for p in range(P)]
+        gd = [dev(x) for x in g]
+        ref = O.step(g, e_o, w_o, wl.eta, mode)
+        A.a2sgd_lazy_step(plan, gd, s, w_l, wl.eta, ws_l)
+        st, gmu = A.a2sgd_read_stats(plan, ws_l)
+        compare_stats(st, gmu, ref)
+        assert_array_close(w_l.cpu().numpy(), ref.w_new, f"step {t} w (lazy)")
+        # the eager GPU path from the same state, three passes with the same reduction geometry: bit-identical
+        A.a2sgd_local_averages(plan, gd, e_g, ws_e)
+        A.a2sgd_global_average(plan, ws_e)
+        A.a2sgd_apply_and_update_error(plan, gd, e_g, w_g, wl.eta, ws_e)
+        assert torch.equal(w_l, w_g), f"step {t}: lazy and eager weights differ"
+        e_o, w_o = ref.e_new, ref.w_new
+    A.a2sgd_lazy_materialize(plan, s, ws_l)
+    for p in range(P):
+        assert_array_close(s[p].cpu().numpy(), e_o[p], f"materialised e[{p}]")
+        assert torch.equal(s[p], e_g[p]), f"materialised error of worker {p} differs from the eager path's"
+    # after materialising, the buffers are true errors again: one more lazy step and one more eager step agree
+    g = [wl.gradient(p, 5, device="cuda") for p in range(P)]
+    A.a2sgd_lazy_step(plan, g, s, w_l, wl.eta, ws_l)
+    A.a2sgd_local_averages(plan, g, e_g, ws_e)
+    A.a2sgd_global_average(plan, ws_e)
+    A.a2sgd_apply_and_update_error(plan, g, e_g, w_g, wl.eta, ws_e)
+    assert torch.equal(w_l, w_g)
