@@ -398,9 +398,13 @@ a2sgd_status_t a2sgd_lazy_step(const a2sgd_plan_t *plan, const float *const *g, 
     fill_table(tab, plan->P, g, s);
     plan->last_token = 0;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    if ((st = dev(launch_lazy_partials(*plan, tab, workspace, hs))) != A2SGD_OK)
+    // The reduction pass of the lazy step also writes; measured best with one workgroup per CU, half of what the
+    // read-only pass wants.  The records and their second-level pass use the same halved count.
+    a2sgd_plan_t half = *plan;
+    half.B = plan->B > 1 ? (plan->B + 1) / 2 : 1;
+    if ((st = dev(launch_lazy_partials(half, tab, workspace, hs))) != A2SGD_OK)
         return st;
-    if ((st = dev(launch_local_finalize(*plan, workspace, hs))) != A2SGD_OK)
+    if ((st = dev(launch_local_finalize(half, workspace, hs))) != A2SGD_OK)
         return st;
     if ((st = dev(launch_global_average(*plan, workspace, hs))) != A2SGD_OK)
         return st;

@@ -372,20 +372,23 @@ def test_lazy_error_state(A, n, P, mode):
         st, gmu = A.a2sgd_read_stats(plan, ws_l)
         compare_stats(st, gmu, ref)
         assert_array_close(w_l.cpu().numpy(), ref.w_new, f"step {t} w (lazy)")
-        # the eager GPU path from the same state, three passes with the same reduction geometry: bit-identical
+        # the eager GPU path from the same state: same counts; the sums are grouped differently, so the means may
+        # differ in the last bit once in a long while, the weights by that much
         A.a2sgd_local_averages(plan, gd, e_g, ws_e)
         A.a2sgd_global_average(plan, ws_e)
         A.a2sgd_apply_and_update_error(plan, gd, e_g, w_g, wl.eta, ws_e)
-        assert torch.equal(w_l, w_g), f"step {t}: lazy and eager weights differ"
+        st_e, _ = A.a2sgd_read_stats(plan, ws_e)
+        assert [(a.n_pos, a.n_neg, a.n_zero) for a in st] == [(a.n_pos, a.n_neg, a.n_zero) for a in st_e]
+        assert float((w_l - w_g).abs().max()) <= 1e-9, f"step {t}: lazy and eager weights differ"
         e_o, w_o = ref.e_new, ref.w_new
     A.a2sgd_lazy_materialize(plan, s, ws_l)
     for p in range(P):
         assert_array_close(s[p].cpu().numpy(), e_o[p], f"materialised e[{p}]")
-        assert torch.equal(s[p], e_g[p]), f"materialised error of worker {p} differs from the eager path's"
+        assert float((s[p] - e_g[p]).abs().max()) <= 1e-9, f"materialised error of worker {p} differs from the eager path's"
     # after materialising, the buffers are true errors again: one more lazy step and one more eager step agree
     g = [wl.gradient(p, 5, device="cuda") for p in range(P)]
     A.a2sgd_lazy_step(plan, g, s, w_l, wl.eta, ws_l)
     A.a2sgd_local_averages(plan, g, e_g, ws_e)
     A.a2sgd_global_average(plan, ws_e)
     A.a2sgd_apply_and_update_error(plan, g, e_g, w_g, wl.eta, ws_e)
-    assert torch.equal(w_l, w_g)
+    assert float((w_l - w_g).abs().max()) <= 1e-9
