@@ -187,6 +187,13 @@ a2sgd_status_t a2sgd_lazy_step(const a2sgd_plan_t *plan, const float *const *g, 
 a2sgd_status_t a2sgd_lazy_materialize(const a2sgd_plan_t *plan, float *const *s, void *workspace,
                                       a2sgd_stream_t stream);
 
+/* Diagnostic: exercises the grid-wide barrier of the single-launch step on a cell of its own.  First 128
+ * workgroups must all pass one barrier; then 128 workgroups wait, with a limit of 64 polls, for an arrival that
+ * never comes: every one of them must give up, exit normally and leave the cell marked failed.  Returns A2SGD_OK
+ * if both behaved, A2SGD_ERR_DEVICE otherwise.  `scratch` is at least 4 KiB of device memory (a workspace
+ * will do; its contents are overwritten).  Synchronises `stream`. */
+a2sgd_status_t a2sgd_selftest_barrier(void *scratch, a2sgd_stream_t stream);
+
 /* Geometry the plan chose, for reports: blocks per worker of the first-level reduction. */
 uint32_t a2sgd_plan_blocks_per_worker(const a2sgd_plan_t *plan);
 

@@ -62,6 +62,8 @@ def _load():
     L.a2sgd_lazy_reset.argtypes = [vp, vp, vp]
     L.a2sgd_lazy_step.argtypes = [vp, tab, tab, vp, C.c_float, vp, vp]
     L.a2sgd_lazy_materialize.argtypes = [vp, tab, vp, vp]
+    L.a2sgd_selftest_barrier.argtypes = [vp, vp]
+    L.a2sgd_selftest_barrier.restype = C.c_int
     L.a2sgd_status_string.argtypes = [C.c_int]
     L.a2sgd_status_string.restype = C.c_char_p
     for name in ("a2sgd_plan", "a2sgd_plan_destroy", "a2sgd_local_averages", "a2sgd_global_average",
@@ -245,3 +247,9 @@ def a2sgd_lazy_step(plan: Plan, g, s, w: torch.Tensor, eta: float, workspace: to
 def a2sgd_lazy_materialize(plan: Plan, s, workspace: torch.Tensor, stream=None) -> None:
     _check(raw.a2sgd_lazy_materialize(plan.handle, _table(plan, s, "s"), _workspace(plan, workspace),
                                       _stream(stream)), "a2sgd_lazy_materialize")
+
+
+def a2sgd_selftest_barrier(scratch: torch.Tensor, stream=None) -> None:
+    if not (isinstance(scratch, torch.Tensor) and scratch.is_cuda and scratch.numel() * scratch.element_size() >= 4096):
+        raise ValueError("scratch: at least 4 KiB of device memory")
+    _check(raw.a2sgd_selftest_barrier(scratch.data_ptr(), _stream(stream)), "a2sgd_selftest_barrier")

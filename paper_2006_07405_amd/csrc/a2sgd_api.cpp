@@ -427,6 +427,33 @@ a2sgd_status_t a2sgd_lazy_materialize(const a2sgd_plan_t *plan, float *const *s,
     return dev(launch_lazy_materialize(*plan, tab, workspace, static_cast<hipStream_t>(stream)));
 }
 
+a2sgd_status_t a2sgd_selftest_barrier(void *scratch, a2sgd_stream_t stream)
+{
+    a2sgd_status_t st = check_buffer(scratch);
+    if (st != A2SGD_OK)
+        return st;
+    constexpr uint32_t kGrid = 128;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint32_t *passed = static_cast<uint32_t *>(scratch);
+    uint32_t *cell_failed = passed + kGrid;
+    uint32_t host[kGrid + 1];
+    for (int round = 0; round < 2; ++round) {
+        const bool starve = round == 1;  // second round: one arrival too few, tiny spin limit
+        if (launch_barrier_selftest(kGrid, starve ? kGrid + 1 : kGrid, starve ? 64u : (1u << 21), passed, cell_failed,
+                                    s) != hipSuccess)
+            return A2SGD_ERR_DEVICE;
+        if (hipMemcpyAsync(host, scratch, sizeof(host), hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess)
+            return A2SGD_ERR_DEVICE;
+        for (uint32_t b = 0; b < kGrid; ++b)
+            if (host[b] != (starve ? 0u : 1u))
+                return A2SGD_ERR_DEVICE;
+        if (host[kGrid] != (starve ? 1u : 0u))
+            return A2SGD_ERR_DEVICE;
+    }
+    return A2SGD_OK;
+}
+
 const char *a2sgd_status_string(a2sgd_status_t status)
 {
     switch (status) {

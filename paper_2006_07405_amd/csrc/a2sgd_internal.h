@@ -108,6 +108,10 @@ hipError_t launch_lazy_reset(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
 hipError_t launch_lazy_partials(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s);
 hipError_t launch_lazy_apply(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eta, void *ws, hipStream_t s);
 hipError_t launch_lazy_materialize(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s);
+// Runs one barrier on the spare cell with `grid` workgroups expecting `expected` arrivals; passed[grid] and
+// *cell_failed (device memory) receive the outcome; the spare cell is cleared afterwards.
+hipError_t launch_barrier_selftest(uint32_t grid, uint32_t expected, uint32_t spin_limit, uint32_t *passed,
+                                   uint32_t *cell_failed, hipStream_t s);
 hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, uint64_t *mask, hipStream_t s);
 hipError_t launch_dense_step(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eta, hipStream_t s);
 

@@ -441,7 +441,7 @@ __global__ __launch_bounds__(BLOCK) void k_apply(const PtrTable tab, float *__re
 struct GridBarrier {
     uint32_t arrive, generation, failed, pad;
 };
-static __device__ GridBarrier g_barriers[kBarrierSlots];
+static __device__ GridBarrier g_barriers[kBarrierSlots + 1];  // the last cell belongs to the self-test
 constexpr uint32_t kBarrierSpinLimit = 1u << 21;  // polls of about a microsecond each
 
 // Device-scope relaxed atomic accessors.  They go to the memory side of the chip, past the XCD's own L2, which
@@ -470,7 +470,7 @@ __device__ __forceinline__ void wait_vector_memory()
 // writes back or invalidates the XCD's whole L2, which costs tens of microseconds when every workgroup does
 // it.  What is needed is order: every wavefront waits for its record stores to be acknowledged before its
 // workgroup arrives, and the records are read only after the generation was seen to move.
-__device__ __forceinline__ bool grid_barrier(GridBarrier *bar, const uint32_t G)
+__device__ __forceinline__ bool grid_barrier(GridBarrier *bar, const uint32_t G, const uint32_t spin_limit)
 {
     __shared__ uint32_t s_ok;
     wait_vector_memory();
@@ -486,7 +486,7 @@ __device__ __forceinline__ bool grid_barrier(GridBarrier *bar, const uint32_t G)
         } else {
             uint32_t polls = 0;
             while (load_device(&bar->generation) == gen) {
-                if (++polls > kBarrierSpinLimit) {
+                if (++polls > spin_limit) {
                     store_device(&bar->failed, 1u);
                     ok = 0;
                     break;
@@ -498,6 +498,28 @@ __device__ __forceinline__ bool grid_barrier(GridBarrier *bar, const uint32_t G)
     }
     __syncthreads();
     return s_ok != 0;
+}
+
+// Self-test of the barrier on the spare cell: every workgroup goes through one barrier that expects `expected`
+// arrivals and reports whether it got through.  With expected = gridDim.x it must; with expected = gridDim.x + 1
+// and a small spin limit nobody is ever last, every wait runs out, and every workgroup still exits.
+__global__ __launch_bounds__(kBlock) void k_barrier_selftest(const uint32_t expected, const uint32_t spin_limit,
+                                                             uint32_t *__restrict__ passed)
+{
+    const bool ok = grid_barrier(&g_barriers[kBarrierSlots], expected, spin_limit);
+    if (threadIdx.x == 0)
+        passed[blockIdx.x] = ok ? 1u : 0u;
+}
+
+__global__ void k_barrier_selftest_reset(uint32_t *__restrict__ cell_failed_out)
+{
+    GridBarrier *bar = &g_barriers[kBarrierSlots];
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        *cell_failed_out = load_device(&bar->failed);
+        store_device(&bar->arrive, 0u);
+        store_device(&bar->generation, 0u);
+        store_device(&bar->failed, 0u);
+    }
 }
 
 constexpr int kFusedUnroll = 4;  // float4 groups per thread per loop trip in the reduction phase
@@ -592,7 +614,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused_step(const PtrTable tab, 
         store_device(part.n_neg + slot, cn);
         store_device(part.n_zero + slot, cz);
     }
-    if (!grid_barrier(bar, G)) {  // uniform per workgroup
+    if (!grid_barrier(bar, G, kBarrierSpinLimit)) {  // uniform per workgroup
         if (tid == 0)
             hdr->failed_token = token;
         return;
@@ -1400,6 +1422,17 @@ hipError_t launch_lazy_materialize(const a2sgd_plan_t &pl, const PtrTable &tab, 
     if (err != hipSuccess)
         return err;
     return launch_lazy_reset(pl, ws, s);
+}
+
+hipError_t launch_barrier_selftest(uint32_t grid, uint32_t expected, uint32_t spin_limit, uint32_t *passed,
+                                   uint32_t *cell_failed, hipStream_t s)
+{
+    k_barrier_selftest<<<dim3(grid), dim3(kBlock), 0, s>>>(expected, spin_limit, passed);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess)
+        return err;
+    k_barrier_selftest_reset<<<dim3(1), dim3(64), 0, s>>>(cell_failed);
+    return hipGetLastError();
 }
 
 hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, uint64_t *mask, hipStream_t s)

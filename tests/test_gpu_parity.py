@@ -392,3 +392,13 @@ def test_lazy_error_state(A, n, P, mode):
     A.a2sgd_global_average(plan, ws_e)
     A.a2sgd_apply_and_update_error(plan, g, e_g, w_g, wl.eta, ws_e)
     assert float((w_l - w_g).abs().max()) <= 1e-9
+
+
+def test_grid_barrier_gives_up_instead_of_hanging(A):
+    """The bounded wait of the single-launch step's barrier, forced from the host on a spare cell: all workgroups
+    pass a complete barrier; all give up, and exit, when one arrival is missing.  Steps still work afterwards."""
+    scratch = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    A.a2sgd_selftest_barrier(scratch)
+    A.a2sgd_selftest_barrier(scratch)  # the spare cell was cleared: the test can run again
+    g, e, w = make_case(8, 100_003, 4)
+    check_against_oracle(A, g, e, w, 0.1, 0, split_calls=False, want_mask=False)
