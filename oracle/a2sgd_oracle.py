@@ -259,3 +259,28 @@ def replica_drift(w: Sequence[np.ndarray]):
     sq = (C.c_longdouble * P)(*([0.0] * P))
     lib().a2sgd_oracle_replica_drift(_fpp(w), P, m, mx, sq)
     return [float(x) for x in mx], [float(np.sqrt(float(x) / m)) for x in sq]
+
+
+def step_segmented(g: Sequence[np.ndarray], e: Optional[Sequence[Optional[np.ndarray]]], w: np.ndarray, eta: float,
+                   mode: int, seg_lengths: Sequence[int]):
+    """Per-tensor variant: the whole-model step applied to each tensor on its own, i.e. one pair of local means per
+    worker AND tensor, averaged over the workers per tensor (the paper's operator of Eq. 2 and Algorithm 1 lines
+    3-7 with v restricted to one tensor).  seg_lengths are the tensor sizes in packing order; they cover [0, n).
+    Returns (list of StepResult per tensor, e_new list, w_new)."""
+    P = len(g)
+    n = int(np.asarray(w).shape[0])
+    assert sum(int(x) for x in seg_lengths) == n and all(int(x) > 0 for x in seg_lengths)
+    e_new = [np.empty(n, dtype=np.float32) for _ in range(P)]
+    w_new = np.empty(n, dtype=np.float32)
+    per_seg = []
+    off = 0
+    for length in seg_lengths:
+        lo, hi = off, off + int(length)
+        es = [x[lo:hi] for x in e] if e is not None else None
+        r = step([x[lo:hi] for x in g], es, w[lo:hi], eta, mode)
+        for p in range(P):
+            e_new[p][lo:hi] = r.e_new[p]
+        w_new[lo:hi] = r.w_new
+        per_seg.append(r)
+        off = hi
+    return per_seg, e_new, w_new

@@ -4,92 +4,9 @@
 // fused elementwise pass (lines 4, 6, 7).  Every global access of the two big passes is a 128-bit load or
 // store, consecutive lanes touching consecutive 16-byte groups, so a wavefront moves 1 KiB per instruction.
 // No matrix cores: there is no contraction anywhere in the method.
-#include "a2sgd_internal.h"
+#include "a2sgd_device.h"
 
 namespace a2sgd {
-
-typedef float vf4 __attribute__((ext_vector_type(4)));
-
-template <bool NT>
-__device__ __forceinline__ vf4 ld4(const vf4 *p)
-{
-    if (NT)
-        return __builtin_nontemporal_load(p);
-    return *p;
-}
-
-// Streaming store: non-temporal and written through at device scope (sc1), so the line does not linger in the
-// XCD's write-back L2.  Measured on the apply pass's mix of 9 read and 5 write streams: 4.5 % faster than the
-// non-temporal hint alone, 14 % faster than plain stores.  The instruction is spelled out because the compiler
-// offers no builtin for the scope bit on a 128-bit store (and its non-temporal metadata has been seen to get
-// lost on the way through the optimiser).  The s_nop belongs to the store: on this chip a vector instruction
-// must not overwrite the data registers of a store wider than 64 bits within 2 wait states of it, a hazard the
-// compiler pads by itself for its own stores but cannot see inside an asm statement.
-template <bool NT>
-__device__ __forceinline__ void st4(vf4 *p, vf4 v)
-{
-    if (NT)
-        asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
-    else
-        *p = v;
-}
-
-// ---------------------------------------------------------------------------------------------------------
-// First-level reduction (Algorithm 1 line 3; group definitions of Sec. 3.1)
-// ---------------------------------------------------------------------------------------------------------
-
-// Running sums and counts of one lane.  Sums in fp64 so that the fp32 means come out the same as an exactly
-// summed reference; counts are taken per wavefront with a ballot and a scalar popcount, which keeps them off
-// the vector ALU.  A NaN fails both comparisons: it is counted nowhere and added to neither sum.
-struct LaneAcc {
-    double s_pos = 0.0, s_neg = 0.0;
-    // Counts of the whole wavefront, identical in every active lane.  The block reduction reads them from
-    // lane 0, which is active whenever any lane of its wavefront is (indices grow with the lane number).
-    // 32 bits hold one tile's worth (at most 64 * 16 per call of flush); the totals are 64-bit.
-    uint32_t t_pos = 0, t_neg = 0, t_zero = 0;
-    uint64_t c_pos = 0, c_neg = 0, c_zero = 0;
-
-    __device__ __forceinline__ void add(float v)
-    {
-        const bool ge = v >= 0.0f;
-        const bool lt = v < 0.0f;
-        s_pos += static_cast<double>(ge ? v : 0.0f);
-        s_neg -= static_cast<double>(lt ? v : 0.0f);
-        t_pos += __popcll(__ballot(ge));
-        t_neg += __popcll(__ballot(lt));
-        t_zero += __popcll(__ballot(v == 0.0f));
-    }
-    __device__ __forceinline__ void flush()
-    {
-        c_pos += t_pos;
-        c_neg += t_neg;
-        c_zero += t_zero;
-        t_pos = t_neg = t_zero = 0;
-    }
-    __device__ __forceinline__ void add4(vf4 v)
-    {
-        add(v.x);
-        add(v.y);
-        add(v.z);
-        add(v.w);
-    }
-};
-
-__device__ __forceinline__ double wave_sum(double x)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1)
-        x += __shfl_down(x, off);
-    return x;  // valid in lane 0; the tree shape is fixed, so the result is reproducible
-}
-
-__device__ __forceinline__ uint64_t wave_sum(uint64_t x)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1)
-        x += __shfl_down(static_cast<unsigned long long>(x), off);
-    return x;
-}
 
 // grid = (B, P).  Block b of worker p takes the tiles b, b + B, b + 2B, ... of that worker's vector; a tile is
 // kBlock * kReduceUnroll consecutive float4 groups.  Whatever does not fill a tile is taken one float4 group
@@ -253,47 +170,6 @@ __global__ void k_global_average(const uint32_t P, WsHeader *__restrict__ hdr)
 // ---------------------------------------------------------------------------------------------------------
 // Fused apply pass (Algorithm 1 lines 4, 6, 7; Eq. 2 for the encoding; Eq. 1 for the average over workers)
 // ---------------------------------------------------------------------------------------------------------
-
-// One element of one worker: rewrites v into the new error and returns that worker's contribution u to the
-// update.  Written as selects on register values so that it compiles to v_cndmask, not to branches.  A NaN
-// fails v >= 0, so v + mu_neg keeps it NaN in e; the extra select keeps it NaN in u as well.
-template <int MODE>
-__device__ __forceinline__ float apply1(float &v, float neg_mu_pos, float mu_neg, float gmu_pos, float neg_gmu_neg)
-{
-    const bool ge = v >= 0.0f;
-    const float err = v + (ge ? neg_mu_pos : mu_neg);  // v - enc(v): Eq. 2, Algorithm 1 line 4
-    float glob = ge ? gmu_pos : neg_gmu_neg;           // global-mean vector at this position: line 6
-    glob = (v != v) ? v : glob;
-    v = err;
-    return MODE == A2SGD_MODE_ALG1_LITERAL ? err + glob : glob;
-}
-
-// Four elements of one worker.  Returns the new error as a fresh value (storing a value that was updated in
-// place in a register array has been seen to lose its non-temporal hint on the way through the optimiser).
-template <int MODE>
-__device__ __forceinline__ vf4 apply4(vf4 v, vf4 &acc, float neg_mu_pos, float mu_neg, float gmu_pos,
-                                      float neg_gmu_neg)
-{
-    float x = v.x, y = v.y, z = v.z, t = v.w;
-    acc.x += apply1<MODE>(x, neg_mu_pos, mu_neg, gmu_pos, neg_gmu_neg);
-    acc.y += apply1<MODE>(y, neg_mu_pos, mu_neg, gmu_pos, neg_gmu_neg);
-    acc.z += apply1<MODE>(z, neg_mu_pos, mu_neg, gmu_pos, neg_gmu_neg);
-    acc.w += apply1<MODE>(t, neg_mu_pos, mu_neg, gmu_pos, neg_gmu_neg);
-    return vf4{x, y, z, t};
-}
-
-// A zero the compiler cannot see through, in a vector register.  Added to an index it turns a load with a
-// wavefront-uniform address into an ordinary vector load.  The apply pass wants that for the handful of means
-// it reads from the workspace: vector loads return in issue order and are counted apart from the scalar loads
-// of the kernel arguments, so when they are issued first they cost a freshly launched workgroup no wait of
-// their own, whereas a scalar load would be waited for together with the kernel-argument pointers before the
-// first big load could be issued.
-__device__ __forceinline__ uint32_t opaque_zero()
-{
-    uint32_t z;
-    asm volatile("v_mov_b32 %0, 0" : "=v"(z));
-    return z;
-}
 
 // Body of the apply pass for one workgroup.  Thread t owns the float4 groups base + it * BLOCK (it < ITEMS) of
 // every worker and of w.  The g and e loads of UP workers x ITEMS groups are all issued before the first use:
