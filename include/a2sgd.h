@@ -67,7 +67,10 @@ typedef struct {
     uint32_t num_workers;       /* P, 1 <= P <= A2SGD_MAX_WORKERS */
     int32_t mode;               /* an a2sgd_mode_t */
     uint32_t blocks_per_worker; /* 0 = let the plan choose; else the first-level reduction's grid width */
-    uint32_t reserved;          /* must be 0 */
+    uint32_t num_segments;      /* 0 or 1: one pair of means per worker over the whole model (the paper's method);
+                                   S > 1: per-tensor means, see below.  At most 2^20. */
+    const uint64_t *seg_length; /* HOST array of num_segments tensor sizes (each >= 1) in packing order, summing to
+                                   n; read during a2sgd_plan only; ignored (may be NULL) when num_segments <= 1 */
 } a2sgd_config_t;
 
 /* Per-worker result of the reduction (Sec. 3.1; the pair (mu_pos, mu_neg) is the worker's 64-bit message of
@@ -137,6 +140,24 @@ a2sgd_status_t a2sgd_export_mask(const a2sgd_plan_t *plan, const float *const *g
  * w_i <- w_i - eta * (1/P) * sum_p g^p_i.  Reads every g^p and w once, writes w once. */
 a2sgd_status_t a2sgd_dense_step(const a2sgd_plan_t *plan, const float *const *g, float *w, float eta,
                                 a2sgd_stream_t stream);
+
+/* ---- Per-tensor means -----------------------------------------------------------------------------------------
+ * A plan made with num_segments = S > 1 applies the operator of Eq. 2 and Algorithm 1 lines 3-7 to every tensor
+ * (segment) of the flat gradient on its own: worker p has one pair of local means per tensor, the global means
+ * are averaged over the workers per tensor, and each element is encoded with the means of its tensor (2S scalars
+ * per worker and step instead of 2).  a2sgd_local_averages, a2sgd_global_average, a2sgd_apply_and_update_error
+ * and a2sgd_step work as described above, per tensor; a2sgd_dense_step and a2sgd_export_mask do not depend on
+ * the segments.  Not available on such a plan (A2SGD_ERR_INVALID_ARG): a2sgd_read_stats, the replica calls and
+ * the lazy calls.  The workspace of such a plan holds static lookup tables: */
+
+/* Uploads the plan's segment tables into the workspace.  Required once per workspace, before its first use, when
+ * the plan has num_segments > 1; a no-op otherwise.  Asynchronous on `stream`; the plan must outlive the copy. */
+a2sgd_status_t a2sgd_workspace_init(const a2sgd_plan_t *plan, void *workspace, a2sgd_stream_t stream);
+
+/* Per-tensor results of the last completed reduction: out_workers[p * S + s] for worker p and tensor s (host array
+ * of P * S records, may be NULL) and out_global[s] (host array of S, may be NULL).  Synchronises `stream`. */
+a2sgd_status_t a2sgd_read_segment_stats(const a2sgd_plan_t *plan, const void *workspace, a2sgd_stream_t stream,
+                                        a2sgd_worker_stats_t *out_workers, a2sgd_global_stats_t *out_global);
 
 /* ---- One weight vector per worker: Algorithm 1 as each worker runs it on its own replica ------------------
  * `w` is a HOST array of P DEVICE pointers, like g and e; w^p is updated in place.  The same workspace serves. */

@@ -23,7 +23,8 @@ A2SGD_MODE_RETAINED_ERROR, A2SGD_MODE_ALG1_LITERAL = 0, 1
 
 class a2sgd_config_t(C.Structure):
     _fields_ = [("n", C.c_uint64), ("num_workers", C.c_uint32), ("mode", C.c_int32),
-                ("blocks_per_worker", C.c_uint32), ("reserved", C.c_uint32)]
+                ("blocks_per_worker", C.c_uint32), ("num_segments", C.c_uint32),
+                ("seg_length", C.POINTER(C.c_uint64))]
 
 
 class a2sgd_worker_stats_t(C.Structure):
@@ -64,6 +65,11 @@ def _load():
     L.a2sgd_lazy_materialize.argtypes = [vp, tab, vp, vp]
     L.a2sgd_selftest_barrier.argtypes = [vp, vp]
     L.a2sgd_selftest_barrier.restype = C.c_int
+    L.a2sgd_workspace_init.argtypes = [vp, vp, vp]
+    L.a2sgd_workspace_init.restype = C.c_int
+    L.a2sgd_read_segment_stats.argtypes = [vp, vp, vp, C.POINTER(a2sgd_worker_stats_t),
+                                           C.POINTER(a2sgd_global_stats_t)]
+    L.a2sgd_read_segment_stats.restype = C.c_int
     L.a2sgd_status_string.argtypes = [C.c_int]
     L.a2sgd_status_string.restype = C.c_char_p
     for name in ("a2sgd_plan", "a2sgd_plan_destroy", "a2sgd_local_averages", "a2sgd_global_average",
@@ -92,8 +98,9 @@ def _check(status: int, where: str) -> None:
 class Plan:
     """Owns an a2sgd_plan_t*; remembers n and P so the binding can check tensor shapes before marshalling."""
 
-    def __init__(self, handle: int, n: int, num_workers: int, mode: int):
+    def __init__(self, handle: int, n: int, num_workers: int, mode: int, num_segments: int = 0):
         self.handle, self.n, self.num_workers, self.mode = handle, n, num_workers, mode
+        self.num_segments = num_segments
 
     def __del__(self):
         if getattr(self, "handle", None):
@@ -133,11 +140,15 @@ def _workspace(plan: Plan, ws: torch.Tensor) -> int:
     return ws.data_ptr()
 
 
-def a2sgd_plan(n: int, num_workers: int, mode: int = A2SGD_MODE_RETAINED_ERROR, blocks_per_worker: int = 0) -> Plan:
-    cfg = a2sgd_config_t(n, num_workers, mode, blocks_per_worker, 0)
+def a2sgd_plan(n: int, num_workers: int, mode: int = A2SGD_MODE_RETAINED_ERROR, blocks_per_worker: int = 0,
+               seg_lengths: Optional[Sequence[int]] = None) -> Plan:
+    """seg_lengths: tensor sizes in packing order (summing to n) for per-tensor means; None = whole-model means."""
+    S = len(seg_lengths) if seg_lengths is not None else 0
+    arr = (C.c_uint64 * S)(*[int(x) for x in seg_lengths]) if S else None
+    cfg = a2sgd_config_t(n, num_workers, mode, blocks_per_worker, S, arr)
     h = C.c_void_p()
     _check(raw.a2sgd_plan(C.byref(cfg), C.byref(h)), "a2sgd_plan")
-    return Plan(h.value, n, num_workers, mode)
+    return Plan(h.value, n, num_workers, mode, S if S > 1 else 0)
 
 
 def a2sgd_workspace_bytes(plan: Plan) -> int:
@@ -149,8 +160,28 @@ def a2sgd_plan_blocks_per_worker(plan: Plan) -> int:
 
 
 def alloc_workspace(plan: Plan, device="cuda") -> torch.Tensor:
-    """Convenience for callers that let torch own the memory: an uninitialised device buffer of the right size."""
-    return torch.empty((a2sgd_workspace_bytes(plan) + 7) // 8, dtype=torch.int64, device=device)
+    """Convenience for callers that let torch own the memory: a device buffer of the right size, with the plan's
+    segment tables uploaded when it has any (a2sgd_workspace_init); otherwise uninitialised."""
+    ws = torch.empty((a2sgd_workspace_bytes(plan) + 7) // 8, dtype=torch.int64, device=device)
+    if plan.num_segments:
+        a2sgd_workspace_init(plan, ws)
+    return ws
+
+
+def a2sgd_workspace_init(plan: Plan, workspace: torch.Tensor, stream=None) -> None:
+    _check(raw.a2sgd_workspace_init(plan.handle, _workspace(plan, workspace), _stream(stream)), "a2sgd_workspace_init")
+
+
+def a2sgd_read_segment_stats(plan: Plan, workspace: torch.Tensor, stream=None):
+    """Returns (stats[p][s] as WorkerStats, [(gmu_pos, gmu_neg)] * S).  Synchronises the stream."""
+    P, S = plan.num_workers, plan.num_segments
+    ws = (a2sgd_worker_stats_t * (P * S))()
+    gs = (a2sgd_global_stats_t * S)()
+    _check(raw.a2sgd_read_segment_stats(plan.handle, _workspace(plan, workspace), _stream(stream), ws, gs),
+           "a2sgd_read_segment_stats")
+    stats = [[WorkerStats(ws[p * S + s].mu_pos, ws[p * S + s].mu_neg, ws[p * S + s].n_pos, ws[p * S + s].n_neg,
+                          ws[p * S + s].n_zero, ws[p * S + s].n_nan) for s in range(S)] for p in range(P)]
+    return stats, [(x.gmu_pos, x.gmu_neg) for x in gs]
 
 
 def a2sgd_local_averages(plan: Plan, g, e, workspace: torch.Tensor, stream=None) -> None:

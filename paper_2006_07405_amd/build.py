@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "liba2sgd.so")
-SOURCES = [os.path.join(HERE, "csrc", "a2sgd_kernels.hip"), os.path.join(HERE, "csrc", "a2sgd_api.cpp")]
+SOURCES = [os.path.join(HERE, "csrc", "a2sgd_kernels.hip"), os.path.join(HERE, "csrc", "a2sgd_segments.hip"),
+           os.path.join(HERE, "csrc", "a2sgd_api.cpp")]
 
 # Denormals are kept (a flushed tiny negative would change sign group); packed-fp32 instructions are disabled.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-flush-denormals-to-zero",

@@ -2,6 +2,7 @@
 // sequencing of the kernels of one step.  No device memory is allocated here.
 #include <atomic>
 #include <new>
+#include <vector>
 
 #include "a2sgd_internal.h"
 
@@ -31,6 +32,64 @@ uint32_t apply_lds_bytes(uint32_t P)
 // Above this many bytes of g + e + w the step cannot live in the 256 MiB last-level cache between its two
 // passes, and every load and store is issued as non-temporal.
 constexpr uint64_t kStreamingBytes = 192ull << 20;
+
+constexpr uint32_t kMaxSegments = 1u << 20;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Static tables of a per-tensor plan: segment ends, work items of at most kSegItemElems elements that stay
+// inside one segment, the items of each segment, a coarse element -> segment lookup; and where all of that, the
+// per-segment results and the partial records live in the workspace.
+void build_segments(a2sgd_plan_t &pl, uint32_t S, const uint64_t *len)
+{
+    SegPlan &sp = pl.seg;
+    sp.S = S;
+    sp.seg_end.resize(S);
+    sp.item_lo.resize(S + 1);
+    uint64_t off = 0;
+    for (uint32_t s = 0; s < S; ++s) {
+        sp.item_lo[s] = static_cast<uint32_t>(sp.item.size());
+        for (uint64_t lo = off; lo < off + len[s]; lo += kSegItemElems) {
+            const uint64_t left = off + len[s] - lo;
+            sp.item.push_back(SegItem{lo, static_cast<uint32_t>(left < kSegItemElems ? left : kSegItemElems), s});
+        }
+        off += len[s];
+        sp.seg_end[s] = off;
+    }
+    sp.item_lo[S] = static_cast<uint32_t>(sp.item.size());
+    const uint64_t chunks = (pl.n + (1ull << kSegCoarseShift) - 1) >> kSegCoarseShift;
+    sp.coarse.resize(chunks);
+    uint32_t s = 0;
+    for (uint64_t c = 0; c < chunks; ++c) {
+        const uint64_t idx = c << kSegCoarseShift;
+        while (sp.seg_end[s] <= idx)
+            ++s;
+        sp.coarse[c] = s;
+    }
+    size_t o = pl.workspace_bytes;  // after the header and the whole-model partials region
+    o = align_up(o, 256);
+    sp.off_seg_end = o;
+    o = align_up(o + 8ull * S, 256);
+    sp.off_item = o;
+    o = align_up(o + sizeof(SegItem) * sp.item.size(), 256);
+    sp.off_item_lo = o;
+    o = align_up(o + 4ull * (S + 1), 256);
+    sp.off_coarse = o;
+    o = align_up(o + 4ull * chunks, 256);
+    sp.off_stats = o;
+    o = align_up(o + sizeof(a2sgd_worker_stats_t) * pl.P * S, 256);
+    sp.off_nmp = o;
+    o = align_up(o + 4ull * S * pl.P, 256);
+    sp.off_mn = o;
+    o = align_up(o + 4ull * S * pl.P, 256);
+    sp.off_gmu = o;
+    o = align_up(o + 8ull * S, 256);
+    sp.off_records = o;
+    o = align_up(o + 5ull * 8ull * pl.P * sp.item.size(), 256);
+    sp.end = o;
+}
+
+inline bool segmented(const a2sgd_plan_t *plan) { return plan->seg.S > 1; }
 
 std::atomic<uint32_t> g_next_slot{0};
 std::atomic<uint32_t> g_next_token{1};
@@ -115,8 +174,20 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
         return A2SGD_ERR_INVALID_ARG;
     if (cfg->mode != A2SGD_MODE_RETAINED_ERROR && cfg->mode != A2SGD_MODE_ALG1_LITERAL)
         return A2SGD_ERR_INVALID_ARG;
-    if (cfg->blocks_per_worker > kMaxBlocksPerWorker || cfg->reserved != 0)
+    if (cfg->blocks_per_worker > kMaxBlocksPerWorker || cfg->num_segments > kMaxSegments)
         return A2SGD_ERR_INVALID_ARG;
+    if (cfg->num_segments > 1) {
+        if (cfg->seg_length == nullptr)
+            return A2SGD_ERR_INVALID_ARG;
+        uint64_t total = 0;
+        for (uint32_t s = 0; s < cfg->num_segments; ++s) {
+            if (cfg->seg_length[s] == 0 || cfg->seg_length[s] > cfg->n - total)
+                return A2SGD_ERR_INVALID_ARG;
+            total += cfg->seg_length[s];
+        }
+        if (total != cfg->n)
+            return A2SGD_ERR_INVALID_ARG;
+    }
     a2sgd_plan_t *pl = new (std::nothrow) a2sgd_plan_t;
     if (pl == nullptr)
         return A2SGD_ERR_NOMEM;
@@ -140,6 +211,16 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
     const size_t partials = 5ull * 8ull * pl->P * rows;
     const size_t drift = 2ull * 8ull * pl->P * (kDriftBlocks + 1);  // the drift diagnostic reuses the same region
     pl->workspace_bytes = kHeaderBytes + (partials > drift ? partials : drift);
+    if (cfg->num_segments > 1) {
+        try {
+            build_segments(*pl, cfg->num_segments, cfg->seg_length);
+        } catch (const std::bad_alloc &) {
+            delete pl;
+            return A2SGD_ERR_NOMEM;
+        }
+        pl->fused_grid = 0;  // the single-launch step knows whole-model means only
+        pl->workspace_bytes = pl->seg.end;
+    }
     *out_plan = pl;
     return A2SGD_OK;
 }
@@ -167,6 +248,11 @@ a2sgd_status_t a2sgd_local_averages(const a2sgd_plan_t *plan, const float *const
     fill_table(tab, plan->P, g, has_e ? e : nullptr);
     plan->last_token = 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (segmented(plan)) {
+        if ((st = dev(launch_seg_partials(*plan, tab, has_e, workspace, s))) != A2SGD_OK)
+            return st;
+        return dev(launch_seg_finalize(*plan, workspace, s));
+    }
     if ((st = dev(launch_local_partials(*plan, tab, has_e, workspace, s))) != A2SGD_OK)
         return st;
     return dev(launch_local_finalize(*plan, workspace, s));
@@ -179,6 +265,8 @@ a2sgd_status_t a2sgd_global_average(const a2sgd_plan_t *plan, void *workspace, a
     a2sgd_status_t st = check_buffer(workspace);
     if (st != A2SGD_OK)
         return st;
+    if (segmented(plan))
+        return dev(launch_seg_global(*plan, workspace, static_cast<hipStream_t>(stream)));
     return dev(launch_global_average(*plan, workspace, static_cast<hipStream_t>(stream)));
 }
 
@@ -195,6 +283,8 @@ a2sgd_status_t a2sgd_apply_and_update_error(const a2sgd_plan_t *plan, const floa
         return st;
     PtrTable tab;
     fill_table(tab, plan->P, g, has_e ? e : nullptr);
+    if (segmented(plan))
+        return dev(launch_seg_apply(*plan, tab, has_e, w, eta, workspace, static_cast<hipStream_t>(stream)));
     return dev(launch_apply(*plan, tab, has_e, w, eta, workspace, static_cast<hipStream_t>(stream)));
 }
 
@@ -229,7 +319,7 @@ a2sgd_status_t a2sgd_step(const a2sgd_plan_t *plan, const float *const *g, float
 a2sgd_status_t a2sgd_read_stats(const a2sgd_plan_t *plan, const void *workspace, a2sgd_stream_t stream,
                                 a2sgd_worker_stats_t *out_workers, a2sgd_global_stats_t *out_global)
 {
-    if (plan == nullptr || workspace == nullptr)
+    if (plan == nullptr || workspace == nullptr || segmented(plan))
         return A2SGD_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     WsHeader hdr;
@@ -291,6 +381,8 @@ a2sgd_status_t a2sgd_apply_and_update_error_replicas(const a2sgd_plan_t *plan, c
     a2sgd_status_t st = check_g_e(plan, g, e, &has_e);
     if (st != A2SGD_OK)
         return st;
+    if (segmented(plan))
+        return A2SGD_ERR_INVALID_ARG;
     if ((st = check_table(w, plan->P, true, &has_w)) != A2SGD_OK)
         return st;
     if ((st = check_buffer(workspace)) != A2SGD_OK)
@@ -309,6 +401,8 @@ a2sgd_status_t a2sgd_step_replicas(const a2sgd_plan_t *plan, const float *const 
     a2sgd_status_t st = check_g_e(plan, g, e, &has_e);
     if (st != A2SGD_OK)
         return st;
+    if (segmented(plan))
+        return A2SGD_ERR_INVALID_ARG;
     if ((st = check_table(w, plan->P, true, &has_w)) != A2SGD_OK)
         return st;
     if ((st = check_buffer(workspace)) != A2SGD_OK)
@@ -371,7 +465,7 @@ a2sgd_status_t a2sgd_replica_drift(const a2sgd_plan_t *plan, const float *const 
 
 a2sgd_status_t a2sgd_lazy_reset(const a2sgd_plan_t *plan, void *workspace, a2sgd_stream_t stream)
 {
-    if (plan == nullptr)
+    if (plan == nullptr || segmented(plan))
         return A2SGD_ERR_INVALID_ARG;
     a2sgd_status_t st = check_buffer(workspace);
     if (st != A2SGD_OK)
@@ -382,7 +476,7 @@ a2sgd_status_t a2sgd_lazy_reset(const a2sgd_plan_t *plan, void *workspace, a2sgd
 a2sgd_status_t a2sgd_lazy_step(const a2sgd_plan_t *plan, const float *const *g, float *const *s, float *w, float eta,
                                void *workspace, a2sgd_stream_t stream)
 {
-    if (plan == nullptr)
+    if (plan == nullptr || segmented(plan))
         return A2SGD_ERR_INVALID_ARG;
     bool has_g = false, has_s = false;
     a2sgd_status_t st = check_table(g, plan->P, true, &has_g);
@@ -414,7 +508,7 @@ a2sgd_status_t a2sgd_lazy_step(const a2sgd_plan_t *plan, const float *const *g, 
 a2sgd_status_t a2sgd_lazy_materialize(const a2sgd_plan_t *plan, float *const *s, void *workspace,
                                       a2sgd_stream_t stream)
 {
-    if (plan == nullptr)
+    if (plan == nullptr || segmented(plan))
         return A2SGD_ERR_INVALID_ARG;
     bool has_s = false;
     a2sgd_status_t st = check_table(s, plan->P, true, &has_s);
@@ -451,6 +545,62 @@ a2sgd_status_t a2sgd_selftest_barrier(void *scratch, a2sgd_stream_t stream)
         if (host[kGrid] != (starve ? 1u : 0u))
             return A2SGD_ERR_DEVICE;
     }
+    return A2SGD_OK;
+}
+
+a2sgd_status_t a2sgd_workspace_init(const a2sgd_plan_t *plan, void *workspace, a2sgd_stream_t stream)
+{
+    if (plan == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    a2sgd_status_t st = check_buffer(workspace);
+    if (st != A2SGD_OK)
+        return st;
+    if (!segmented(plan))
+        return A2SGD_OK;
+    const SegPlan &sp = plan->seg;
+    char *b = static_cast<char *>(workspace);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const struct {
+        size_t off;
+        const void *src;
+        size_t bytes;
+    } parts[] = {{sp.off_seg_end, sp.seg_end.data(), 8ull * sp.seg_end.size()},
+                 {sp.off_item, sp.item.data(), sizeof(SegItem) * sp.item.size()},
+                 {sp.off_item_lo, sp.item_lo.data(), 4ull * sp.item_lo.size()},
+                 {sp.off_coarse, sp.coarse.data(), 4ull * sp.coarse.size()}};
+    for (const auto &part : parts)
+        if (hipMemcpyAsync(b + part.off, part.src, part.bytes, hipMemcpyHostToDevice, s) != hipSuccess)
+            return A2SGD_ERR_DEVICE;
+    return A2SGD_OK;
+}
+
+a2sgd_status_t a2sgd_read_segment_stats(const a2sgd_plan_t *plan, const void *workspace, a2sgd_stream_t stream,
+                                        a2sgd_worker_stats_t *out_workers, a2sgd_global_stats_t *out_global)
+{
+    if (plan == nullptr || workspace == nullptr || !segmented(plan))
+        return A2SGD_ERR_INVALID_ARG;
+    const SegPlan &sp = plan->seg;
+    const char *b = static_cast<const char *>(workspace);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    std::vector<float> gmu;
+    try {
+        gmu.resize(2ull * sp.S);
+    } catch (const std::bad_alloc &) {
+        return A2SGD_ERR_NOMEM;
+    }
+    if (out_workers && hipMemcpyAsync(out_workers, b + sp.off_stats, sizeof(a2sgd_worker_stats_t) * plan->P * sp.S,
+                                      hipMemcpyDeviceToHost, s) != hipSuccess)
+        return A2SGD_ERR_DEVICE;
+    if (out_global &&
+        hipMemcpyAsync(gmu.data(), b + sp.off_gmu, 8ull * sp.S, hipMemcpyDeviceToHost, s) != hipSuccess)
+        return A2SGD_ERR_DEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess)
+        return A2SGD_ERR_DEVICE;
+    if (out_global)
+        for (uint32_t k = 0; k < sp.S; ++k) {
+            out_global[k].gmu_pos = gmu[2 * k];
+            out_global[k].gmu_neg = -gmu[2 * k + 1];  // the table keeps the negated value for the apply pass
+        }
     return A2SGD_OK;
 }
 

@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "a2sgd.h"
 
 namespace a2sgd {
@@ -74,6 +76,45 @@ struct ApplyGeom {
 };
 }  // namespace a2sgd
 
+namespace a2sgd {
+
+// ---- per-tensor means: static tables the plan builds on the host and a2sgd_workspace_init uploads --------------
+constexpr uint32_t kSegItemElems = 65536;  // a work item of the segmented reduction covers at most this many elements
+constexpr uint32_t kSegCoarseShift = 14;   // the coarse lookup table has one entry per 2^14 elements
+
+struct SegItem {  // one work item: a run of elements inside one segment
+    uint64_t start;
+    uint32_t count;
+    uint32_t seg;
+};
+
+// Device views of the segmented part of the workspace (all offsets are fixed by the plan).
+struct SegView {
+    uint32_t S;
+    uint32_t num_items;
+    const uint64_t *seg_end;   // [S] exclusive end of every segment
+    const SegItem *item;       // [num_items], ascending start
+    const uint32_t *item_lo;   // [S + 1]: items of segment s are item_lo[s] .. item_lo[s + 1] - 1
+    const uint32_t *coarse;    // [ceil(n / 2^14)]: segment of element k * 2^14
+    a2sgd_worker_stats_t *stats;  // [P][S]
+    float *neg_mu_pos, *mu_neg;   // [S][P], packed for the apply pass
+    float *gmu;                   // [S][2]: gmu_pos, -gmu_neg
+    double *r_spos, *r_sneg;      // [P][num_items] partial records of the reduction
+    uint64_t *r_npos, *r_nneg, *r_nzero;
+};
+
+struct SegPlan {
+    uint32_t S = 0;  // 0 = whole-model means
+    std::vector<uint64_t> seg_end;
+    std::vector<SegItem> item;
+    std::vector<uint32_t> item_lo, coarse;
+    // byte offsets into the workspace
+    size_t off_seg_end = 0, off_item = 0, off_item_lo = 0, off_coarse = 0, off_stats = 0, off_nmp = 0, off_mn = 0,
+           off_gmu = 0, off_records = 0, end = 0;
+};
+
+}  // namespace a2sgd
+
 struct a2sgd_plan {
     uint64_t n;
     uint32_t P;
@@ -84,6 +125,7 @@ struct a2sgd_plan {
     uint32_t fused_grid;  // workgroups of the single-launch step; 0 = a2sgd_step runs the three passes
     uint32_t barrier_slot;
     mutable uint32_t last_token;  // token of the last single-launch step enqueued with this plan; 0 = none
+    a2sgd::SegPlan seg;
     size_t workspace_bytes;
 };
 
@@ -112,6 +154,13 @@ hipError_t launch_lazy_materialize(const a2sgd_plan_t &pl, const PtrTable &tab, 
 // *cell_failed (device memory) receive the outcome; the spare cell is cleared afterwards.
 hipError_t launch_barrier_selftest(uint32_t grid, uint32_t expected, uint32_t spin_limit, uint32_t *passed,
                                    uint32_t *cell_failed, hipStream_t s);
+// Per-tensor means (a2sgd_segments.hip).
+SegView seg_view(const a2sgd_plan_t &pl, void *ws);
+hipError_t launch_seg_partials(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, void *ws, hipStream_t s);
+hipError_t launch_seg_finalize(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
+hipError_t launch_seg_global(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
+hipError_t launch_seg_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
+                            hipStream_t s);
 hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, uint64_t *mask, hipStream_t s);
 hipError_t launch_dense_step(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eta, hipStream_t s);
 

@@ -1,0 +1,370 @@
+// Per-tensor means: the A2SGD step with one pair of local means per worker AND per tensor (segment) of the flat
+// gradient instead of one pair per worker.  The paper states its operator for "a gradient vector v" (Sec. 3.1,
+// Eq. 2) and applies it to the whole model; this is the same operator and the same Algorithm 1 lines 3-7 applied
+// tensor by tensor, the way a per-layer hook would.  Segments are contiguous, in packing order, and cover [0, n).
+//
+// The plan splits every segment into work items of at most kSegItemElems elements that never cross a segment
+// boundary.  Reduction: one partial record per (worker, item); second level per (worker, segment) over that
+// segment's items in index order; then the per-segment global means.  The apply pass is the one-shot
+// single-wavefront shape of k_apply; a workgroup looks its segment up through a coarse table, and the few
+// workgroups that straddle a boundary fall back to a per-element path.
+#include "a2sgd_device.h"
+
+namespace a2sgd {
+
+SegView seg_view(const a2sgd_plan_t &pl, void *ws)
+{
+    char *b = static_cast<char *>(ws);
+    const SegPlan &sp = pl.seg;
+    const size_t stride = 8ull * pl.P * sp.item.size();
+    SegView v;
+    v.S = sp.S;
+    v.num_items = static_cast<uint32_t>(sp.item.size());
+    v.seg_end = reinterpret_cast<const uint64_t *>(b + sp.off_seg_end);
+    v.item = reinterpret_cast<const SegItem *>(b + sp.off_item);
+    v.item_lo = reinterpret_cast<const uint32_t *>(b + sp.off_item_lo);
+    v.coarse = reinterpret_cast<const uint32_t *>(b + sp.off_coarse);
+    v.stats = reinterpret_cast<a2sgd_worker_stats_t *>(b + sp.off_stats);
+    v.neg_mu_pos = reinterpret_cast<float *>(b + sp.off_nmp);
+    v.mu_neg = reinterpret_cast<float *>(b + sp.off_mn);
+    v.gmu = reinterpret_cast<float *>(b + sp.off_gmu);
+    v.r_spos = reinterpret_cast<double *>(b + sp.off_records);
+    v.r_sneg = reinterpret_cast<double *>(b + sp.off_records + stride);
+    v.r_npos = reinterpret_cast<uint64_t *>(b + sp.off_records + 2 * stride);
+    v.r_nneg = reinterpret_cast<uint64_t *>(b + sp.off_records + 3 * stride);
+    v.r_nzero = reinterpret_cast<uint64_t *>(b + sp.off_records + 4 * stride);
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Reduction, first level (Algorithm 1 line 3 per tensor).  grid = (B, P); block b of worker p takes the items
+// b, b + B, ...  An item starts and ends anywhere: elements up to the first 16-byte boundary and after the
+// last one are taken one per thread, the float4 groups in between kSegUnroll per thread per trip.
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kSegUnroll = 4;
+
+template <bool HAS_E, bool NT>
+__global__ __launch_bounds__(kBlock) void k_seg_partials(const PtrTable tab, const uint32_t B, const SegView sv)
+{
+    const uint32_t p = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float *__restrict__ g = tab.g[p];
+    const float *__restrict__ e = HAS_E ? tab.e[p] : nullptr;
+    const vf4 *g4 = reinterpret_cast<const vf4 *>(g), *e4 = reinterpret_cast<const vf4 *>(e);
+    __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
+    __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
+
+    for (uint32_t it = blockIdx.x; it < sv.num_items; it += B) {
+        const SegItem item = sv.item[it];
+        const uint64_t lo = item.start, hi = item.start + item.count;
+        uint64_t a = (lo + 3) & ~static_cast<uint64_t>(3);  // first element on a 16-byte boundary
+        if (a > hi)
+            a = hi;
+        const uint64_t z = a + ((hi - a) & ~static_cast<uint64_t>(3));  // end of the float4 groups
+        LaneAcc acc;
+        if (tid < a - lo) {  // head, at most 3 elements
+            const uint64_t i = lo + tid;
+            acc.add(HAS_E ? g[i] + e[i] : g[i]);
+            acc.flush();
+        }
+        const uint64_t v_lo = a >> 2, v_hi = z >> 2;
+        for (uint64_t i0 = v_lo + tid; i0 < v_hi; i0 += static_cast<uint64_t>(kBlock) * kSegUnroll) {
+            vf4 gv[kSegUnroll], ev[kSegUnroll];
+#pragma unroll
+            for (int u = 0; u < kSegUnroll; ++u)
+                if (i0 + u * kBlock < v_hi) {
+                    gv[u] = ld4<NT>(g4 + i0 + u * kBlock);
+                    if (HAS_E)
+                        ev[u] = ld4<NT>(e4 + i0 + u * kBlock);
+                }
+#pragma unroll
+            for (int u = 0; u < kSegUnroll; ++u)
+                if (i0 + u * kBlock < v_hi)
+                    acc.add4(HAS_E ? gv[u] + ev[u] : gv[u]);
+            acc.flush();
+        }
+        if (tid < hi - z) {  // tail, at most 3 elements
+            const uint64_t i = z + tid;
+            acc.add(HAS_E ? g[i] + e[i] : g[i]);
+            acc.flush();
+        }
+        // block reduction of this item (the counts are wavefront totals, valid in lane 0: indices grow with the lane)
+        const double wp = wave_sum(acc.s_pos), wn = wave_sum(acc.s_neg);
+        if (lane == 0) {
+            sh_pos[wave] = wp;
+            sh_neg[wave] = wn;
+            sh_cp[wave] = acc.c_pos;
+            sh_cn[wave] = acc.c_neg;
+            sh_cz[wave] = acc.c_zero;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            double sp = 0.0, sn = 0.0;
+            uint64_t cp = 0, cn = 0, cz = 0;
+#pragma unroll
+            for (int k = 0; k < kBlock / 64; ++k) {
+                sp += sh_pos[k];
+                sn += sh_neg[k];
+                cp += sh_cp[k];
+                cn += sh_cn[k];
+                cz += sh_cz[k];
+            }
+            const size_t slot = static_cast<size_t>(p) * sv.num_items + it;
+            sv.r_spos[slot] = sp;
+            sv.r_sneg[slot] = sn;
+            sv.r_npos[slot] = cp;
+            sv.r_nneg[slot] = cn;
+            sv.r_nzero[slot] = cz;
+        }
+        __syncthreads();  // the LDS slots are free again for the next item
+    }
+}
+
+// Second level: grid = (S, P), one wavefront per (segment, worker): that segment's records in a fixed order, then
+// the two local means rounded to fp32 (Sec. 3.1; empty group: 0).
+__global__ __launch_bounds__(64) void k_seg_finalize(const SegView sv)
+{
+    const uint32_t s = blockIdx.x, p = blockIdx.y, lane = threadIdx.x;
+    const uint32_t lo = sv.item_lo[s], hi = sv.item_lo[s + 1];
+    const size_t row = static_cast<size_t>(p) * sv.num_items;
+    double sp = 0.0, sn = 0.0;
+    uint64_t cp = 0, cn = 0, cz = 0;
+    for (uint32_t j = lo + lane; j < hi; j += 64) {
+        sp += sv.r_spos[row + j];
+        sn += sv.r_sneg[row + j];
+        cp += sv.r_npos[row + j];
+        cn += sv.r_nneg[row + j];
+        cz += sv.r_nzero[row + j];
+    }
+    sp = wave_sum(sp);
+    sn = wave_sum(sn);
+    cp = wave_sum(cp);
+    cn = wave_sum(cn);
+    cz = wave_sum(cz);
+    if (lane == 0) {
+        const uint64_t len = sv.seg_end[s] - (s ? sv.seg_end[s - 1] : 0);
+        a2sgd_worker_stats_t r;
+        r.mu_pos = cp ? static_cast<float>(sp / static_cast<double>(cp)) : 0.0f;
+        r.mu_neg = cn ? static_cast<float>(sn / static_cast<double>(cn)) : 0.0f;
+        r.n_pos = cp;
+        r.n_neg = cn;
+        r.n_zero = cz;
+        r.n_nan = len - cp - cn;
+        sv.stats[static_cast<size_t>(p) * sv.S + s] = r;
+    }
+}
+
+// Algorithm 1 line 5 per segment, and the tables the apply pass reads: one thread per segment.
+__global__ __launch_bounds__(64) void k_seg_global(const uint32_t P, const SegView sv)
+{
+    const uint32_t s = blockIdx.x * 64 + threadIdx.x;
+    if (s >= sv.S)
+        return;
+    double sp = 0.0, sn = 0.0;
+    for (uint32_t p = 0; p < P; ++p) {
+        const a2sgd_worker_stats_t &r = sv.stats[static_cast<size_t>(p) * sv.S + s];
+        sp += static_cast<double>(r.mu_pos);
+        sn += static_cast<double>(r.mu_neg);
+        sv.neg_mu_pos[static_cast<size_t>(s) * P + p] = -r.mu_pos;
+        sv.mu_neg[static_cast<size_t>(s) * P + p] = r.mu_neg;
+    }
+    sv.gmu[2 * s] = static_cast<float>(sp / static_cast<double>(P));
+    sv.gmu[2 * s + 1] = -static_cast<float>(sn / static_cast<double>(P));
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Apply pass (Algorithm 1 lines 4, 6, 7 per tensor)
+// ---------------------------------------------------------------------------------------------------------
+
+// Segment of element idx, scanning forward from a segment known to start at or before it.
+__device__ __forceinline__ uint32_t seg_of(const SegView &sv, uint32_t s, uint64_t idx)
+{
+    while (sv.seg_end[s] <= idx)
+        ++s;
+    return s;
+}
+
+// Per-element path for the workgroups that straddle a segment boundary and for the last n % 4 elements.
+template <int MODE, bool HAS_E>
+__device__ __forceinline__ void seg_apply_element(const PtrTable &tab, float *w, const uint64_t idx, const uint32_t s,
+                                                  const uint32_t P, const float eta_over_P, const SegView &sv)
+{
+    const float gmu_pos = sv.gmu[2 * s], neg_gmu_neg = sv.gmu[2 * s + 1];
+    float acc = 0.0f;
+    for (uint32_t p = 0; p < P; ++p) {
+        float v = tab.g[p][idx];
+        if (HAS_E)
+            v += tab.e[p][idx];
+        acc += apply1<MODE>(v, sv.neg_mu_pos[static_cast<size_t>(s) * P + p], sv.mu_neg[static_cast<size_t>(s) * P + p],
+                            gmu_pos, neg_gmu_neg);
+        if (HAS_E)
+            tab.e[p][idx] = v;
+    }
+    w[idx] -= eta_over_P * acc;
+}
+
+// grid = ceil(ceil(n/4) / BLOCK) single-wavefront workgroups, thread t owning float4 group t.  The big loads of
+// the first UP workers are issued first; the segment lookup (two dependent scalar loads) and the loads of that
+// segment's means follow and overlap with them.
+template <int MODE, bool HAS_E, bool NT, int UP, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_seg_apply(const PtrTable tab, float *__restrict__ w, const uint64_t n,
+                                                     const uint32_t P, const float eta_over_P, const SegView sv)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint64_t nvec = n >> 2;
+    const uint64_t first = static_cast<uint64_t>(blockIdx.x) * BLOCK;  // first float4 group of the workgroup
+    const uint64_t i = first + tid;
+    if (first < nvec) {
+        const uint64_t e_first = first << 2;
+        uint64_t e_last = ((first + BLOCK) << 2) - 1;  // last element of the workgroup's float4 groups
+        if (e_last > (nvec << 2) - 1)
+            e_last = (nvec << 2) - 1;
+        const bool live = i < nvec;
+        vf4 *w4 = reinterpret_cast<vf4 *>(w) + i;
+        vf4 wv, v[UP], ev[UP];
+        if (live) {
+            wv = ld4<NT>(w4);
+#pragma unroll
+            for (int u = 0; u < UP; ++u)
+                if (static_cast<uint32_t>(u) < P)
+                    v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[u]) + i);
+            if (HAS_E) {
+#pragma unroll
+                for (int u = 0; u < UP; ++u)
+                    if (static_cast<uint32_t>(u) < P)
+                        ev[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[u]) + i);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        const uint32_t s0 = seg_of(sv, sv.coarse[e_first >> kSegCoarseShift], e_first);
+        if (sv.seg_end[s0] > e_last) {
+            // the whole workgroup lies in segment s0
+            if (live) {
+                const uint32_t lz = opaque_zero();
+                const float *nmp = sv.neg_mu_pos + static_cast<size_t>(s0) * P + lz;
+                const float *mn = sv.mu_neg + static_cast<size_t>(s0) * P + lz;
+                const float gmu_pos = sv.gmu[2 * s0 + lz], neg_gmu_neg = sv.gmu[2 * s0 + 1 + lz];
+                vf4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int u = 0; u < UP; ++u)
+                    if (static_cast<uint32_t>(u) < P) {
+                        const vf4 vv = HAS_E ? v[u] + ev[u] : v[u];
+                        const vf4 err = apply4<MODE>(vv, acc, nmp[u], mn[u], gmu_pos, neg_gmu_neg);
+                        if (HAS_E)
+                            st4<NT>(reinterpret_cast<vf4 *>(tab.e[u]) + i, err);
+                    }
+                for (uint32_t p0 = UP; p0 < P; p0 += UP) {  // further groups of UP workers
+                    vf4 v2[UP], e2[UP];
+#pragma unroll
+                    for (int u = 0; u < UP; ++u)
+                        if (p0 + u < P) {
+                            v2[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + i);
+                            if (HAS_E)
+                                e2[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0 + u]) + i);
+                        }
+#pragma unroll
+                    for (int u = 0; u < UP; ++u)
+                        if (p0 + u < P) {
+                            const vf4 vv = HAS_E ? v2[u] + e2[u] : v2[u];
+                            const vf4 err = apply4<MODE>(vv, acc, nmp[p0 + u], mn[p0 + u], gmu_pos, neg_gmu_neg);
+                            if (HAS_E)
+                                st4<NT>(reinterpret_cast<vf4 *>(tab.e[p0 + u]) + i, err);
+                        }
+                }
+                const vf4 wn = wv - eta_over_P * acc;
+                st4<NT>(w4, wn);
+            }
+        } else if (live) {
+            // a boundary inside the workgroup: element by element (what was loaded above is simply dropped)
+            uint32_t s = s0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint64_t idx = (i << 2) + c;
+                s = seg_of(sv, s, idx);
+                seg_apply_element<MODE, HAS_E>(tab, w, idx, s, P, eta_over_P, sv);
+            }
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
+        const uint64_t idx = (nvec << 2) + tid;
+        const uint32_t s = seg_of(sv, sv.coarse[idx >> kSegCoarseShift], idx);
+        seg_apply_element<MODE, HAS_E>(tab, w, idx, s, P, eta_over_P, sv);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------------------------------------
+
+hipError_t launch_seg_partials(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, void *ws, hipStream_t s)
+{
+    const SegView sv = seg_view(pl, ws);
+    uint32_t B = pl.B;
+    if (B > sv.num_items)
+        B = sv.num_items;
+    const dim3 grid(B, pl.P), block(kBlock);
+    if (has_e) {
+        if (pl.streaming)
+            k_seg_partials<true, true><<<grid, block, 0, s>>>(tab, B, sv);
+        else
+            k_seg_partials<true, false><<<grid, block, 0, s>>>(tab, B, sv);
+    } else {
+        if (pl.streaming)
+            k_seg_partials<false, true><<<grid, block, 0, s>>>(tab, B, sv);
+        else
+            k_seg_partials<false, false><<<grid, block, 0, s>>>(tab, B, sv);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_seg_finalize(const a2sgd_plan_t &pl, void *ws, hipStream_t s)
+{
+    const SegView sv = seg_view(pl, ws);
+    k_seg_finalize<<<dim3(sv.S, pl.P), dim3(64), 0, s>>>(sv);
+    return hipGetLastError();
+}
+
+hipError_t launch_seg_global(const a2sgd_plan_t &pl, void *ws, hipStream_t s)
+{
+    const SegView sv = seg_view(pl, ws);
+    k_seg_global<<<dim3((sv.S + 63) / 64), dim3(64), 0, s>>>(pl.P, sv);
+    return hipGetLastError();
+}
+
+template <int MODE, bool HAS_E, bool NT>
+static hipError_t launch_seg_apply_shape(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eop,
+                                         const SegView &sv, hipStream_t s)
+{
+    constexpr int kThreads = 64;
+    const uint64_t nvec = (pl.n + 3) >> 2;
+    const dim3 grid(static_cast<uint32_t>((nvec + kThreads - 1) / kThreads)), block(kThreads);
+    const uint32_t lds = pl.apply.lds_bytes;
+    if (pl.apply.up == 8)
+        k_seg_apply<MODE, HAS_E, NT, 8, kThreads><<<grid, block, lds, s>>>(tab, w, pl.n, pl.P, eop, sv);
+    else
+        k_seg_apply<MODE, HAS_E, NT, 4, kThreads><<<grid, block, lds, s>>>(tab, w, pl.n, pl.P, eop, sv);
+    return hipGetLastError();
+}
+
+hipError_t launch_seg_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
+                            hipStream_t s)
+{
+    const float eop = static_cast<float>(static_cast<double>(eta) / static_cast<double>(pl.P));
+    const SegView sv = seg_view(pl, ws);
+    const bool lit = pl.mode == A2SGD_MODE_ALG1_LITERAL;
+#define A2SGD_SEG_CASE(L, E, N)                                                                                  \
+    if (lit == L && has_e == E && pl.streaming == N)                                                             \
+        return launch_seg_apply_shape<L ? A2SGD_MODE_ALG1_LITERAL : A2SGD_MODE_RETAINED_ERROR, E, N>(pl, tab, w, eop, \
+                                                                                                     sv, s);
+    A2SGD_SEG_CASE(false, true, true)
+    A2SGD_SEG_CASE(false, true, false)
+    A2SGD_SEG_CASE(false, false, true)
+    A2SGD_SEG_CASE(false, false, false)
+    A2SGD_SEG_CASE(true, true, true)
+    A2SGD_SEG_CASE(true, true, false)
+    A2SGD_SEG_CASE(true, false, true)
+    A2SGD_SEG_CASE(true, false, false)
+#undef A2SGD_SEG_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace a2sgd

@@ -42,7 +42,7 @@ def test_binding_has_the_same_names(A):
 def test_struct_layouts_match_header(A):
     from paper_2006_07405_amd import binding as B
     assert C.sizeof(B.a2sgd_worker_stats_t) == 40
-    assert C.sizeof(B.a2sgd_config_t) == 24
+    assert C.sizeof(B.a2sgd_config_t) == 32
     assert C.sizeof(B.a2sgd_global_stats_t) == 8
 
 
@@ -56,11 +56,11 @@ def test_plan_rejects_bad_config(A, n, P, mode, bpw):
 
 def test_plan_null_pointers(A):
     from paper_2006_07405_amd import binding as B
-    cfg = B.a2sgd_config_t(10, 2, 0, 0, 0)
+    cfg = B.a2sgd_config_t(10, 2, 0, 0, 0, None)
     h = C.c_void_p()
     assert A.raw.a2sgd_plan(None, C.byref(h)) == A.A2SGD_ERR_INVALID_ARG
     assert A.raw.a2sgd_plan(C.byref(cfg), None) == A.A2SGD_ERR_INVALID_ARG
-    cfg.reserved = 1
+    cfg.num_segments = 3  # segments announced, no lengths given
     assert A.raw.a2sgd_plan(C.byref(cfg), C.byref(h)) == A.A2SGD_ERR_INVALID_ARG
     assert A.raw.a2sgd_workspace_bytes(None) == 0
     assert A.raw.a2sgd_plan_destroy(None) == A.A2SGD_OK
@@ -74,6 +74,23 @@ def test_plan_geometry(A):
     assert A.a2sgd_plan_blocks_per_worker(p) == 1
     p = A.a2sgd_plan(1000, 2, blocks_per_worker=7)
     assert A.a2sgd_plan_blocks_per_worker(p) == 7
+
+
+def test_segmented_plan_validation_and_workspace(A):
+    for bad in ([5, 4], [5, 6], [10, 0], [0, 10], [3, 3, 3]):
+        with pytest.raises(A.A2sgdError) as ei:
+            A.a2sgd_plan(10, 2, 0, 0, seg_lengths=bad)
+        assert ei.value.status == A.A2SGD_ERR_INVALID_ARG
+    whole = A.a2sgd_plan(1_000_000, 4)
+    seg = A.a2sgd_plan(1_000_000, 4, 0, 0, seg_lengths=[1, 70_000, 3, 929_996])
+    assert A.a2sgd_workspace_bytes(seg) > A.a2sgd_workspace_bytes(whole)
+    one = A.a2sgd_plan(1_000_000, 4, 0, 0, seg_lengths=[1_000_000])  # a single segment is the whole-model method
+    assert A.a2sgd_workspace_bytes(one) == A.a2sgd_workspace_bytes(whole) and one.num_segments == 0
+    R = A.raw
+    assert R.a2sgd_read_stats(seg.handle, 0x30000, None, None, None) == A.A2SGD_ERR_INVALID_ARG
+    assert R.a2sgd_read_segment_stats(whole.handle, 0x30000, None, None, None) == A.A2SGD_ERR_INVALID_ARG
+    assert R.a2sgd_lazy_reset(seg.handle, 0x30000, None) == A.A2SGD_ERR_INVALID_ARG
+    assert R.a2sgd_workspace_init(whole.handle, 0x30000, None) == A.A2SGD_OK  # nothing to upload
 
 
 def _tab(vals):

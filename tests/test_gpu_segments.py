@@ -1,0 +1,148 @@
+"""GPU parity of the per-tensor variant: one pair of means per worker and tensor.  The oracle is the whole-model
+oracle applied to every tensor's slice (oracle.step_segmented)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import a2sgd_oracle as O
+from tests.helpers import assert_array_close, close, dev
+
+pytestmark = pytest.mark.gpu
+f32 = np.float32
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2006_07405_amd as A
+    assert torch.cuda.is_available()
+    return A
+
+
+def run_case(A, g, e, w, eta, mode, seg, split_calls=True):
+    P, n = len(g), int(w.shape[0])
+    plan = A.a2sgd_plan(n, P, mode, 0, seg_lengths=seg)
+    ws = A.alloc_workspace(plan)
+    gd = [dev(x) for x in g]
+    ed = [dev(x) for x in e] if e is not None else None
+    wd = dev(w)
+    if split_calls:
+        A.a2sgd_local_averages(plan, gd, ed, ws)
+        A.a2sgd_global_average(plan, ws)
+        A.a2sgd_apply_and_update_error(plan, gd, ed, wd, eta, ws)
+    else:
+        A.a2sgd_step(plan, gd, ed, wd, eta, ws)
+    stats, gmu = A.a2sgd_read_segment_stats(plan, ws)
+    per_seg, e_ref, w_ref = O.step_segmented(g, e, w, eta, mode, seg)
+    for s, r in enumerate(per_seg):
+        for p in range(P):
+            a, b = stats[p][s], r.workers[p]
+            assert (a.n_pos, a.n_neg, a.n_zero, a.n_nan) == (b.n_pos, b.n_neg, b.n_zero, b.n_nan), f"segment {s} worker {p}"
+            close(a.mu_pos, b.mu_pos, f"segment {s} worker {p} mu_pos")
+            close(a.mu_neg, b.mu_neg, f"segment {s} worker {p} mu_neg")
+        close(gmu[s][0], r.gmu_pos, f"segment {s} gmu_pos")
+        close(gmu[s][1], r.gmu_neg, f"segment {s} gmu_neg")
+    # tolerance per tensor: the rms that scales it is the tensor's own
+    off = 0
+    for s, length in enumerate(seg):
+        lo, hi = off, off + length
+        if ed is not None:
+            for p in range(P):
+                assert_array_close(ed[p][lo:hi].cpu().numpy(), e_ref[p][lo:hi], f"e[{p}] segment {s}")
+        assert_array_close(wd[lo:hi].cpu().numpy(), w_ref[lo:hi], f"w segment {s}")
+        off = hi
+    return stats, gmu
+
+
+def make_case(seed, n, P, scales):
+    """Per-segment scales make a wrong segment assignment visible at once."""
+    rng = np.random.default_rng(seed)
+    g = [(rng.standard_normal(n)).astype(f32) * scales for _ in range(P)]
+    e = [(rng.standard_normal(n) * 0.5).astype(f32) * scales for _ in range(P)]
+    w = (rng.standard_normal(n) * 0.02).astype(f32)
+    return [x.astype(f32) for x in g], [x.astype(f32) for x in e], w
+
+
+def scales_for(seg, seed):
+    rng = np.random.default_rng(seed)
+    return np.concatenate([np.full(L, 10.0 ** rng.uniform(-5, -2), dtype=f32) for L in seg])
+
+
+LAYOUTS = [
+    [1, 1],
+    [3, 2],
+    [1, 2, 3, 4, 5, 6, 7],
+    [255, 1, 256, 3, 257],
+    [4096, 1, 4095, 2, 4097],
+    [65_536, 65_537, 65_535, 1, 131_073],
+    [5] * 300,
+    [1000, 1] * 50 + [70_001],
+    [300_001, 7, 200_000],
+]
+
+
+@pytest.mark.parametrize("seg", LAYOUTS, ids=[f"layout{i}" for i in range(len(LAYOUTS))])
+def test_segment_layouts(A, seg):
+    n = sum(seg)
+    for P, mode, with_e, split in ((1, 0, True, True), (3, 0, True, False), (4, 1, True, True), (5, 1, False, False),
+                                   (9, 0, True, True)):
+        print(f"case S={len(seg)} n={n} P={P} mode={mode} e={with_e}", flush=True)
+        g, e, w = make_case(n + P, n, P, scales_for(seg, n))
+        run_case(A, g, e if with_e else None, w, 0.1, mode, seg, split_calls=split)
+
+
+@pytest.mark.parametrize("k", [2, 3, 4, 5])
+def test_small_model_shapes(A, k):
+    wl = workloads.small(k)
+    P = wl.num_workers
+    seg = [numel for _, numel in wl.tensors]
+    g = [wl.gradient(p).numpy() for p in range(P)]
+    e = [wl.synthetic_error(p).numpy() for p in range(P)]
+    w = wl.weights().numpy()
+    run_case(A, g, e, w, wl.eta, 0, seg)
+
+
+def test_empty_groups_and_nan_per_segment(A):
+    seg = [4, 4, 5]
+    g = [np.array([1, 2, 3, 0, -1, -2, -3, -2, 1, -1, np.nan, 2, -2], f32)]
+    e = [np.zeros(13, f32)]
+    stats, gmu = run_case(A, g, e, np.zeros(13, f32), 1.0, 0, seg)
+    assert (stats[0][0].n_neg, stats[0][0].mu_neg, stats[0][1].n_pos, stats[0][1].mu_pos) == (0, 0.0, 0, 0.0)
+    assert stats[0][2].n_nan == 1 and stats[0][2].n_pos == 2 and stats[0][2].n_neg == 2
+
+
+def test_one_segment_is_the_whole_model_method(A):
+    g, e, w = make_case(3, 50_001, 3, np.full(50_001, 1e-3, f32))
+    plan_seg = A.a2sgd_plan(50_001, 3, 0, 0, seg_lengths=[50_001])
+    assert plan_seg.num_segments == 0  # treated as whole-model
+
+
+def test_config2_full_size_per_tensor(A):
+    """ResNet-50 shape, 161 tensors, 25.6 M parameters, 8 workers, inputs generated on the device: every tensor's
+    counts and means against the oracle, e and w on the first and last tensors and on the largest one."""
+    wl = workloads.config2()
+    n, P = wl.n, wl.num_workers
+    seg = [numel for _, numel in wl.tensors]
+    plan = A.a2sgd_plan(n, P, 0, 0, seg_lengths=seg)
+    ws = A.alloc_workspace(plan)
+    g = [wl.gradient(p, 0, device="cuda") for p in range(P)]
+    e = [wl.synthetic_error(p, device="cuda") for p in range(P)]
+    w = wl.weights(device="cuda")
+    gh, eh, wh = [x.cpu().numpy() for x in g], [x.cpu().numpy() for x in e], w.cpu().numpy()
+    A.a2sgd_step(plan, g, e, w, wl.eta, ws)
+    stats, gmu = A.a2sgd_read_segment_stats(plan, ws)
+    per_seg, e_ref, w_ref = O.step_segmented(gh, eh, wh, wl.eta, 0, seg)
+    offs = np.concatenate([[0], np.cumsum(seg)])
+    for s, r in enumerate(per_seg):
+        for p in range(P):
+            a, b = stats[p][s], r.workers[p]
+            assert (a.n_pos, a.n_neg, a.n_zero, a.n_nan) == (b.n_pos, b.n_neg, b.n_zero, b.n_nan)
+            close(a.mu_pos, b.mu_pos, f"tensor {s} worker {p} mu_pos")
+            close(a.mu_neg, b.mu_neg, f"tensor {s} worker {p} mu_neg")
+        close(gmu[s][0], r.gmu_pos, f"tensor {s}")
+        close(gmu[s][1], r.gmu_neg, f"tensor {s}")
+    for s in sorted(set([0, 1, 2, len(seg) - 2, len(seg) - 1, int(np.argmax(seg))] + list(range(3, len(seg), 13)))):
+        lo, hi = int(offs[s]), int(offs[s + 1])
+        for p in range(P):
+            assert_array_close(e[p][lo:hi].cpu().numpy(), e_ref[p][lo:hi], f"e[{p}] tensor {s}")
+        assert_array_close(w[lo:hi].cpu().numpy(), w_ref[lo:hi], f"w tensor {s}")
