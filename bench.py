@@ -37,6 +37,8 @@ def main() -> int:
     ap.add_argument("--blocks-per-worker", type=int, default=0)
     ap.add_argument("--n", type=int, default=0, help="override n (config 1 only: one flat tensor)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-tensor", action="store_true",
+                    help="one pair of means per worker and tensor of the workload's layout instead of per worker")
     ap.add_argument("--single-call", action="store_true",
                     help="time a2sgd_step (one call per step; a single cooperative launch when the model fits the "
                          "caches) instead of the three calls with events between them")
@@ -67,7 +69,8 @@ def main() -> int:
     for p in range(P):
         wl.gradient(p, 0, out=g[p])
     wl.weights(out=w)
-    plan = A.a2sgd_plan(n, P, A.A2SGD_MODE_RETAINED_ERROR, args.blocks_per_worker)
+    seg = [numel for _, numel in wl.tensors] if args.per_tensor else None
+    plan = A.a2sgd_plan(n, P, A.A2SGD_MODE_RETAINED_ERROR, args.blocks_per_worker, seg_lengths=seg)
     ws = A.alloc_workspace(plan)
 
     def step(ev=None):
@@ -116,7 +119,11 @@ def main() -> int:
         ms_global = sum(ev[1].elapsed_time(ev[2]) for ev in events) / args.steps
         ms_apply = sum(ev[2].elapsed_time(ev[3]) for ev in events) / args.steps
     achieved = bytes_apply / (ms_apply * 1e-3) / 1e9
-    stats, gmu = A.a2sgd_read_stats(plan, ws)
+    if plan.num_segments:
+        seg_stats, seg_gmu = A.a2sgd_read_segment_stats(plan, ws)
+        stats, gmu = [row[0] for row in seg_stats], seg_gmu[0]
+    else:
+        stats, gmu = A.a2sgd_read_stats(plan, ws)
 
     out = {
         "metric": "a2sgd_step_params_per_s",
@@ -132,7 +139,7 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"config{args.config}:{wl.name}", "n": n, "num_workers": P, "seed": wl.seed,
-                   "recipe": wl.recipe, "mode": "retained_error", "eta": wl.eta,
+                   "recipe": wl.recipe, "mode": "retained_error", "eta": wl.eta, "per_tensor_means": plan.num_segments,
                    "blocks_per_worker": A.a2sgd_plan_blocks_per_worker(plan)},
         "step_hbm_gbps": bytes_step / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
@@ -158,6 +165,12 @@ def main() -> int:
     ms_dense = ev0.elapsed_time(ev1) / 5
     out["dense_step"] = {"ms": ms_dense, "gbps": (4 * n * P + 8 * n) / (ms_dense * 1e-3) / 1e9,
                          "params_per_s": n / (ms_dense * 1e-3)}
+
+    if plan.num_segments:  # the lazy state is not offered with per-tensor means
+        if not args.no_cpu_baseline:
+            out["cpu_baseline"] = cpu_baseline(wl, g, w, min(args.cpu_sample, n))
+        print(json.dumps(out))
+        return 0
 
     # Also outside the timed region: the same step on the lazy error state (16nP + 8n bytes: the buffers keep v and
     # the error is formed on the next read).  Same results bit for bit; a different contract for what e holds.

@@ -80,7 +80,7 @@ namespace a2sgd {
 
 // ---- per-tensor means: static tables the plan builds on the host and a2sgd_workspace_init uploads --------------
 constexpr uint32_t kSegItemElems = 65536;  // a work item of the segmented reduction covers at most this many elements
-constexpr uint32_t kSegCoarseShift = 14;   // the coarse lookup table has one entry per 2^14 elements
+constexpr uint32_t kSegCoarseShift = 8;    // the lookup table has one entry per 2^8 elements: one per apply workgroup
 
 struct SegItem {  // one work item: a run of elements inside one segment
     uint64_t start;
@@ -95,7 +95,7 @@ struct SegView {
     const uint64_t *seg_end;   // [S] exclusive end of every segment
     const SegItem *item;       // [num_items], ascending start
     const uint32_t *item_lo;   // [S + 1]: items of segment s are item_lo[s] .. item_lo[s + 1] - 1
-    const uint32_t *coarse;    // [ceil(n / 2^14)]: segment of element k * 2^14
+    const uint32_t *coarse;    // [ceil(n / 2^8)]: segment of element k * 2^8
     a2sgd_worker_stats_t *stats;  // [P][S]
     float *neg_mu_pos, *mu_neg;   // [S][P], packed for the apply pass
     float *gmu;                   // [S][2]: gmu_pos, -gmu_neg

@@ -6,7 +6,7 @@
 // The plan splits every segment into work items of at most kSegItemElems elements that never cross a segment
 // boundary.  Reduction: one partial record per (worker, item); second level per (worker, segment) over that
 // segment's items in index order; then the per-segment global means.  The apply pass is the one-shot
-// single-wavefront shape of k_apply; a workgroup looks its segment up through a coarse table, and the few
+// single-wavefront shape of k_apply; a workgroup reads its segment from a table with one entry per workgroup, and the few
 // workgroups that straddle a boundary fall back to a per-element path.
 #include "a2sgd_device.h"
 
@@ -203,8 +203,8 @@ __device__ __forceinline__ void seg_apply_element(const PtrTable &tab, float *w,
 }
 
 // grid = ceil(ceil(n/4) / BLOCK) single-wavefront workgroups, thread t owning float4 group t.  The big loads of
-// the first UP workers are issued first; the segment lookup (two dependent scalar loads) and the loads of that
-// segment's means follow and overlap with them.
+// the first UP workers are issued first; the segment lookup and, behind it, the loads of that segment's end and
+// means follow and overlap with them.
 template <int MODE, bool HAS_E, bool NT, int UP, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void k_seg_apply(const PtrTable tab, float *__restrict__ w, const uint64_t n,
                                                      const uint32_t P, const float eta_over_P, const SegView sv)
@@ -214,7 +214,6 @@ __global__ __launch_bounds__(BLOCK) void k_seg_apply(const PtrTable tab, float *
     const uint64_t first = static_cast<uint64_t>(blockIdx.x) * BLOCK;  // first float4 group of the workgroup
     const uint64_t i = first + tid;
     if (first < nvec) {
-        const uint64_t e_first = first << 2;
         uint64_t e_last = ((first + BLOCK) << 2) - 1;  // last element of the workgroup's float4 groups
         if (e_last > (nvec << 2) - 1)
             e_last = (nvec << 2) - 1;
@@ -235,7 +234,9 @@ __global__ __launch_bounds__(BLOCK) void k_seg_apply(const PtrTable tab, float *
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        const uint32_t s0 = seg_of(sv, sv.coarse[e_first >> kSegCoarseShift], e_first);
+        // the table has exactly one entry per workgroup: the segment of its first element
+        static_assert(BLOCK * 4 == (1 << kSegCoarseShift), "one lookup entry per apply workgroup");
+        const uint32_t s0 = sv.coarse[blockIdx.x];
         if (sv.seg_end[s0] > e_last) {
             // the whole workgroup lies in segment s0
             if (live) {
