@@ -275,14 +275,35 @@ __global__ __launch_bounds__(BLOCK) void k_seg_apply(const PtrTable tab, float *
                 st4<NT>(w4, wn);
             }
         } else if (live) {
-            // a boundary inside the workgroup: element by element (what was loaded above is simply dropped)
-            uint32_t s = s0;
+            // A boundary inside the workgroup: each of the lane's four elements has its own segment.  Still one
+            // float4 per worker and array; only the means are gathered per element.  (What was loaded above is
+            // reloaded, from the cache, to keep this rare path simple.)
+            uint32_t sc[4];
+            uint32_t sx = s0;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const uint64_t idx = (i << 2) + c;
-                s = seg_of(sv, s, idx);
-                seg_apply_element<MODE, HAS_E>(tab, w, idx, s, P, eta_over_P, sv);
+                sx = seg_of(sv, sx, (i << 2) + c);
+                sc[c] = sx;
             }
+            vf4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+            for (uint32_t p = 0; p < P; ++p) {
+                vf4 vv = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p]) + i);
+                if (HAS_E)
+                    vv += ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p]) + i);
+                float x[4] = {vv.x, vv.y, vv.z, vv.w}, a[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const size_t k = static_cast<size_t>(sc[c]) * P + p;
+                    a[c] += apply1<MODE>(x[c], sv.neg_mu_pos[k], sv.mu_neg[k], sv.gmu[2 * sc[c]], sv.gmu[2 * sc[c] + 1]);
+                }
+                acc = vf4{a[0], a[1], a[2], a[3]};
+                if (HAS_E) {
+                    const vf4 err = vf4{x[0], x[1], x[2], x[3]};
+                    st4<NT>(reinterpret_cast<vf4 *>(tab.e[p]) + i, err);
+                }
+            }
+            const vf4 wn = wv - eta_over_P * acc;
+            st4<NT>(w4, wn);
         }
     }
     if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
@@ -338,7 +359,9 @@ static hipError_t launch_seg_apply_shape(const a2sgd_plan_t &pl, const PtrTable 
     constexpr int kThreads = 64;
     const uint64_t nvec = (pl.n + 3) >> 2;
     const dim3 grid(static_cast<uint32_t>((nvec + kThreads - 1) / kThreads)), block(kThreads);
-    const uint32_t lds = pl.apply.lds_bytes;
+    // The segment lookup sits between a workgroup's big loads and its arithmetic and makes it live longer, so more
+    // workgroups per CU are wanted than in k_apply for the same bytes in flight (measured: 10 instead of 6 at P = 4).
+    const uint32_t lds = pl.apply.lds_bytes * 5 / 8;
     if (pl.apply.up == 8)
         k_seg_apply<MODE, HAS_E, NT, 8, kThreads><<<grid, block, lds, s>>>(tab, w, pl.n, pl.P, eop, sv);
     else
