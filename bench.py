@@ -107,6 +107,7 @@ def main() -> int:
     t1 = time.perf_counter()
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_median = None if args.single_call else sorted(ev[0].elapsed_time(ev[3]) for ev in events)[args.steps // 2]
     bytes_reduce = 8 * n * P
     bytes_apply = 12 * n * P + 8 * n
     bytes_step = bytes_reduce + bytes_apply
@@ -141,6 +142,8 @@ def main() -> int:
         "config": {"workload": f"config{args.config}:{wl.name}", "n": n, "num_workers": P, "seed": wl.seed,
                    "recipe": wl.recipe, "mode": "retained_error", "eta": wl.eta, "per_tensor_means": plan.num_segments,
                    "blocks_per_worker": A.a2sgd_plan_blocks_per_worker(plan)},
+        "ms_per_step_median_events": ms_median,
+        "worker_params_per_s": n * P / (ms_per_step * 1e-3),
         "step_hbm_gbps": bytes_step / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "kernels_ms": {"local_averages": ms_reduce, "global_average": ms_global, "apply_and_update_error": ms_apply},
@@ -166,6 +169,24 @@ def main() -> int:
     out["dense_step"] = {"ms": ms_dense, "gbps": (4 * n * P + 8 * n) / (ms_dense * 1e-3) / 1e9,
                          "params_per_s": n / (ms_dense * 1e-3)}
 
+    # A plain device-to-device copy of n floats (torch's, 8n bytes): the measured ceiling for a stream that reads
+    # and writes, next to the published peak; and the peak that the device properties give.
+    scratch = torch.empty_like(w)
+    scratch.copy_(w)
+    ev0.record()
+    for _ in range(5):
+        scratch.copy_(w)
+    ev1.record()
+    torch.cuda.synchronize()
+    del scratch
+    props = torch.cuda.get_device_properties(0)
+    clock_khz, bus_bits = getattr(props, "memory_clock_rate", None), getattr(props, "memory_bus_width", None)
+    out["hbm_reference"] = {"published_peak_gbps": HBM_PEAK_GBPS, "used_for_frac": "published_peak_gbps",
+                            "plain_copy_gbps": 8 * n / (ev0.elapsed_time(ev1) / 5 * 1e-3) / 1e9,
+                            "device_props": {"memory_clock_khz": clock_khz, "memory_bus_bits": bus_bits,
+                                             "ddr_peak_gbps": None if not (clock_khz and bus_bits)
+                                             else 2 * clock_khz * 1e3 * bus_bits / 8 / 1e9}}
+
     if plan.num_segments:  # the lazy state is not offered with per-tensor means
         if not args.no_cpu_baseline:
             out["cpu_baseline"] = cpu_baseline(wl, g, w, min(args.cpu_sample, n))
@@ -189,8 +210,45 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, g, w, min(args.cpu_sample, n))
+        out["cpu_baseline_threads"] = cpu_baseline_threads(wl, g, w, min(args.cpu_sample, n))
     print(json.dumps(out))
     return 0
+
+
+def cpu_baseline_threads(wl, g, w, m, chunk=1 << 22):
+    """The same oracle calls on the same sample from a pool of host threads (the C calls release the interpreter
+    lock): pass A runs one worker's accumulator per thread, fed in index order as the single-threaded run does;
+    pass B runs one index chunk per task.  The arithmetic and its order per worker are the oracle's own."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import a2sgd_oracle as O
+    P = wl.num_workers
+    threads = max(1, min(16, len(os.sched_getaffinity(0))))
+    gh = [x[:m].cpu().numpy() for x in g]
+    eh = [np.zeros(m, dtype=np.float32) for _ in range(P)]
+    wh = w[:m].cpu().numpy()
+    O.lib()
+
+    def pass_a(p):
+        acc = O.LocalAccumulator()
+        for lo in range(0, m, chunk):
+            acc.feed(gh[p][lo:min(m, lo + chunk)], eh[p][lo:min(m, lo + chunk)])
+        return acc.stats()
+
+    with ThreadPoolExecutor(threads) as pool:
+        t0 = time.perf_counter()
+        workers = list(pool.map(pass_a, range(P)))
+        gp, gn = O.global_means(workers)
+
+        def pass_b(lo):
+            hi = min(m, lo + chunk)
+            O.apply_chunk([x[lo:hi] for x in gh], [x[lo:hi] for x in eh], wh[lo:hi], workers, gp, gn, wl.eta, O.RETAINED_ERROR)
+
+        list(pool.map(pass_b, range(0, m, chunk)))
+        dt = time.perf_counter() - t0
+    return {"value": m / dt, "unit": "params/s", "cores": threads, "kind": "oracle", "seconds": dt,
+            "sample": f"first {m} of {wl.n} parameters of all {P} workers, one whole step; pass A on min(P, cores) "
+                      f"threads (one worker each), pass B on {threads} threads (one chunk each), e = 0"}
 
 
 def cpu_baseline(wl, g, w, m):

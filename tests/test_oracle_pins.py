@@ -137,6 +137,46 @@ def test_brute_force_exact_rationals():
     check_brute_force()
 
 
+def test_per_tensor_variant_worked_example_and_brute_force():
+    """The per-tensor variant is Sec. 3.1 / Algorithm 1 lines 3-7 restricted to each tensor.  Pinned by a case
+    worked by hand (the step-1 gradients of the worked example cut into two tensors of three elements) and by the
+    exact-rational brute force on every tensor of random splits."""
+    gA, gB = arr([1, -2, 3, 0, -4, 2]), arr([-1, -3, 2, -2, 4, 0])
+    zero = arr([0] * 6)
+    per_seg, e_new, w_new = O.step_segmented([gA, gB], [zero, zero], zero, 0.5, O.RETAINED_ERROR, [3, 3])
+    # tensor 0: A = [1,-2,3] and B = [-1,-3,2] both have mu+ = 2, mu- = 2
+    # tensor 1: A = [0,-4,2] has mu+ = 1, mu- = 4; B = [-2,4,0] has mu+ = 2, mu- = 2; global 1.5 and 3
+    assert [(s.mu_pos, s.mu_neg) for s in per_seg[0].workers] == [(2.0, 2.0), (2.0, 2.0)]
+    assert [(s.mu_pos, s.mu_neg) for s in per_seg[1].workers] == [(1.0, 4.0), (2.0, 2.0)]
+    assert (per_seg[0].gmu_pos, per_seg[0].gmu_neg) == (2.0, 2.0)
+    assert (per_seg[1].gmu_pos, per_seg[1].gmu_neg) == (1.5, 3.0)
+    assert e_new[0].tolist() == [-1, 0, 1, -1, 0, 1]
+    assert e_new[1].tolist() == [1, -1, 0, 0, 2, -2]
+    assert w_new.tolist() == [0, 1, -1, 0.375, 0.375, -0.75]
+
+    rng = np.random.default_rng(77)
+    for _ in range(25):
+        P, S = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        seg = [int(x) for x in rng.integers(1, 7, S)]
+        n = sum(seg)
+        g = [arr(rng.integers(-32, 33, n) / 8.0) for _ in range(P)]
+        e = [arr(rng.integers(-16, 17, n) / 8.0) for _ in range(P)]
+        w = arr(rng.integers(-64, 65, n) / 16.0)
+        for mode in (O.RETAINED_ERROR, O.ALG1_LITERAL):
+            per_seg, e_new, w_new = O.step_segmented(g, e, w, 0.25, mode, seg)
+            off = 0
+            for k, length in enumerate(seg):
+                sl = slice(off, off + length)
+                mu_pos, mu_neg, gp, gn, err, wn = brute_force([x[sl] for x in g], [x[sl] for x in e], w[sl], 0.25, mode)
+                assert [s.mu_pos for s in per_seg[k].workers] == [float(x) for x in mu_pos]
+                assert [s.mu_neg for s in per_seg[k].workers] == [float(x) for x in mu_neg]
+                assert (per_seg[k].gmu_pos, per_seg[k].gmu_neg) == (float(gp), float(gn))
+                for p in range(P):
+                    assert e_new[p][sl].tolist() == [float(x) for x in err[p]]
+                assert w_new[sl].tolist() == [float(x) for x in wn]
+                off += length
+
+
 # ---------------------------------------------------------------------------------------------------------
 # exactly rounded means: math.fsum is an exact sum, so fl32(fsum/n) is the definition's value
 # ---------------------------------------------------------------------------------------------------------
