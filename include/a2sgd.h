@@ -92,7 +92,8 @@ a2sgd_status_t a2sgd_plan_destroy(a2sgd_plan_t *plan);
 
 /* Bytes of device workspace the caller must provide (16-byte aligned) to the calls below.  Its contents need
  * no initialisation; it carries the block partials, the per-worker means and counts and the global means from
- * one call of a step to the next.  Returns 0 for a NULL plan. */
+ * one call of a step to the next.  For a whole-model plan it includes the records of the lazy calls' reduction
+ * pass (40 bytes per 2048 elements and worker).  Returns 0 for a NULL plan. */
 size_t a2sgd_workspace_bytes(const a2sgd_plan_t *plan);
 
 /* Algorithm 1 line 3.  For every worker p: one pass over v^p = fl32(g^p + e^p) giving n_pos = #{v >= 0},

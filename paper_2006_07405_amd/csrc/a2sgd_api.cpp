@@ -211,6 +211,16 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
     const size_t partials = 5ull * 8ull * pl->P * rows;
     const size_t drift = 2ull * 8ull * pl->P * (kDriftBlocks + 1);  // the drift diagnostic reuses the same region
     pl->workspace_bytes = kHeaderBytes + (partials > drift ? partials : drift);
+    pl->lazy_blocks = pl->lazy_folded = 0;
+    pl->lazy_offset = 0;
+    if (cfg->num_segments <= 1) {
+        // one record per workgroup of the lazy state's one-shot reduction pass, and their folded table
+        const uint64_t per = 64ull * kLazyItems, nvec = pl->n >> 2;
+        pl->lazy_blocks = static_cast<uint32_t>(nvec ? (nvec + per - 1) / per : 1);
+        pl->lazy_folded = (pl->lazy_blocks + kFoldSpan - 1) / kFoldSpan;
+        pl->lazy_offset = (pl->workspace_bytes + 255) & ~static_cast<size_t>(255);
+        pl->workspace_bytes = pl->lazy_offset + 5ull * 8ull * pl->P * (static_cast<size_t>(pl->lazy_blocks) + pl->lazy_folded);
+    }
     if (cfg->num_segments > 1) {
         try {
             build_segments(*pl, cfg->num_segments, cfg->seg_length);
@@ -492,13 +502,7 @@ a2sgd_status_t a2sgd_lazy_step(const a2sgd_plan_t *plan, const float *const *g, 
     fill_table(tab, plan->P, g, s);
     plan->last_token = 0;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    // The reduction pass of the lazy step also writes; measured best with one workgroup per CU, half of what the
-    // read-only pass wants.  The records and their second-level pass use the same halved count.
-    a2sgd_plan_t half = *plan;
-    half.B = plan->B > 1 ? (plan->B + 1) / 2 : 1;
-    if ((st = dev(launch_lazy_partials(half, tab, workspace, hs))) != A2SGD_OK)
-        return st;
-    if ((st = dev(launch_local_finalize(half, workspace, hs))) != A2SGD_OK)
+    if ((st = dev(launch_lazy_partials(*plan, tab, workspace, hs))) != A2SGD_OK)
         return st;
     if ((st = dev(launch_global_average(*plan, workspace, hs))) != A2SGD_OK)
         return st;

@@ -18,12 +18,16 @@ constexpr int kReduceUnroll = 4;      // float4 loads per array per thread per t
 constexpr uint32_t kMaxBlocksPerWorker = 65536;
 constexpr int kFusedBlock = 512;       // threads per workgroup of the single-launch step
 constexpr uint32_t kBarrierSlots = 64;  // grid-barrier cells of the single-launch step, one per plan (mod 64)
+constexpr int kLazyItems = 8;           // float4 groups per array per thread in the lazy state's reduction pass
+constexpr uint32_t kFoldSpan = 4096;    // records that one workgroup of k_fold_partials adds up
 
 // Device workspace, in this order:
 //   WsHeader                                   (kHeaderBytes, padded)
 //   double   s_pos [P][B]   block partial sums of v over v >= 0
 //   double   s_neg [P][B]   block partial sums of |v| over v < 0
 //   uint64_t n_pos [P][B], n_neg [P][B], n_zero [P][B]
+//   whole-model plans only, at plan.lazy_offset: the same five arrays as [P][lazy_blocks] (one record per
+//   workgroup of the lazy state's reduction pass), then as [P][lazy_folded]
 struct WsHeader {
     float gmu_pos, gmu_neg;  // Algorithm 1 line 5
     uint32_t failed_token;   // set to the launch's token by a single-launch step that could not complete
@@ -41,9 +45,9 @@ struct Partials {
     uint64_t *n_pos, *n_neg, *n_zero;
 };
 
-inline Partials partials_of(void *workspace, uint32_t P, uint32_t B)
+inline Partials partials_at(void *workspace, size_t offset, uint32_t P, uint32_t B)
 {
-    char *base = static_cast<char *>(workspace) + kHeaderBytes;
+    char *base = static_cast<char *>(workspace) + offset;
     const size_t stride = static_cast<size_t>(P) * B * 8;
     Partials q;
     q.s_pos = reinterpret_cast<double *>(base);
@@ -52,6 +56,11 @@ inline Partials partials_of(void *workspace, uint32_t P, uint32_t B)
     q.n_neg = reinterpret_cast<uint64_t *>(base + 3 * stride);
     q.n_zero = reinterpret_cast<uint64_t *>(base + 4 * stride);
     return q;
+}
+
+inline Partials partials_of(void *workspace, uint32_t P, uint32_t B)
+{
+    return partials_at(workspace, kHeaderBytes, P, B);
 }
 
 // Kernel argument block: the P device pointers of each kind, passed by value (1 KiB of kernarg).
@@ -126,6 +135,9 @@ struct a2sgd_plan {
     uint32_t barrier_slot;
     mutable uint32_t last_token;  // token of the last single-launch step enqueued with this plan; 0 = none
     a2sgd::SegPlan seg;
+    uint32_t lazy_blocks;  // workgroups per worker of the lazy state's reduction pass (one record each)
+    uint32_t lazy_folded;  // records per worker after k_fold_partials
+    size_t lazy_offset;    // byte offset of those records in the workspace; 0 = the plan has no lazy state
     size_t workspace_bytes;
 };
 

@@ -846,87 +846,125 @@ __device__ __forceinline__ vf4 pending_error4(vf4 s, float neg_mu_pos, float mu_
                pending_error(s.z, neg_mu_pos, mu_neg), pending_error(s.w, neg_mu_pos, mu_neg)};
 }
 
-// Reduction pass on the lazy state.  Same grid, tiling and combination order as k_local_partials; each element
-// is e = pending error of the stored value, v = fl32(g + e), v is written back in place of the stored value and
-// enters the sums and counts.  tab.e holds the state buffers.  8 bytes read and 4 written per element-worker.
+// Reduction pass on the lazy state: each element is e = pending error of the stored value, v = fl32(g + e); v is
+// written back in place of the stored value and enters the sums and counts.  tab.e holds the state buffers.
+// 8 bytes read and 4 written per element-worker.  Because it stores, it has the shape of the apply pass and not of
+// k_local_partials: grid = (blocks, P) of single-wavefront workgroups launched once, each with kLazyItems float4
+// groups per thread, all loads issued before the first store (a loop would wait for its own older stores before
+// it could use newer loads, since both are counted together).  Every workgroup writes one record; the records
+// of a worker are combined in index order by k_fold_partials and k_local_finalize.
 template <bool NT>
-__global__ __launch_bounds__(kBlock) void k_lazy_partials(const PtrTable tab, const uint64_t n, const uint32_t B,
-                                                          const WsHeader *__restrict__ hdr, Partials out)
+__global__ __launch_bounds__(64) void k_lazy_partials(const PtrTable tab, const uint64_t n, const uint32_t blocks,
+                                                      const WsHeader *__restrict__ hdr, Partials out)
 {
     const uint32_t p = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
+    const uint32_t lz = opaque_zero();
+    // the means of the step that stored the values
+    const float nmp = hdr->neg_mu_pos[p + lz], mn = hdr->mu_neg[p + lz];
     const float *__restrict__ g = tab.g[p];
     float *s = tab.e[p];
     const vf4 *__restrict__ g4 = reinterpret_cast<const vf4 *>(g);
     vf4 *s4 = reinterpret_cast<vf4 *>(s);
-    const float nmp = hdr->neg_mu_pos[p], mn = hdr->mu_neg[p];  // the means of the step that stored the values
-
     const uint64_t nvec = n >> 2;
-    constexpr uint64_t kTile = static_cast<uint64_t>(kBlock) * kReduceUnroll;
-    const uint64_t ntile = nvec / kTile;
+    constexpr uint64_t kPer = 64ull * kLazyItems;
+    const uint64_t base = static_cast<uint64_t>(b) * kPer + tid;
 
     LaneAcc acc;
-    for (uint64_t t = b; t < ntile; t += B) {
-        const uint64_t base = t * kTile + tid;
-        vf4 gv[kReduceUnroll], sv[kReduceUnroll];
+    if ((static_cast<uint64_t>(b) + 1) * kPer <= nvec) {
+        vf4 gv[kLazyItems], sv[kLazyItems];
 #pragma unroll
-        for (int u = 0; u < kReduceUnroll; ++u)
-            gv[u] = ld4<NT>(g4 + base + u * kBlock);
+        for (int u = 0; u < kLazyItems; ++u)
+            gv[u] = ld4<NT>(g4 + base + u * 64);
 #pragma unroll
-        for (int u = 0; u < kReduceUnroll; ++u)
-            sv[u] = ld4<NT>(s4 + base + u * kBlock);
+        for (int u = 0; u < kLazyItems; ++u)
+            sv[u] = ld4<NT>(s4 + base + u * 64);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int u = 0; u < kReduceUnroll; ++u) {
+        for (int u = 0; u < kLazyItems; ++u) {
             const vf4 v = gv[u] + pending_error4(sv[u], nmp, mn);
-            st4<NT>(s4 + base + u * kBlock, v);
+            st4<NT>(s4 + base + u * 64, v);
             acc.add4(v);
         }
-        acc.flush();
-    }
-    for (uint64_t i = ntile * kTile + static_cast<uint64_t>(b) * kBlock + tid; i < nvec;
-         i += static_cast<uint64_t>(B) * kBlock) {
-        const vf4 v = ld4<NT>(g4 + i) + pending_error4(ld4<NT>(s4 + i), nmp, mn);
-        st4<NT>(s4 + i, v);
-        acc.add4(v);
-        acc.flush();
+    } else {
+        for (int u = 0; u < kLazyItems; ++u) {
+            const uint64_t i = base + static_cast<uint64_t>(u) * 64;
+            if (i < nvec) {
+                const vf4 v = ld4<NT>(g4 + i) + pending_error4(ld4<NT>(s4 + i), nmp, mn);
+                st4<NT>(s4 + i, v);
+                acc.add4(v);
+            }
+        }
     }
     if (b == 0 && tid < (n & 3)) {
         const uint64_t i = (nvec << 2) + tid;
         const float v = g[i] + pending_error(s[i], nmp, mn);
         s[i] = v;
         acc.add(v);
-        acc.flush();
     }
+    acc.flush();
 
+    const double wp = wave_sum(acc.s_pos), wn = wave_sum(acc.s_neg);
+    if (tid == 0) {
+        const size_t slot = static_cast<size_t>(p) * blocks + b;
+        out.s_pos[slot] = wp;
+        out.s_neg[slot] = wn;
+        out.n_pos[slot] = acc.c_pos;
+        out.n_neg[slot] = acc.c_neg;
+        out.n_zero[slot] = acc.c_zero;
+    }
+}
+
+// Between the one-shot reduction and k_local_finalize: workgroup (j, p) adds the records
+// [j * kFoldSpan, (j + 1) * kFoldSpan) of worker p in a fixed order (strided per thread, shuffle tree, wavefronts
+// in index order) into record j of the folded table.
+__global__ __launch_bounds__(kBlock) void k_fold_partials(const uint32_t rows, const Partials in, const uint32_t folded,
+                                                          Partials out)
+{
+    const uint32_t p = blockIdx.y, j = blockIdx.x, tid = threadIdx.x;
+    const size_t row = static_cast<size_t>(p) * rows;
+    const uint32_t lo = j * kFoldSpan, hi = rows - lo < kFoldSpan ? rows : lo + kFoldSpan;
+    double sp = 0.0, sn = 0.0;
+    uint64_t cp = 0, cn = 0, cz = 0;
+    for (uint32_t k = lo + tid; k < hi; k += kBlock) {
+        sp += in.s_pos[row + k];
+        sn += in.s_neg[row + k];
+        cp += in.n_pos[row + k];
+        cn += in.n_neg[row + k];
+        cz += in.n_zero[row + k];
+    }
     __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
     __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
-    const double wp = wave_sum(acc.s_pos), wn = wave_sum(acc.s_neg);
+    sp = wave_sum(sp);
+    sn = wave_sum(sn);
+    cp = wave_sum(cp);
+    cn = wave_sum(cn);
+    cz = wave_sum(cz);
     const uint32_t lane = tid & 63, wave = tid >> 6;
     if (lane == 0) {
-        sh_pos[wave] = wp;
-        sh_neg[wave] = wn;
-        sh_cp[wave] = acc.c_pos;
-        sh_cn[wave] = acc.c_neg;
-        sh_cz[wave] = acc.c_zero;
+        sh_pos[wave] = sp;
+        sh_neg[wave] = sn;
+        sh_cp[wave] = cp;
+        sh_cn[wave] = cn;
+        sh_cz[wave] = cz;
     }
     __syncthreads();
     if (tid == 0) {
-        double sp = 0.0, sn = 0.0;
-        uint64_t cp = 0, cn = 0, cz = 0;
+        double tp = 0.0, tn = 0.0;
+        uint64_t np = 0, nn = 0, nz = 0;
 #pragma unroll
         for (int k = 0; k < kBlock / 64; ++k) {
-            sp += sh_pos[k];
-            sn += sh_neg[k];
-            cp += sh_cp[k];
-            cn += sh_cn[k];
-            cz += sh_cz[k];
+            tp += sh_pos[k];
+            tn += sh_neg[k];
+            np += sh_cp[k];
+            nn += sh_cn[k];
+            nz += sh_cz[k];
         }
-        const size_t slot = static_cast<size_t>(p) * B + b;
-        out.s_pos[slot] = sp;
-        out.s_neg[slot] = sn;
-        out.n_pos[slot] = cp;
-        out.n_neg[slot] = cn;
-        out.n_zero[slot] = cz;
+        const size_t slot = static_cast<size_t>(p) * folded + j;
+        out.s_pos[slot] = tp;
+        out.s_neg[slot] = tn;
+        out.n_pos[slot] = np;
+        out.n_neg[slot] = nn;
+        out.n_zero[slot] = nz;
     }
 }
 
@@ -1240,15 +1278,26 @@ hipError_t launch_lazy_reset(const a2sgd_plan_t &, void *ws, hipStream_t s)
     return hipGetLastError();
 }
 
+// The lazy state's reduction: one-shot pass, fold of its records, local means.  The dynamic LDS request only limits
+// the workgroups per compute unit (6 of them keep about 96 KiB of loads in flight per CU).
 hipError_t launch_lazy_partials(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s)
 {
-    const dim3 grid(pl.B, pl.P), block(kBlock);
-    const Partials out = partials_of(ws, pl.P, pl.B);
-    const WsHeader *hdr = static_cast<const WsHeader *>(ws);
+    const dim3 grid(pl.lazy_blocks, pl.P), block(64);
+    const Partials rec = partials_at(ws, pl.lazy_offset, pl.P, pl.lazy_blocks);
+    const size_t folded_offset = pl.lazy_offset + 5ull * 8ull * pl.P * pl.lazy_blocks;
+    const Partials folded = partials_at(ws, folded_offset, pl.P, pl.lazy_folded);
+    WsHeader *hdr = static_cast<WsHeader *>(ws);
     if (pl.streaming)
-        k_lazy_partials<true><<<grid, block, 0, s>>>(tab, pl.n, pl.B, hdr, out);
+        k_lazy_partials<true><<<grid, block, 25 * 1024, s>>>(tab, pl.n, pl.lazy_blocks, hdr, rec);
     else
-        k_lazy_partials<false><<<grid, block, 0, s>>>(tab, pl.n, pl.B, hdr, out);
+        k_lazy_partials<false><<<grid, block, 0, s>>>(tab, pl.n, pl.lazy_blocks, hdr, rec);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess)
+        return err;
+    k_fold_partials<<<dim3(pl.lazy_folded, pl.P), dim3(kBlock), 0, s>>>(pl.lazy_blocks, rec, pl.lazy_folded, folded);
+    if ((err = hipGetLastError()) != hipSuccess)
+        return err;
+    k_local_finalize<<<dim3(pl.P), dim3(kBlock), 0, s>>>(pl.n, pl.lazy_folded, folded, hdr);
     return hipGetLastError();
 }
 

@@ -69,7 +69,10 @@ def test_plan_null_pointers(A):
 def test_plan_geometry(A):
     p = A.a2sgd_plan(1_500_000_000, 4)
     assert A.a2sgd_plan_blocks_per_worker(p) == 128  # 256 CUs x 2 resident workgroups / 4 workers
-    assert A.a2sgd_workspace_bytes(p) == 4096 + 5 * 8 * 4 * 128
+    # header, the 128 records per worker of the reduction pass, then (256-byte aligned) one record per 2048
+    # elements and worker for the lazy state's reduction pass and one per 4096 of those
+    blocks = -(-(1_500_000_000 // 4) // 512)
+    assert A.a2sgd_workspace_bytes(p) == 4096 + 5 * 8 * 4 * 128 + 5 * 8 * 4 * (blocks + -(-blocks // 4096))
     p = A.a2sgd_plan(5, 3)
     assert A.a2sgd_plan_blocks_per_worker(p) == 1
     p = A.a2sgd_plan(1000, 2, blocks_per_worker=7)
@@ -83,7 +86,8 @@ def test_segmented_plan_validation_and_workspace(A):
         assert ei.value.status == A.A2SGD_ERR_INVALID_ARG
     whole = A.a2sgd_plan(1_000_000, 4)
     seg = A.a2sgd_plan(1_000_000, 4, 0, 0, seg_lengths=[1, 70_000, 3, 929_996])
-    assert A.a2sgd_workspace_bytes(seg) > A.a2sgd_workspace_bytes(whole)
+    # the tables of the per-tensor plan come after the header and the whole-model partial records
+    assert A.a2sgd_workspace_bytes(seg) > 4096 + 5 * 8 * 4 * A.a2sgd_plan_blocks_per_worker(whole)
     one = A.a2sgd_plan(1_000_000, 4, 0, 0, seg_lengths=[1_000_000])  # a single segment is the whole-model method
     assert A.a2sgd_workspace_bytes(one) == A.a2sgd_workspace_bytes(whole) and one.num_segments == 0
     R = A.raw

@@ -57,8 +57,10 @@ def oracle_pass_a(g, e, n, P, chunk):
     return [a.stats() for a in accs]
 
 
-@pytest.mark.parametrize("k", [2, 3, 4, 5])
-def test_full_size_config(A, k):
+@pytest.mark.parametrize("k,lazy", [(2, False), (3, False), (4, False), (5, False), (4, True), (5, True)])
+def test_full_size_config(A, k, lazy):
+    """lazy = the same step through a2sgd_lazy_step (the buffers then hold v) followed by a2sgd_lazy_materialize,
+    after which they hold the same new errors as the eager step leaves."""
     t0 = time.time()
     wl = workloads.FULL[k]()
     n, P = wl.n, wl.num_workers
@@ -80,7 +82,12 @@ def test_full_size_config(A, k):
 
     plan = A.a2sgd_plan(n, P, 0)
     ws = A.alloc_workspace(plan)
-    A.a2sgd_step(plan, g, e, w, wl.eta, ws)
+    if lazy:
+        A.a2sgd_lazy_reset(plan, ws)
+        A.a2sgd_lazy_step(plan, g, e, w, wl.eta, ws)
+        A.a2sgd_lazy_materialize(plan, e, ws)
+    else:
+        A.a2sgd_step(plan, g, e, w, wl.eta, ws)
     stats, gmu = A.a2sgd_read_stats(plan, ws)
     ref = O.StepResult(stats_ref, gp, gn, [], np.empty(0, f32), [])
     compare_stats(stats, gmu, ref)

@@ -348,10 +348,12 @@ def test_replicas_full_size_config2(A):
 
 
 @pytest.mark.parametrize("n,P,mode", [(1, 1, 0), (7, 2, 0), (4099, 3, 1), (65_539, 4, 0), (300_001, 8, 1), (50_001, 17, 0),
-                                      (2_000_003, 4, 0)])
+                                      (2_000_003, 4, 0), (2047, 2, 0), (3 * 2048, 2, 1), (12_000_017, 2, 0)])
 def test_lazy_error_state(A, n, P, mode):
     """Five steps on the lazy state (buffers hold v, the error is formed on the next read) against five eager
-    steps of the oracle and of the GPU: same w and statistics at every step, same errors once materialised."""
+    steps of the oracle and of the GPU: same w and statistics at every step, same errors once materialised.  The
+    sizes include less than one workgroup of the reduction pass (2048 elements), a whole number of them, and one
+    whose records need more than one workgroup of the fold pass (and whose footprint takes the streaming path)."""
     wl = workloads.config1(n=n, num_workers=P)
     rng = np.random.default_rng(n)
     e0 = [(rng.standard_normal(n) * 4e-4).astype(f32) for _ in range(P)]  # start from a nonzero true error
