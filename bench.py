@@ -42,6 +42,8 @@ def main() -> int:
     ap.add_argument("--single-call", action="store_true",
                     help="time a2sgd_step (one call per step; a single cooperative launch when the model fits the "
                          "caches) instead of the three calls with events between them")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="capture one step in a HIP graph and time its replays (no events inside the step)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain copy of n floats (for scaling rocprofv3 HBM counters)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28, help="parameters in the CPU-baseline sample")
@@ -100,18 +102,31 @@ def main() -> int:
         step()
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step(events[k])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    if args.hip_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    else:
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            step(events[k])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    ms_median = None if args.single_call else sorted(ev[0].elapsed_time(ev[3]) for ev in events)[args.steps // 2]
+    no_events = args.single_call or args.hip_graph  # then the roofline entry is the whole step
+    ms_median = None if no_events else sorted(ev[0].elapsed_time(ev[3]) for ev in events)[args.steps // 2]
     bytes_reduce = 8 * n * P
     bytes_apply = 12 * n * P + 8 * n
     bytes_step = bytes_reduce + bytes_apply
-    if args.single_call:  # no events inside the step: the roofline entry is the whole step
+    if no_events:
         ms_reduce = ms_global = None
         ms_apply = ms_per_step
         bytes_apply = bytes_step
@@ -141,18 +156,19 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"config{args.config}:{wl.name}", "n": n, "num_workers": P, "seed": wl.seed,
                    "recipe": wl.recipe, "mode": "retained_error", "eta": wl.eta, "per_tensor_means": plan.num_segments,
-                   "blocks_per_worker": A.a2sgd_plan_blocks_per_worker(plan)},
+                   "blocks_per_worker": A.a2sgd_plan_blocks_per_worker(plan),
+                   "launch": ("one_call" if args.single_call else "three_calls") + ("+hip_graph_replay" if args.hip_graph else "")},
         "ms_per_step_median_events": ms_median,
         "worker_params_per_s": n * P / (ms_per_step * 1e-3),
         "step_hbm_gbps": bytes_step / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "kernels_ms": {"local_averages": ms_reduce, "global_average": ms_global, "apply_and_update_error": ms_apply},
         "local_averages_gbps": None if ms_reduce is None else bytes_reduce / (ms_reduce * 1e-3) / 1e9,
-        "roofline": {"kernel": "a2sgd_step (one call)" if args.single_call else "k_apply (a2sgd_apply_and_update_error)",
+        "roofline": {"kernel": "whole step" if no_events else "k_apply (a2sgd_apply_and_update_error)",
                      "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "algorithmic_bytes_per_launch": bytes_apply,
-                     "traffic": None if args.single_call else MEASURED_TRAFFIC_BYTES.get(f"config{args.config}")},
+                     "traffic": None if no_events else MEASURED_TRAFFIC_BYTES.get(f"config{args.config}")},
         "result_check": {"gmu_pos": gmu[0], "gmu_neg": gmu[1], "n_pos_worker0": stats[0].n_pos},
     }
 

@@ -396,6 +396,56 @@ def test_lazy_error_state(A, n, P, mode):
     assert float((w_l - w_g).abs().max()) <= 1e-9
 
 
+@pytest.mark.parametrize("n,P,calls", [(1_048_576, 4, "step"), (1_048_576, 4, "three"), (14_000_003, 4, "three"),
+                                       (300_001, 3, "lazy")])
+def test_step_captured_in_a_hip_graph(A, n, P, calls):
+    """The step calls only enqueue kernels (no allocation, no copy, no host wait), so a stream capture records them.
+    Three replays, with the program's own eager work and synchronisations between them, must leave exactly what
+    three eager steps leave (the eager steps are the ones the other tests check against the oracle)."""
+    wl = workloads.config1(n=n, num_workers=P)
+    g = [wl.gradient(p, 0, device="cuda") for p in range(P)]
+    e0 = [wl.synthetic_error(p, device="cuda") for p in range(P)]
+    w0 = wl.weights(device="cuda")
+    plan = A.a2sgd_plan(n, P, 0)
+
+    def one_step(e, w, ws):
+        if calls == "step":  # one launch at this size
+            A.a2sgd_step(plan, g, e, w, wl.eta, ws)
+        elif calls == "lazy":
+            A.a2sgd_lazy_step(plan, g, e, w, wl.eta, ws)
+        else:
+            A.a2sgd_local_averages(plan, g, e, ws)
+            A.a2sgd_global_average(plan, ws)
+            A.a2sgd_apply_and_update_error(plan, g, e, w, wl.eta, ws)
+
+    ws_ref = A.alloc_workspace(plan)
+    e_ref, w_ref = [x.clone() for x in e0], w0.clone()
+    if calls == "lazy":
+        A.a2sgd_lazy_reset(plan, ws_ref)
+    expected = []
+    for _ in range(3):
+        one_step(e_ref, w_ref, ws_ref)
+        expected.append(([x.clone() for x in e_ref], w_ref.clone()))
+    torch.cuda.synchronize()
+
+    ws = A.alloc_workspace(plan)
+    e, w = [x.clone() for x in e0], w0.clone()
+    if calls == "lazy":
+        A.a2sgd_lazy_reset(plan, ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        one_step(e, w, ws)
+    for k in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        busy = (w0 * 2.0).sum().item()  # unrelated eager work and a host wait between replays
+        assert np.isfinite(busy)
+        for p in range(P):
+            assert torch.equal(e[p], expected[k][0][p]), f"replay {k}: buffer of worker {p} differs from eager"
+        assert torch.equal(w, expected[k][1]), f"replay {k}: w differs from eager"
+
+
 def test_grid_barrier_gives_up_instead_of_hanging(A):
     """The bounded wait of the single-launch step's barrier, forced from the host on a spare cell: all workgroups
     pass a complete barrier; all give up, and exit, when one arrival is missing.  Steps still work afterwards."""
