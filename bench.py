@@ -209,8 +209,9 @@ def main() -> int:
         print(json.dumps(out))
         return 0
 
-    # Also outside the timed region: the same step on the lazy error state (16nP + 8n bytes: the buffers keep v and
-    # the error is formed on the next read).  Same results bit for bit; a different contract for what e holds.
+    # Also outside the timed region: the same step on the lazy error state: the buffers keep v, the error is formed
+    # on the next read, and in this mode the apply pass reads one sign bit per element-worker that the reduction
+    # pass left (12nP + 8n bytes plus nP/8 written and read).  A different contract for what e holds.
     A.a2sgd_lazy_reset(plan, ws)
     for _ in range(2):
         A.a2sgd_lazy_step(plan, g, e, w, wl.eta, ws)
@@ -221,7 +222,7 @@ def main() -> int:
     torch.cuda.synchronize()
     ms_lazy = ev0.elapsed_time(ev1) / 5
     A.a2sgd_lazy_materialize(plan, e, ws)
-    out["lazy_step"] = {"ms": ms_lazy, "gbps": (16 * n * P + 8 * n) / (ms_lazy * 1e-3) / 1e9,
+    out["lazy_step"] = {"ms": ms_lazy, "gbps": (12.25 * n * P + 8 * n) / (ms_lazy * 1e-3) / 1e9,
                         "params_per_s": n / (ms_lazy * 1e-3)}
 
     if not args.no_cpu_baseline:

@@ -186,15 +186,20 @@ a2sgd_status_t a2sgd_dense_step_replicas(const a2sgd_plan_t *plan, const float *
 a2sgd_status_t a2sgd_replica_drift(const a2sgd_plan_t *plan, const float *const *w, void *workspace,
                                    a2sgd_stream_t stream, double *out_max_abs, double *out_rms);
 
-/* ---- Lazy error state: the same step with 16nP + 8n bytes of traffic instead of 20nP + 8n ------------------
+/* ---- Lazy error state: the same step with less traffic than a2sgd_step's 20nP + 8n bytes -------------------
  * Between lazy steps worker p's buffer s^p holds the folded vector v^p of the last step instead of the error,
  * and the workspace carries that step's local means; the error is e^p_i = fl32(s^p_i - enc(s^p)_i) with those
  * means (Eq. 2), and it is formed on the fly when the next step reads the buffer.  The reduction pass then reads
- * g and s and writes the new v into s (12 bytes per element and worker); the apply pass only reads s for the
- * sign groups and updates w (4 bytes per element and worker plus 8 per parameter); nothing else differs: w, the
- * means and the counts are bit-identical to a2sgd_step's, and so are the errors once materialised.
+ * g and s and writes the new v into s (12 bytes per element and worker).  What the apply pass reads depends on
+ * the plan's mode.  A2SGD_MODE_ALG1_LITERAL: s again, for the errors that enter the update (4 bytes per element
+ * and worker plus 8 per parameter: 16nP + 8n in all).  A2SGD_MODE_RETAINED_ERROR: the update of a parameter
+ * depends only on how many workers have it in the positive group, so the reduction pass also leaves pos(v) as one
+ * bit per element and worker in the workspace and the apply pass reads those (12.25nP + 8n in all; if any worker
+ * counted a NaN, which has no sign, it reads s instead).  The counts are the same as a2sgd_step's; the means may
+ * differ from its in the last bit (the sums are grouped differently) and w by an ulp; the errors once
+ * materialised are those of a2sgd_step within that.
  * A workspace in lazy use carries state: between a2sgd_lazy_reset and a2sgd_lazy_materialize it must see no other
- * calls than a2sgd_lazy_step and a2sgd_read_stats.  Both plan modes are supported; s is required. */
+ * calls than a2sgd_lazy_step and a2sgd_read_stats.  s is required. */
 
 /* Declares that the buffers that will be passed as s hold true errors (for a fresh run: zeros): clears the local
  * means carried in the workspace.  Call once before the first a2sgd_lazy_step on a workspace. */

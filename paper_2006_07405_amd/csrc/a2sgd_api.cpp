@@ -212,14 +212,16 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
     const size_t drift = 2ull * 8ull * pl->P * (kDriftBlocks + 1);  // the drift diagnostic reuses the same region
     pl->workspace_bytes = kHeaderBytes + (partials > drift ? partials : drift);
     pl->lazy_blocks = pl->lazy_folded = 0;
-    pl->lazy_offset = 0;
+    pl->lazy_offset = pl->lazy_sign_offset = 0;
     if (cfg->num_segments <= 1) {
         // one record per workgroup of the lazy state's one-shot reduction pass, and their folded table
         const uint64_t per = 64ull * kLazyItems, nvec = pl->n >> 2;
         pl->lazy_blocks = static_cast<uint32_t>(nvec ? (nvec + per - 1) / per : 1);
         pl->lazy_folded = (pl->lazy_blocks + kFoldSpan - 1) / kFoldSpan;
         pl->lazy_offset = (pl->workspace_bytes + 255) & ~static_cast<size_t>(255);
-        pl->workspace_bytes = pl->lazy_offset + 5ull * 8ull * pl->P * (static_cast<size_t>(pl->lazy_blocks) + pl->lazy_folded);
+        pl->lazy_sign_offset = pl->lazy_offset + 5ull * 8ull * pl->P * (static_cast<size_t>(pl->lazy_blocks) + pl->lazy_folded);
+        pl->lazy_sign_offset = (pl->lazy_sign_offset + 255) & ~static_cast<size_t>(255);
+        pl->workspace_bytes = pl->lazy_sign_offset + 4ull * pl->P * (64ull * pl->lazy_blocks);
     }
     if (cfg->num_segments > 1) {
         try {

@@ -27,11 +27,12 @@ constexpr uint32_t kFoldSpan = 4096;    // records that one workgroup of k_fold_
 //   double   s_neg [P][B]   block partial sums of |v| over v < 0
 //   uint64_t n_pos [P][B], n_neg [P][B], n_zero [P][B]
 //   whole-model plans only, at plan.lazy_offset: the same five arrays as [P][lazy_blocks] (one record per
-//   workgroup of the lazy state's reduction pass), then as [P][lazy_folded]
+//   workgroup of the lazy state's reduction pass), then as [P][lazy_folded]; at plan.lazy_sign_offset:
+//   uint32_t sign [P][lazy_blocks * 64], one bit per element: pos(v) of Eq. 2
 struct WsHeader {
     float gmu_pos, gmu_neg;  // Algorithm 1 line 5
     uint32_t failed_token;   // set to the launch's token by a single-launch step that could not complete
-    uint32_t pad;
+    uint32_t any_nan;        // nonzero if any worker counted a NaN in the last reduction (set with the global means)
     a2sgd_worker_stats_t workers[kMaxWorkers];  // Algorithm 1 line 3, per worker
     float neg_mu_pos[kMaxWorkers];  // -mu_pos and mu_neg of every worker again, packed for the apply pass
     float mu_neg[kMaxWorkers];
@@ -138,6 +139,7 @@ struct a2sgd_plan {
     uint32_t lazy_blocks;  // workgroups per worker of the lazy state's reduction pass (one record each)
     uint32_t lazy_folded;  // records per worker after k_fold_partials
     size_t lazy_offset;    // byte offset of those records in the workspace; 0 = the plan has no lazy state
+    size_t lazy_sign_offset;  // byte offset of the sign words
     size_t workspace_bytes;
 };
 

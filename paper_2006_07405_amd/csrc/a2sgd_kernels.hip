@@ -159,6 +159,10 @@ __global__ void k_global_average(const uint32_t P, WsHeader *__restrict__ hdr)
         }
         hdr->gmu_pos = static_cast<float>(sp / static_cast<double>(P));
         hdr->gmu_neg = static_cast<float>(sn / static_cast<double>(P));
+        uint32_t any_nan = 0;
+        for (uint32_t p = 0; p < P; ++p)
+            any_nan |= hdr->workers[p].n_nan != 0 ? 1u : 0u;
+        hdr->any_nan = any_nan;
     }
     // the same local means again, packed and pre-negated the way the apply pass consumes them
     for (uint32_t p = threadIdx.x; p < P && blockIdx.x == 0; p += blockDim.x) {
@@ -853,10 +857,25 @@ __device__ __forceinline__ vf4 pending_error4(vf4 s, float neg_mu_pos, float mu_
 // groups per thread, all loads issued before the first store (a loop would wait for its own older stores before
 // it could use newer loads, since both are counted together).  Every workgroup writes one record; the records
 // of a worker are combined in index order by k_fold_partials and k_local_finalize.
-template <bool NT>
-__global__ __launch_bounds__(64) void k_lazy_partials(const PtrTable tab, const uint64_t n, const uint32_t blocks,
-                                                      const WsHeader *__restrict__ hdr, Partials out)
+// Shifts pos(v) of the four components into the low end of `bits`, x first.
+__device__ __forceinline__ uint32_t push_signs(uint32_t bits, vf4 v)
 {
+    bits = bits * 2u + (v.x >= 0.0f ? 1u : 0u);
+    bits = bits * 2u + (v.y >= 0.0f ? 1u : 0u);
+    bits = bits * 2u + (v.z >= 0.0f ? 1u : 0u);
+    bits = bits * 2u + (v.w >= 0.0f ? 1u : 0u);
+    return bits;
+}
+
+// With SIGNS the pass also leaves pos(v) of Eq. 2 as one bit per element for the apply pass: thread `tid` of
+// workgroup b writes one 32-bit word, sign[p][64 * b + tid], whose bit 31 - (4 * u + c) belongs to component c of
+// its float4 group u (0 where the group lies past the end).
+template <bool NT, bool SIGNS>
+__global__ __launch_bounds__(64) void k_lazy_partials(const PtrTable tab, const uint64_t n, const uint32_t blocks,
+                                                      const WsHeader *__restrict__ hdr, Partials out,
+                                                      uint32_t *__restrict__ sign)
+{
+    static_assert(4 * kLazyItems == 32, "one thread's sign bits fill one 32-bit word");
     const uint32_t p = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
     const uint32_t lz = opaque_zero();
     // the means of the step that stored the values
@@ -870,6 +889,7 @@ __global__ __launch_bounds__(64) void k_lazy_partials(const PtrTable tab, const 
     const uint64_t base = static_cast<uint64_t>(b) * kPer + tid;
 
     LaneAcc acc;
+    uint32_t bits = 0;
     if ((static_cast<uint64_t>(b) + 1) * kPer <= nvec) {
         vf4 gv[kLazyItems], sv[kLazyItems];
 #pragma unroll
@@ -884,17 +904,26 @@ __global__ __launch_bounds__(64) void k_lazy_partials(const PtrTable tab, const 
             const vf4 v = gv[u] + pending_error4(sv[u], nmp, mn);
             st4<NT>(s4 + base + u * 64, v);
             acc.add4(v);
+            if (SIGNS)
+                bits = push_signs(bits, v);
         }
     } else {
+#pragma unroll
         for (int u = 0; u < kLazyItems; ++u) {
             const uint64_t i = base + static_cast<uint64_t>(u) * 64;
             if (i < nvec) {
                 const vf4 v = ld4<NT>(g4 + i) + pending_error4(ld4<NT>(s4 + i), nmp, mn);
                 st4<NT>(s4 + i, v);
                 acc.add4(v);
+                if (SIGNS)
+                    bits = push_signs(bits, v);
+            } else {
+                bits <<= 4;
             }
         }
     }
+    if (SIGNS)
+        sign[(static_cast<size_t>(p) * blocks + b) * 64 + tid] = bits;
     if (b == 0 && tid < (n & 3)) {
         const uint64_t i = (nvec << 2) + tid;
         const float v = g[i] + pending_error(s[i], nmp, mn);
@@ -1018,6 +1047,103 @@ __global__ __launch_bounds__(BLOCK) void k_lazy_apply(const PtrTable tab, float 
             a += apply1<MODE>(v, neg_mu_pos[p], mu_neg[p], gmu_pos, neg_gmu_neg);
         }
         w[k] -= eta_over_P * a;
+    }
+}
+
+constexpr int kLazySignItems = 4;          // float4 groups of w per thread of the sign-reading apply pass
+constexpr uint32_t kLazySignLds = 8 * 1024;  // its dynamic-LDS request when streaming (20 workgroups per CU)
+
+// Apply pass on the lazy state in retained-error mode, from the sign words: there the update of an element is
+// (k * gmu_pos - (P - k) * gmu_neg) / P with k = the number of workers whose v is >= 0 (Algorithm 1 line 6 summed
+// over the workers as in Eq. 1), so the pass reads one bit per element-worker instead of v.  A workgroup is one
+// wavefront; it covers ITEMS of the kLazyItems float4 groups that each thread of one workgroup of the reduction
+// pass owned, so a thread finds its bits in that thread's word of every worker.  A NaN has no sign: if the
+// reduction counted any, the pass reads v as k_lazy_apply does (a branch that is uniform over the grid).
+template <bool NT, int ITEMS, int UP>
+__global__ __launch_bounds__(64) void k_lazy_apply_signs(const PtrTable tab, const uint32_t *__restrict__ sign,
+                                                         const uint64_t row_words, float *__restrict__ w,
+                                                         const uint64_t n, const uint32_t P, const float eta_over_P,
+                                                         const WsHeader *__restrict__ hdr)
+{
+    static_assert(kLazyItems % ITEMS == 0, "a workgroup stays inside one workgroup of the reduction pass");
+    constexpr uint32_t kParts = kLazyItems / ITEMS;
+    const uint32_t lane = threadIdx.x;
+    const uint32_t lz = opaque_zero();
+    const float gmu_pos = (&hdr->gmu_pos)[lz], gmu_neg = (&hdr->gmu_neg)[lz];
+    const uint32_t any_nan = (&hdr->any_nan)[lz];
+    const uint64_t nvec = n >> 2;
+    const uint64_t b = blockIdx.x / kParts;            // workgroup of the reduction pass
+    const uint32_t u0 = (blockIdx.x % kParts) * ITEMS;  // first of its float4 groups handled here
+    const uint64_t first = b * (64ull * kLazyItems) + u0 * 64ull + lane;
+    vf4 *w4 = reinterpret_cast<vf4 *>(w);
+    vf4 wv[ITEMS];
+#pragma unroll
+    for (int t = 0; t < ITEMS; ++t)
+        if (first + t * 64 < nvec)
+            wv[t] = ld4<NT>(w4 + first + t * 64);
+    vf4 acc[ITEMS];
+    if (any_nan == 0) {
+        const uint32_t *word = sign + b * 64 + lane;
+        uint32_t k[ITEMS][4];
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t)
+            k[t][0] = k[t][1] = k[t][2] = k[t][3] = 0;
+        uint32_t p0 = 0;
+        for (; p0 + UP <= P; p0 += UP) {
+            uint32_t d[UP];
+#pragma unroll
+            for (int q = 0; q < UP; ++q)
+                d[q] = word[(p0 + q) * row_words];
+#pragma unroll
+            for (int q = 0; q < UP; ++q)
+#pragma unroll
+                for (int t = 0; t < ITEMS; ++t)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        k[t][c] += (d[q] >> (31u - (4u * (u0 + t) + c))) & 1u;
+        }
+        for (; p0 < P; ++p0) {
+            const uint32_t d = word[p0 * row_words];
+#pragma unroll
+            for (int t = 0; t < ITEMS; ++t)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    k[t][c] += (d >> (31u - (4u * (u0 + t) + c))) & 1u;
+        }
+        const float gsum = gmu_pos + gmu_neg, base = static_cast<float>(P) * gmu_neg;
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t)
+            acc[t] = vf4{static_cast<float>(k[t][0]) * gsum - base, static_cast<float>(k[t][1]) * gsum - base,
+                         static_cast<float>(k[t][2]) * gsum - base, static_cast<float>(k[t][3]) * gsum - base};
+    } else {
+        const float neg_gmu_neg = -gmu_neg;
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t)
+            acc[t] = vf4{0.0f, 0.0f, 0.0f, 0.0f};
+        for (uint32_t p = 0; p < P; ++p) {
+            const vf4 *v4 = reinterpret_cast<const vf4 *>(tab.e[p]);
+            const float nmp = hdr->neg_mu_pos[p], mn = hdr->mu_neg[p];
+#pragma unroll
+            for (int t = 0; t < ITEMS; ++t)
+                if (first + t * 64 < nvec)
+                    (void)apply4<A2SGD_MODE_RETAINED_ERROR>(ld4<NT>(v4 + first + t * 64), acc[t], nmp, mn, gmu_pos,
+                                                            neg_gmu_neg);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < ITEMS; ++t)
+        if (first + t * 64 < nvec) {
+            const vf4 wn = wv[t] - eta_over_P * acc[t];
+            st4<NT>(w4 + first + t * 64, wn);
+        }
+    if (blockIdx.x == gridDim.x - 1 && lane < (n & 3)) {  // the scalar tail reads v itself
+        const uint64_t i = (nvec << 2) + lane;
+        float a = 0.0f;
+        for (uint32_t p = 0; p < P; ++p) {
+            float v = tab.e[p][i];
+            a += apply1<A2SGD_MODE_RETAINED_ERROR>(v, hdr->neg_mu_pos[p], hdr->mu_neg[p], gmu_pos, -gmu_neg);
+        }
+        w[i] -= eta_over_P * a;
     }
 }
 
@@ -1287,10 +1413,19 @@ hipError_t launch_lazy_partials(const a2sgd_plan_t &pl, const PtrTable &tab, voi
     const size_t folded_offset = pl.lazy_offset + 5ull * 8ull * pl.P * pl.lazy_blocks;
     const Partials folded = partials_at(ws, folded_offset, pl.P, pl.lazy_folded);
     WsHeader *hdr = static_cast<WsHeader *>(ws);
-    if (pl.streaming)
-        k_lazy_partials<true><<<grid, block, 25 * 1024, s>>>(tab, pl.n, pl.lazy_blocks, hdr, rec);
-    else
-        k_lazy_partials<false><<<grid, block, 0, s>>>(tab, pl.n, pl.lazy_blocks, hdr, rec);
+    uint32_t *sign = reinterpret_cast<uint32_t *>(static_cast<char *>(ws) + pl.lazy_sign_offset);
+    const bool signs = pl.mode == A2SGD_MODE_RETAINED_ERROR;  // the literal mode's apply pass needs v itself
+    if (pl.streaming) {
+        if (signs)
+            k_lazy_partials<true, true><<<grid, block, 25 * 1024, s>>>(tab, pl.n, pl.lazy_blocks, hdr, rec, sign);
+        else
+            k_lazy_partials<true, false><<<grid, block, 25 * 1024, s>>>(tab, pl.n, pl.lazy_blocks, hdr, rec, sign);
+    } else {
+        if (signs)
+            k_lazy_partials<false, true><<<grid, block, 0, s>>>(tab, pl.n, pl.lazy_blocks, hdr, rec, sign);
+        else
+            k_lazy_partials<false, false><<<grid, block, 0, s>>>(tab, pl.n, pl.lazy_blocks, hdr, rec, sign);
+    }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess)
         return err;
@@ -1327,8 +1462,27 @@ hipError_t launch_lazy_apply(const a2sgd_plan_t &pl, const PtrTable &tab, float 
     if (pl.mode == A2SGD_MODE_ALG1_LITERAL)
         return pl.streaming ? launch_lazy_apply_shape<A2SGD_MODE_ALG1_LITERAL, true>(pl, tab, w, eop, hdr, s)
                             : launch_lazy_apply_shape<A2SGD_MODE_ALG1_LITERAL, false>(pl, tab, w, eop, hdr, s);
-    return pl.streaming ? launch_lazy_apply_shape<A2SGD_MODE_RETAINED_ERROR, true>(pl, tab, w, eop, hdr, s)
-                        : launch_lazy_apply_shape<A2SGD_MODE_RETAINED_ERROR, false>(pl, tab, w, eop, hdr, s);
+    // retained-error mode: from the sign words that the reduction pass left, one workgroup per kLazySignItems of
+    // the float4 groups of each of its workgroups
+    const uint32_t *sign = reinterpret_cast<const uint32_t *>(static_cast<const char *>(ws) + pl.lazy_sign_offset);
+    const uint64_t row_words = 64ull * pl.lazy_blocks;
+    const dim3 grid(pl.lazy_blocks * (kLazyItems / kLazySignItems)), block(64);
+    if (pl.streaming) {
+        if (pl.P >= 4)
+            k_lazy_apply_signs<true, kLazySignItems, 4><<<grid, block, kLazySignLds, s>>>(tab, sign, row_words, w, pl.n,
+                                                                                         pl.P, eop, hdr);
+        else
+            k_lazy_apply_signs<true, kLazySignItems, 1><<<grid, block, kLazySignLds, s>>>(tab, sign, row_words, w, pl.n,
+                                                                                         pl.P, eop, hdr);
+    } else {
+        if (pl.P >= 4)
+            k_lazy_apply_signs<false, kLazySignItems, 4><<<grid, block, 0, s>>>(tab, sign, row_words, w, pl.n, pl.P,
+                                                                               eop, hdr);
+        else
+            k_lazy_apply_signs<false, kLazySignItems, 1><<<grid, block, 0, s>>>(tab, sign, row_words, w, pl.n, pl.P,
+                                                                               eop, hdr);
+    }
+    return hipGetLastError();
 }
 
 hipError_t launch_lazy_materialize(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s)

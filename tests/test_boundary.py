@@ -70,9 +70,11 @@ def test_plan_geometry(A):
     p = A.a2sgd_plan(1_500_000_000, 4)
     assert A.a2sgd_plan_blocks_per_worker(p) == 128  # 256 CUs x 2 resident workgroups / 4 workers
     # header, the 128 records per worker of the reduction pass, then (256-byte aligned) one record per 2048
-    # elements and worker for the lazy state's reduction pass and one per 4096 of those
+    # elements and worker for the lazy state's reduction pass and one per 4096 of those, then (aligned again) one
+    # sign bit per element and worker, rounded up to whole 2048-element blocks
     blocks = -(-(1_500_000_000 // 4) // 512)
-    assert A.a2sgd_workspace_bytes(p) == 4096 + 5 * 8 * 4 * 128 + 5 * 8 * 4 * (blocks + -(-blocks // 4096))
+    records = 4096 + 5 * 8 * 4 * 128 + 5 * 8 * 4 * (blocks + -(-blocks // 4096))
+    assert A.a2sgd_workspace_bytes(p) == -(-records // 256) * 256 + 4 * blocks * 2048 // 8
     p = A.a2sgd_plan(5, 3)
     assert A.a2sgd_plan_blocks_per_worker(p) == 1
     p = A.a2sgd_plan(1000, 2, blocks_per_worker=7)

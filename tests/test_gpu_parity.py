@@ -366,6 +366,7 @@ def test_lazy_error_state(A, n, P, mode):
     w_g = dev(w0)
     e_o, w_o = [x.copy() for x in e0], w0.copy()
     A.a2sgd_lazy_reset(plan, ws_l)
+    ulp_w = float(np.spacing(f32(np.abs(w0).max() + 1e-3)))
     for t in range(5):
         g = [wl.gradient(p, t).numpy() for p in range(P)]
         gd = [dev(x) for x in g]
@@ -375,13 +376,14 @@ def test_lazy_error_state(A, n, P, mode):
         compare_stats(st, gmu, ref)
         assert_array_close(w_l.cpu().numpy(), ref.w_new, f"step {t} w (lazy)")
         # the eager GPU path from the same state: same counts; the sums are grouped differently, so the means may
-        # differ in the last bit once in a long while, the weights by that much
+        # differ in the last bit once in a long while, and in retained-error mode the lazy update is formed from
+        # the number of workers in the positive group instead of worker by worker: the weights agree to an ulp
         A.a2sgd_local_averages(plan, gd, e_g, ws_e)
         A.a2sgd_global_average(plan, ws_e)
         A.a2sgd_apply_and_update_error(plan, gd, e_g, w_g, wl.eta, ws_e)
         st_e, _ = A.a2sgd_read_stats(plan, ws_e)
         assert [(a.n_pos, a.n_neg, a.n_zero) for a in st] == [(a.n_pos, a.n_neg, a.n_zero) for a in st_e]
-        assert float((w_l - w_g).abs().max()) <= 1e-9, f"step {t}: lazy and eager weights differ"
+        assert float((w_l - w_g).abs().max()) <= ulp_w, f"step {t}: lazy and eager weights differ"
         e_o, w_o = ref.e_new, ref.w_new
     A.a2sgd_lazy_materialize(plan, s, ws_l)
     for p in range(P):
