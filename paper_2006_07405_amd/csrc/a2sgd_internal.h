@@ -28,7 +28,7 @@ constexpr uint32_t kFoldSpan = 4096;    // records that one workgroup of k_fold_
 //   uint64_t n_pos [P][B], n_neg [P][B], n_zero [P][B]
 //   whole-model plans only, at plan.lazy_offset: the same five arrays as [P][lazy_blocks] (one record per
 //   workgroup of the lazy state's reduction pass), then as [P][lazy_folded]; at plan.lazy_sign_offset:
-//   uint32_t sign [P][lazy_blocks * 64], one bit per element: pos(v) of Eq. 2
+//   uint16_t sign [P][lazy_blocks][2][64], one bit per element: pos(v) of Eq. 2
 struct WsHeader {
     float gmu_pos, gmu_neg;  // Algorithm 1 line 5
     uint32_t failed_token;   // set to the launch's token by a single-launch step that could not complete

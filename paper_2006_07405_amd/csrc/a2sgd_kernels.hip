@@ -868,14 +868,15 @@ __device__ __forceinline__ uint32_t push_signs(uint32_t bits, vf4 v)
 }
 
 // With SIGNS the pass also leaves pos(v) of Eq. 2 as one bit per element for the apply pass: thread `tid` of
-// workgroup b writes one 32-bit word, sign[p][64 * b + tid], whose bit 31 - (4 * u + c) belongs to component c of
-// its float4 group u (0 where the group lies past the end).
+// workgroup b collects 32 bits, bit 31 - (4 * u + c) for component c of its float4 group u (0 where the group lies
+// past the end), and writes them as two 16-bit halves, sign[p][b][h][tid] (h = 0: groups 0-3), so that a
+// workgroup of the apply pass, which covers half of the groups, reads 128 contiguous bytes per worker.
 template <bool NT, bool SIGNS>
 __global__ __launch_bounds__(64) void k_lazy_partials(const PtrTable tab, const uint64_t n, const uint32_t blocks,
                                                       const WsHeader *__restrict__ hdr, Partials out,
-                                                      uint32_t *__restrict__ sign)
+                                                      uint16_t *__restrict__ sign)
 {
-    static_assert(4 * kLazyItems == 32, "one thread's sign bits fill one 32-bit word");
+    static_assert(4 * kLazyItems == 32, "one thread's sign bits fill two 16-bit halves");
     const uint32_t p = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
     const uint32_t lz = opaque_zero();
     // the means of the step that stored the values
@@ -922,8 +923,11 @@ __global__ __launch_bounds__(64) void k_lazy_partials(const PtrTable tab, const 
             }
         }
     }
-    if (SIGNS)
-        sign[(static_cast<size_t>(p) * blocks + b) * 64 + tid] = bits;
+    if (SIGNS) {
+        uint16_t *row = sign + (static_cast<size_t>(p) * blocks + b) * 128 + tid;
+        row[0] = static_cast<uint16_t>(bits >> 16);
+        row[64] = static_cast<uint16_t>(bits & 0xffffu);
+    }
     if (b == 0 && tid < (n & 3)) {
         const uint64_t i = (nvec << 2) + tid;
         const float v = g[i] + pending_error(s[i], nmp, mn);
@@ -1050,23 +1054,23 @@ __global__ __launch_bounds__(BLOCK) void k_lazy_apply(const PtrTable tab, float 
     }
 }
 
-constexpr int kLazySignItems = 4;          // float4 groups of w per thread of the sign-reading apply pass
 constexpr uint32_t kLazySignLds = 8 * 1024;  // its dynamic-LDS request when streaming (20 workgroups per CU)
 
 // Apply pass on the lazy state in retained-error mode, from the sign words: there the update of an element is
 // (k * gmu_pos - (P - k) * gmu_neg) / P with k = the number of workers whose v is >= 0 (Algorithm 1 line 6 summed
 // over the workers as in Eq. 1), so the pass reads one bit per element-worker instead of v.  A workgroup is one
-// wavefront; it covers ITEMS of the kLazyItems float4 groups that each thread of one workgroup of the reduction
-// pass owned, so a thread finds its bits in that thread's word of every worker.  A NaN has no sign: if the
+// wavefront; it covers one half (4) of the float4 groups that each thread of one workgroup of the reduction pass
+// owned, so a thread finds its 16 bits in that thread's half-word of every worker.  A NaN has no sign: if the
 // reduction counted any, the pass reads v as k_lazy_apply does (a branch that is uniform over the grid).
-template <bool NT, int ITEMS, int UP>
-__global__ __launch_bounds__(64) void k_lazy_apply_signs(const PtrTable tab, const uint32_t *__restrict__ sign,
-                                                         const uint64_t row_words, float *__restrict__ w,
+template <bool NT, int UP>
+__global__ __launch_bounds__(64) void k_lazy_apply_signs(const PtrTable tab, const uint16_t *__restrict__ sign,
+                                                         const uint64_t row_halves, float *__restrict__ w,
                                                          const uint64_t n, const uint32_t P, const float eta_over_P,
                                                          const WsHeader *__restrict__ hdr)
 {
-    static_assert(kLazyItems % ITEMS == 0, "a workgroup stays inside one workgroup of the reduction pass");
+    constexpr int ITEMS = 4;
     constexpr uint32_t kParts = kLazyItems / ITEMS;
+    static_assert(kParts == 2, "two 16-bit halves per thread of the reduction pass");
     const uint32_t lane = threadIdx.x;
     const uint32_t lz = opaque_zero();
     const float gmu_pos = (&hdr->gmu_pos)[lz], gmu_neg = (&hdr->gmu_neg)[lz];
@@ -1083,7 +1087,7 @@ __global__ __launch_bounds__(64) void k_lazy_apply_signs(const PtrTable tab, con
             wv[t] = ld4<NT>(w4 + first + t * 64);
     vf4 acc[ITEMS];
     if (any_nan == 0) {
-        const uint32_t *word = sign + b * 64 + lane;
+        const uint16_t *half = sign + b * 128 + (blockIdx.x % kParts) * 64 + lane;
         uint32_t k[ITEMS][4];
 #pragma unroll
         for (int t = 0; t < ITEMS; ++t)
@@ -1093,22 +1097,22 @@ __global__ __launch_bounds__(64) void k_lazy_apply_signs(const PtrTable tab, con
             uint32_t d[UP];
 #pragma unroll
             for (int q = 0; q < UP; ++q)
-                d[q] = word[(p0 + q) * row_words];
+                d[q] = half[(p0 + q) * row_halves];
 #pragma unroll
             for (int q = 0; q < UP; ++q)
 #pragma unroll
                 for (int t = 0; t < ITEMS; ++t)
 #pragma unroll
                     for (int c = 0; c < 4; ++c)
-                        k[t][c] += (d[q] >> (31u - (4u * (u0 + t) + c))) & 1u;
+                        k[t][c] += (d[q] >> (15u - (4u * t + c))) & 1u;
         }
         for (; p0 < P; ++p0) {
-            const uint32_t d = word[p0 * row_words];
+            const uint32_t d = half[p0 * row_halves];
 #pragma unroll
             for (int t = 0; t < ITEMS; ++t)
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    k[t][c] += (d >> (31u - (4u * (u0 + t) + c))) & 1u;
+                    k[t][c] += (d >> (15u - (4u * t + c))) & 1u;
         }
         const float gsum = gmu_pos + gmu_neg, base = static_cast<float>(P) * gmu_neg;
 #pragma unroll
@@ -1413,7 +1417,7 @@ hipError_t launch_lazy_partials(const a2sgd_plan_t &pl, const PtrTable &tab, voi
     const size_t folded_offset = pl.lazy_offset + 5ull * 8ull * pl.P * pl.lazy_blocks;
     const Partials folded = partials_at(ws, folded_offset, pl.P, pl.lazy_folded);
     WsHeader *hdr = static_cast<WsHeader *>(ws);
-    uint32_t *sign = reinterpret_cast<uint32_t *>(static_cast<char *>(ws) + pl.lazy_sign_offset);
+    uint16_t *sign = reinterpret_cast<uint16_t *>(static_cast<char *>(ws) + pl.lazy_sign_offset);
     const bool signs = pl.mode == A2SGD_MODE_RETAINED_ERROR;  // the literal mode's apply pass needs v itself
     if (pl.streaming) {
         if (signs)
@@ -1462,25 +1466,21 @@ hipError_t launch_lazy_apply(const a2sgd_plan_t &pl, const PtrTable &tab, float 
     if (pl.mode == A2SGD_MODE_ALG1_LITERAL)
         return pl.streaming ? launch_lazy_apply_shape<A2SGD_MODE_ALG1_LITERAL, true>(pl, tab, w, eop, hdr, s)
                             : launch_lazy_apply_shape<A2SGD_MODE_ALG1_LITERAL, false>(pl, tab, w, eop, hdr, s);
-    // retained-error mode: from the sign words that the reduction pass left, one workgroup per kLazySignItems of
-    // the float4 groups of each of its workgroups
-    const uint32_t *sign = reinterpret_cast<const uint32_t *>(static_cast<const char *>(ws) + pl.lazy_sign_offset);
-    const uint64_t row_words = 64ull * pl.lazy_blocks;
-    const dim3 grid(pl.lazy_blocks * (kLazyItems / kLazySignItems)), block(64);
+    // retained-error mode: from the sign bits that the reduction pass left, two workgroups per workgroup of that
+    // pass (one per half of its float4 groups)
+    const uint16_t *sign = reinterpret_cast<const uint16_t *>(static_cast<const char *>(ws) + pl.lazy_sign_offset);
+    const uint64_t row_halves = 128ull * pl.lazy_blocks;
+    const dim3 grid(pl.lazy_blocks * 2), block(64);
     if (pl.streaming) {
         if (pl.P >= 4)
-            k_lazy_apply_signs<true, kLazySignItems, 4><<<grid, block, kLazySignLds, s>>>(tab, sign, row_words, w, pl.n,
-                                                                                         pl.P, eop, hdr);
+            k_lazy_apply_signs<true, 4><<<grid, block, kLazySignLds, s>>>(tab, sign, row_halves, w, pl.n, pl.P, eop, hdr);
         else
-            k_lazy_apply_signs<true, kLazySignItems, 1><<<grid, block, kLazySignLds, s>>>(tab, sign, row_words, w, pl.n,
-                                                                                         pl.P, eop, hdr);
+            k_lazy_apply_signs<true, 1><<<grid, block, kLazySignLds, s>>>(tab, sign, row_halves, w, pl.n, pl.P, eop, hdr);
     } else {
         if (pl.P >= 4)
-            k_lazy_apply_signs<false, kLazySignItems, 4><<<grid, block, 0, s>>>(tab, sign, row_words, w, pl.n, pl.P,
-                                                                               eop, hdr);
+            k_lazy_apply_signs<false, 4><<<grid, block, 0, s>>>(tab, sign, row_halves, w, pl.n, pl.P, eop, hdr);
         else
-            k_lazy_apply_signs<false, kLazySignItems, 1><<<grid, block, 0, s>>>(tab, sign, row_words, w, pl.n, pl.P,
-                                                                               eop, hdr);
+            k_lazy_apply_signs<false, 1><<<grid, block, 0, s>>>(tab, sign, row_halves, w, pl.n, pl.P, eop, hdr);
     }
     return hipGetLastError();
 }
