@@ -19,7 +19,9 @@
  *     P device pointers (copied into the kernel arguments at launch).  Everything else is host memory.
  *   - Ownership: the library never allocates, frees or keeps user device memory.  Buffers are borrowed until
  *     the work enqueued on `stream` has completed.  The plan is the only object the library owns.
- *   - Aliasing: g^p is read-only; e^p and w are updated in place.  No two of g^p, e^p, w, workspace overlap.
+ *   - Aliasing: g^p is read-only; e^p and w are updated in place.  A buffer that a call writes (e^p, w, w^p, the
+ *     workspace) must not overlap any other buffer of that call (else A2SGD_ERR_INVALID_ARG); buffers that are
+ *     only read may coincide.
  *   - Alignment: every device pointer must be 16-byte aligned (else A2SGD_ERR_ALIGNMENT).  n is arbitrary.
  *   - Asynchrony: the step calls only enqueue kernels on `stream` (a hipStream_t passed as void*; NULL is the
  *     default stream) and return.  Only a2sgd_read_stats synchronises.

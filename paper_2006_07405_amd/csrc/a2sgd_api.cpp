@@ -1,5 +1,6 @@
 // Host side of the C ABI declared in include/a2sgd.h: plan construction, argument validation, and the
 // sequencing of the kernels of one step.  No device memory is allocated here.
+#include <algorithm>
 #include <atomic>
 #include <new>
 #include <vector>
@@ -146,6 +147,43 @@ void fill_table(PtrTable &t, uint32_t P, const float *const *g, const float *con
     }
 }
 
+// Address ranges of one call, for the aliasing rule: a buffer that the call writes must not overlap any other
+// buffer of the call; buffers that are only read may coincide (two workers may share one g).
+struct Ranges {
+    struct R {
+        uintptr_t lo, hi;
+        bool written;
+    };
+    R r[3 * kMaxWorkers + 2];
+    size_t count = 0;
+    void add(const void *p, uint64_t bytes, bool written)
+    {
+        if (p != nullptr && bytes != 0 && count < sizeof(r) / sizeof(r[0]))
+            r[count++] = R{reinterpret_cast<uintptr_t>(p), reinterpret_cast<uintptr_t>(p) + bytes, written};
+    }
+    void add_table(const float *const *tab, uint32_t P, uint64_t n, bool written)
+    {
+        for (uint32_t p = 0; tab != nullptr && p < P; ++p)
+            add(tab[p], 4 * n, written);
+    }
+    // In order of start address, an earlier range overlaps the current one exactly if it ends after the
+    // current one starts; so it is enough to carry the furthest end seen so far, of all ranges and of the
+    // written ones.
+    bool disjoint()
+    {
+        std::sort(r, r + count, [](const R &a, const R &b) { return a.lo < b.lo; });
+        uintptr_t end_any = 0, end_written = 0;
+        for (size_t i = 0; i < count; ++i) {
+            if (r[i].lo < (r[i].written ? end_any : end_written))
+                return false;
+            end_any = r[i].hi > end_any ? r[i].hi : end_any;
+            if (r[i].written)
+                end_written = r[i].hi > end_written ? r[i].hi : end_written;
+        }
+        return true;
+    }
+};
+
 inline a2sgd_status_t dev(hipError_t err) { return err == hipSuccess ? A2SGD_OK : A2SGD_ERR_DEVICE; }
 
 // Validation shared by the calls that take g and e.  In retained-error mode e is required.
@@ -158,6 +196,20 @@ a2sgd_status_t check_g_e(const a2sgd_plan_t *plan, const float *const *g, const 
     if (st != A2SGD_OK)
         return st;
     return check_table(e, plan->P, plan->mode == A2SGD_MODE_RETAINED_ERROR, has_e);
+}
+
+// The aliasing rule for a call that reads g, updates e (if given) and w (one vector, or one per worker) in place
+// and uses the workspace.
+a2sgd_status_t check_step_ranges(const a2sgd_plan_t *plan, const float *const *g, const float *const *e, const float *w,
+                                 const float *const *w_replicas, const void *workspace)
+{
+    Ranges rg;
+    rg.add_table(g, plan->P, plan->n, false);
+    rg.add_table(e, plan->P, plan->n, true);
+    rg.add(w, 4 * plan->n, true);
+    rg.add_table(w_replicas, plan->P, plan->n, true);
+    rg.add(workspace, plan->workspace_bytes, true);
+    return rg.disjoint() ? A2SGD_OK : A2SGD_ERR_INVALID_ARG;
 }
 
 }  // namespace
@@ -256,6 +308,12 @@ a2sgd_status_t a2sgd_local_averages(const a2sgd_plan_t *plan, const float *const
         return st;
     if ((st = check_buffer(workspace)) != A2SGD_OK)
         return st;
+    Ranges rg;
+    rg.add_table(g, plan->P, plan->n, false);
+    rg.add_table(has_e ? e : nullptr, plan->P, plan->n, false);
+    rg.add(workspace, plan->workspace_bytes, true);
+    if (!rg.disjoint())
+        return A2SGD_ERR_INVALID_ARG;
     PtrTable tab;
     fill_table(tab, plan->P, g, has_e ? e : nullptr);
     plan->last_token = 0;
@@ -293,6 +351,8 @@ a2sgd_status_t a2sgd_apply_and_update_error(const a2sgd_plan_t *plan, const floa
         return st;
     if ((st = check_buffer(workspace)) != A2SGD_OK)
         return st;
+    if ((st = check_step_ranges(plan, g, has_e ? e : nullptr, w, nullptr, workspace)) != A2SGD_OK)
+        return st;
     PtrTable tab;
     fill_table(tab, plan->P, g, has_e ? e : nullptr);
     if (segmented(plan))
@@ -311,6 +371,8 @@ a2sgd_status_t a2sgd_step(const a2sgd_plan_t *plan, const float *const *g, float
     if ((st = check_buffer(w)) != A2SGD_OK)
         return st;
     if ((st = check_buffer(workspace)) != A2SGD_OK)
+        return st;
+    if ((st = check_step_ranges(plan, g, has_e ? e : nullptr, w, nullptr, workspace)) != A2SGD_OK)
         return st;
     if (plan->fused_grid != 0) {
         PtrTable tab;
@@ -364,6 +426,12 @@ a2sgd_status_t a2sgd_export_mask(const a2sgd_plan_t *plan, const float *const *g
         return st;
     if ((st = check_buffer(mask)) != A2SGD_OK)
         return st;
+    Ranges rg;
+    rg.add_table(g, plan->P, plan->n, false);
+    rg.add_table(has_e ? e : nullptr, plan->P, plan->n, false);
+    rg.add(mask, 8ull * plan->P * ((plan->n + 63) / 64), true);
+    if (!rg.disjoint())
+        return A2SGD_ERR_INVALID_ARG;
     PtrTable tab;
     fill_table(tab, plan->P, g, has_e ? e : nullptr);
     return dev(launch_export_mask(*plan, tab, has_e, mask, static_cast<hipStream_t>(stream)));
@@ -379,6 +447,8 @@ a2sgd_status_t a2sgd_dense_step(const a2sgd_plan_t *plan, const float *const *g,
     if (st != A2SGD_OK)
         return st;
     if ((st = check_buffer(w)) != A2SGD_OK)
+        return st;
+    if ((st = check_step_ranges(plan, g, nullptr, w, nullptr, nullptr)) != A2SGD_OK)
         return st;
     PtrTable tab;
     fill_table(tab, plan->P, g, nullptr);
@@ -398,6 +468,8 @@ a2sgd_status_t a2sgd_apply_and_update_error_replicas(const a2sgd_plan_t *plan, c
     if ((st = check_table(w, plan->P, true, &has_w)) != A2SGD_OK)
         return st;
     if ((st = check_buffer(workspace)) != A2SGD_OK)
+        return st;
+    if ((st = check_step_ranges(plan, g, has_e ? e : nullptr, nullptr, w, workspace)) != A2SGD_OK)
         return st;
     PtrTable tab;
     ReplicaTable wt;
@@ -419,6 +491,8 @@ a2sgd_status_t a2sgd_step_replicas(const a2sgd_plan_t *plan, const float *const 
         return st;
     if ((st = check_buffer(workspace)) != A2SGD_OK)
         return st;
+    if ((st = check_step_ranges(plan, g, has_e ? e : nullptr, nullptr, w, workspace)) != A2SGD_OK)
+        return st;
     if ((st = a2sgd_local_averages(plan, g, e, workspace, stream)) != A2SGD_OK)
         return st;
     if ((st = a2sgd_global_average(plan, workspace, stream)) != A2SGD_OK)
@@ -436,6 +510,8 @@ a2sgd_status_t a2sgd_dense_step_replicas(const a2sgd_plan_t *plan, const float *
     if (st != A2SGD_OK)
         return st;
     if ((st = check_table(w, plan->P, true, &has_w)) != A2SGD_OK)
+        return st;
+    if ((st = check_step_ranges(plan, g, nullptr, nullptr, w, nullptr)) != A2SGD_OK)
         return st;
     PtrTable tab;
     ReplicaTable wt;
@@ -499,6 +575,8 @@ a2sgd_status_t a2sgd_lazy_step(const a2sgd_plan_t *plan, const float *const *g, 
     if ((st = check_buffer(w)) != A2SGD_OK)
         return st;
     if ((st = check_buffer(workspace)) != A2SGD_OK)
+        return st;
+    if ((st = check_step_ranges(plan, g, s, w, nullptr, workspace)) != A2SGD_OK)
         return st;
     PtrTable tab;
     fill_table(tab, plan->P, g, s);

@@ -131,6 +131,17 @@ def test_step_calls_validate_before_launch(A):
     assert R.a2sgd_dense_step(h, None, w, 0.1, None) == INV
     assert R.a2sgd_dense_step(h, good, w + 2, 0.1, None) == ALN
     assert R.a2sgd_read_stats(h, None, None, None, None) == INV
+    # aliasing: a written buffer may not overlap anything else of the call; read-only ones may coincide
+    other = _tab([0x50000, 0x60000])
+    same_g = _tab([0x10000, 0x10000])
+    assert R.a2sgd_step(h, good, good, w, 0.1, ws, None) == INV                    # e^p is g^p
+    assert R.a2sgd_step(h, good, _tab([0x50000, 0x50000 + 3984]), w, 0.1, ws, None) == INV  # e^0 and e^1 overlap by 16 B
+    assert R.a2sgd_step(h, good, other, 0x50000 + 2000, 0.1, ws, None) == INV      # w inside e^0
+    assert R.a2sgd_apply_and_update_error(h, good, other, w, 0.1, 0x60000 + 1600, None) == INV  # workspace inside e^1
+    assert R.a2sgd_local_averages(h, good, other, 0x10000 + 3200, None) == INV     # workspace inside g^0
+    assert R.a2sgd_dense_step(h, good, 0x20000 + 160, 0.1, None) == INV            # w inside g^1
+    assert R.a2sgd_lazy_step(h, same_g, other, 0x50000 + 800, 0.1, ws, None) == INV
+    assert R.a2sgd_step_replicas(h, same_g, other, _tab([0x70000, 0x70000]), 0.1, ws, None) == INV  # w^0 is w^1
     assert R.a2sgd_status_string(ALN) == b"device pointer not 16-byte aligned"
 
 
