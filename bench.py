@@ -36,6 +36,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--blocks-per-worker", type=int, default=0)
     ap.add_argument("--n", type=int, default=0, help="override n (config 1 only: one flat tensor)")
+    ap.add_argument("--workers", type=int, default=0, help="override P (config 1 only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-tensor", action="store_true",
                     help="one pair of means per worker and tensor of the workload's layout instead of per worker")
@@ -60,9 +61,9 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     wl = workloads.FULL[args.config]()
-    if args.n:
-        assert args.config == 1, "--n applies to the flat workload of config 1"
-        wl = workloads.config1(n=args.n)
+    if args.n or args.workers:
+        assert args.config == 1, "--n and --workers apply to the flat workload of config 1"
+        wl = workloads.config1(n=args.n or wl.n, num_workers=args.workers or wl.num_workers)
     n, P = wl.n, wl.num_workers
     # the big buffers are allocated before anything else touches the device heap, then filled in place
     g = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(P)]

@@ -101,7 +101,8 @@ uint32_t choose_blocks_per_worker(uint64_t n, uint32_t P)
 {
     const uint64_t tile = static_cast<uint64_t>(kBlock) * kReduceUnroll * 4;  // elements per tile
     uint64_t tiles = (n + tile - 1) / tile;
-    uint64_t want = (static_cast<uint64_t>(kComputeUnits) * kReduceBlocksPerCU + P - 1) / P;
+    // rounded down: one workgroup more than the chip holds at once would run after all the others
+    uint64_t want = static_cast<uint64_t>(kComputeUnits) * kReduceBlocksPerCU / P;
     uint64_t B = tiles < want ? tiles : want;
     if (B < 1)
         B = 1;

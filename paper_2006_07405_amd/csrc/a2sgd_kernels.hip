@@ -4,6 +4,8 @@
 // fused elementwise pass (lines 4, 6, 7).  Every global access of the two big passes is a 128-bit load or
 // store, consecutive lanes touching consecutive 16-byte groups, so a wavefront moves 1 KiB per instruction.
 // No matrix cores: there is no contraction anywhere in the method.
+#include <type_traits>
+
 #include "a2sgd_device.h"
 
 namespace a2sgd {
@@ -194,70 +196,59 @@ __device__ __forceinline__ void apply_body(const PtrTable &tab, float *__restric
         if (FULL || base + it * BLOCK < nvec)
             wv[it] = ld4<NT>(w4 + base + it * BLOCK);
     }
-    uint32_t p0 = 0;
-    for (; p0 + UP <= P; p0 += UP) {
+    // One group of up to UP workers starting at p0.  With PARTIAL the group may be short: worker p0 + u takes part
+    // only if it exists, a test that is uniform over the grid.
+    auto group = [&](auto partial, const uint32_t p0) {
+        constexpr bool PARTIAL = decltype(partial)::value;
         vf4 v[UP * ITEMS], ev[UP * ITEMS];
         float nmp[UP], mn[UP];
 #pragma unroll
-        for (int u = 0; u < UP; ++u) {
-            nmp[u] = neg_mu_pos[p0 + u];
-            mn[u] = mu_neg[p0 + u];
-        }
+        for (int u = 0; u < UP; ++u)
+            if (!PARTIAL || p0 + u < P) {
+                nmp[u] = neg_mu_pos[p0 + u];
+                mn[u] = mu_neg[p0 + u];
+            }
 #pragma unroll
-        for (int u = 0; u < UP; ++u) {
-            const vf4 *gp = reinterpret_cast<const vf4 *>(tab.g[p0 + u]);
-#pragma unroll
-            for (int it = 0; it < ITEMS; ++it)
-                if (FULL || base + it * BLOCK < nvec)
-                    v[u * ITEMS + it] = ld4<NT>(gp + base + it * BLOCK);
-        }
-        if (HAS_E) {
-#pragma unroll
-            for (int u = 0; u < UP; ++u) {
-                const vf4 *ep = reinterpret_cast<const vf4 *>(tab.e[p0 + u]);
+        for (int u = 0; u < UP; ++u)
+            if (!PARTIAL || p0 + u < P) {
+                const vf4 *gp = reinterpret_cast<const vf4 *>(tab.g[p0 + u]);
 #pragma unroll
                 for (int it = 0; it < ITEMS; ++it)
                     if (FULL || base + it * BLOCK < nvec)
-                        ev[u * ITEMS + it] = ld4<NT>(ep + base + it * BLOCK);
+                        v[u * ITEMS + it] = ld4<NT>(gp + base + it * BLOCK);
             }
+        if (HAS_E) {
+#pragma unroll
+            for (int u = 0; u < UP; ++u)
+                if (!PARTIAL || p0 + u < P) {
+                    const vf4 *ep = reinterpret_cast<const vf4 *>(tab.e[p0 + u]);
+#pragma unroll
+                    for (int it = 0; it < ITEMS; ++it)
+                        if (FULL || base + it * BLOCK < nvec)
+                            ev[u * ITEMS + it] = ld4<NT>(ep + base + it * BLOCK);
+                }
         }
         __builtin_amdgcn_sched_barrier(0);  // keep every load of the group ahead of the first use
 #pragma unroll
-        for (int u = 0; u < UP; ++u) {
-            vf4 *ep = reinterpret_cast<vf4 *>(tab.e[p0 + u]);
+        for (int u = 0; u < UP; ++u)
+            if (!PARTIAL || p0 + u < P) {
+                vf4 *ep = reinterpret_cast<vf4 *>(tab.e[p0 + u]);
 #pragma unroll
-            for (int it = 0; it < ITEMS; ++it) {
-                if (FULL || base + it * BLOCK < nvec) {
-                    const vf4 vv = HAS_E ? v[u * ITEMS + it] + ev[u * ITEMS + it] : v[u * ITEMS + it];
-                    const vf4 err = apply4<MODE>(vv, acc[it], nmp[u], mn[u], gmu_pos, neg_gmu_neg);
-                    if (HAS_E)
-                        st4<NT>(ep + base + it * BLOCK, err);
+                for (int it = 0; it < ITEMS; ++it) {
+                    if (FULL || base + it * BLOCK < nvec) {
+                        const vf4 vv = HAS_E ? v[u * ITEMS + it] + ev[u * ITEMS + it] : v[u * ITEMS + it];
+                        const vf4 err = apply4<MODE>(vv, acc[it], nmp[u], mn[u], gmu_pos, neg_gmu_neg);
+                        if (HAS_E)
+                            st4<NT>(ep + base + it * BLOCK, err);
+                    }
                 }
             }
-        }
-    }
-    for (; p0 < P; ++p0) {  // workers past the last full group of UP
-        const vf4 *gp = reinterpret_cast<const vf4 *>(tab.g[p0]);
-        vf4 *ep = reinterpret_cast<vf4 *>(tab.e[p0]);
-        const float nmp = neg_mu_pos[p0], mn = mu_neg[p0];
-        vf4 v[ITEMS], ev[ITEMS];
-#pragma unroll
-        for (int it = 0; it < ITEMS; ++it)
-            if (FULL || base + it * BLOCK < nvec) {
-                v[it] = ld4<NT>(gp + base + it * BLOCK);
-                if (HAS_E)
-                    ev[it] = ld4<NT>(ep + base + it * BLOCK);
-            }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int it = 0; it < ITEMS; ++it)
-            if (FULL || base + it * BLOCK < nvec) {
-                const vf4 vv = HAS_E ? v[it] + ev[it] : v[it];
-                const vf4 err = apply4<MODE>(vv, acc[it], nmp, mn, gmu_pos, neg_gmu_neg);
-                if (HAS_E)
-                    st4<NT>(ep + base + it * BLOCK, err);
-            }
-    }
+    };
+    uint32_t p0 = 0;
+    for (; p0 + UP <= P; p0 += UP)
+        group(std::false_type{}, p0);
+    if (UP > 1 && p0 < P)  // the workers past the last full group, in one short group
+        group(std::true_type{}, p0);
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it)
         if (FULL || base + it * BLOCK < nvec) {
@@ -605,28 +596,30 @@ __global__ __launch_bounds__(BLOCK) void k_dense_step(const PtrTable tab, float 
         if (base + it * BLOCK < nvec)
             wv[it] = ld4<NT>(w4 + base + it * BLOCK);
     }
-    uint32_t p0 = 0;
-    for (; p0 + UP <= P; p0 += UP) {
+    auto group = [&](auto partial, const uint32_t p0) {  // up to UP workers; PARTIAL: the last, short group
+        constexpr bool PARTIAL = decltype(partial)::value;
         vf4 v[UP * ITEMS];
 #pragma unroll
         for (int u = 0; u < UP; ++u)
+            if (!PARTIAL || p0 + u < P)
 #pragma unroll
-            for (int it = 0; it < ITEMS; ++it)
-                if (base + it * BLOCK < nvec)
-                    v[u * ITEMS + it] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + base + it * BLOCK);
+                for (int it = 0; it < ITEMS; ++it)
+                    if (base + it * BLOCK < nvec)
+                        v[u * ITEMS + it] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + base + it * BLOCK);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < UP; ++u)
+            if (!PARTIAL || p0 + u < P)
 #pragma unroll
-            for (int it = 0; it < ITEMS; ++it)
-                if (base + it * BLOCK < nvec)
-                    acc[it] += v[u * ITEMS + it];
-    }
-    for (; p0 < P; ++p0)
-#pragma unroll
-        for (int it = 0; it < ITEMS; ++it)
-            if (base + it * BLOCK < nvec)
-                acc[it] += ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0]) + base + it * BLOCK);
+                for (int it = 0; it < ITEMS; ++it)
+                    if (base + it * BLOCK < nvec)
+                        acc[it] += v[u * ITEMS + it];
+    };
+    uint32_t p0 = 0;
+    for (; p0 + UP <= P; p0 += UP)
+        group(std::false_type{}, p0);
+    if (UP > 1 && p0 < P)
+        group(std::true_type{}, p0);
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it)
         if (base + it * BLOCK < nvec) {
@@ -662,50 +655,48 @@ __global__ __launch_bounds__(BLOCK) void k_apply_replicas(const PtrTable tab, co
     const uint64_t nvec = n >> 2;
     const uint64_t i = static_cast<uint64_t>(blockIdx.x) * BLOCK + tid;
     if (i < nvec) {
-        uint32_t p0 = 0;
-        for (; p0 + UP <= P; p0 += UP) {
+        auto group = [&](auto partial, const uint32_t p0) {  // up to UP workers; PARTIAL: the last, short group
+            constexpr bool PARTIAL = decltype(partial)::value;
             vf4 v[UP], ev[UP], wv[UP];
             float nmp[UP], mn[UP];
 #pragma unroll
-            for (int u = 0; u < UP; ++u) {
-                nmp[u] = neg_mu_pos[p0 + u];
-                mn[u] = mu_neg[p0 + u];
-            }
+            for (int u = 0; u < UP; ++u)
+                if (!PARTIAL || p0 + u < P) {
+                    nmp[u] = neg_mu_pos[p0 + u];
+                    mn[u] = mu_neg[p0 + u];
+                }
 #pragma unroll
             for (int u = 0; u < UP; ++u)
-                v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + i);
+                if (!PARTIAL || p0 + u < P)
+                    v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + i);
             if (HAS_E) {
 #pragma unroll
                 for (int u = 0; u < UP; ++u)
-                    ev[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0 + u]) + i);
+                    if (!PARTIAL || p0 + u < P)
+                        ev[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0 + u]) + i);
             }
 #pragma unroll
             for (int u = 0; u < UP; ++u)
-                wv[u] = ld4<NT>(reinterpret_cast<const vf4 *>(wt.w[p0 + u]) + i);
+                if (!PARTIAL || p0 + u < P)
+                    wv[u] = ld4<NT>(reinterpret_cast<const vf4 *>(wt.w[p0 + u]) + i);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int u = 0; u < UP; ++u) {
-                const vf4 vv = HAS_E ? v[u] + ev[u] : v[u];
-                vf4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
-                const vf4 err = apply4<MODE>(vv, upd, nmp[u], mn[u], gmu_pos, neg_gmu_neg);
-                if (HAS_E)
-                    st4<NT>(reinterpret_cast<vf4 *>(tab.e[p0 + u]) + i, err);
-                const vf4 wn = wv[u] - eta * upd;
-                st4<NT>(reinterpret_cast<vf4 *>(wt.w[p0 + u]) + i, wn);
-            }
-        }
-        for (; p0 < P; ++p0) {
-            vf4 vv = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0]) + i);
-            if (HAS_E)
-                vv += ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0]) + i);
-            const vf4 wv = ld4<NT>(reinterpret_cast<const vf4 *>(wt.w[p0]) + i);
-            vf4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
-            const vf4 err = apply4<MODE>(vv, upd, neg_mu_pos[p0], mu_neg[p0], gmu_pos, neg_gmu_neg);
-            if (HAS_E)
-                st4<NT>(reinterpret_cast<vf4 *>(tab.e[p0]) + i, err);
-            const vf4 wn = wv - eta * upd;
-            st4<NT>(reinterpret_cast<vf4 *>(wt.w[p0]) + i, wn);
-        }
+            for (int u = 0; u < UP; ++u)
+                if (!PARTIAL || p0 + u < P) {
+                    const vf4 vv = HAS_E ? v[u] + ev[u] : v[u];
+                    vf4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
+                    const vf4 err = apply4<MODE>(vv, upd, nmp[u], mn[u], gmu_pos, neg_gmu_neg);
+                    if (HAS_E)
+                        st4<NT>(reinterpret_cast<vf4 *>(tab.e[p0 + u]) + i, err);
+                    const vf4 wn = wv[u] - eta * upd;
+                    st4<NT>(reinterpret_cast<vf4 *>(wt.w[p0 + u]) + i, wn);
+                }
+        };
+        uint32_t p0 = 0;
+        for (; p0 + UP <= P; p0 += UP)
+            group(std::false_type{}, p0);
+        if (UP > 1 && p0 < P)
+            group(std::true_type{}, p0);
     }
     if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
         const uint64_t k = (nvec << 2) + tid;
@@ -732,37 +723,45 @@ __global__ __launch_bounds__(BLOCK) void k_dense_step_replicas(const PtrTable ta
     const uint64_t i = static_cast<uint64_t>(blockIdx.x) * BLOCK + tid;
     if (i < nvec) {
         vf4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-        uint32_t p0 = 0;
-        for (; p0 + UP <= P; p0 += UP) {
+        vf4 step;
+        auto sum_group = [&](auto partial, const uint32_t p0) {  // up to UP workers; PARTIAL: the last, short group
+            constexpr bool PARTIAL = decltype(partial)::value;
             vf4 v[UP];
 #pragma unroll
             for (int u = 0; u < UP; ++u)
-                v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + i);
+                if (!PARTIAL || p0 + u < P)
+                    v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + i);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < UP; ++u)
-                acc += v[u];
-        }
-        for (; p0 < P; ++p0)
-            acc += ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0]) + i);
-        const vf4 step = eta_over_P * acc;
-        p0 = 0;
-        for (; p0 + UP <= P; p0 += UP) {
+                if (!PARTIAL || p0 + u < P)
+                    acc += v[u];
+        };
+        auto update_group = [&](auto partial, const uint32_t p0) {
+            constexpr bool PARTIAL = decltype(partial)::value;
             vf4 wv[UP];
 #pragma unroll
             for (int u = 0; u < UP; ++u)
-                wv[u] = ld4<NT>(reinterpret_cast<const vf4 *>(wt.w[p0 + u]) + i);
+                if (!PARTIAL || p0 + u < P)
+                    wv[u] = ld4<NT>(reinterpret_cast<const vf4 *>(wt.w[p0 + u]) + i);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int u = 0; u < UP; ++u) {
-                const vf4 wn = wv[u] - step;
-                st4<NT>(reinterpret_cast<vf4 *>(wt.w[p0 + u]) + i, wn);
-            }
-        }
-        for (; p0 < P; ++p0) {
-            const vf4 wn = ld4<NT>(reinterpret_cast<const vf4 *>(wt.w[p0]) + i) - step;
-            st4<NT>(reinterpret_cast<vf4 *>(wt.w[p0]) + i, wn);
-        }
+            for (int u = 0; u < UP; ++u)
+                if (!PARTIAL || p0 + u < P) {
+                    const vf4 wn = wv[u] - step;
+                    st4<NT>(reinterpret_cast<vf4 *>(wt.w[p0 + u]) + i, wn);
+                }
+        };
+        uint32_t p0 = 0;
+        for (; p0 + UP <= P; p0 += UP)
+            sum_group(std::false_type{}, p0);
+        if (UP > 1 && p0 < P)
+            sum_group(std::true_type{}, p0);
+        step = eta_over_P * acc;
+        for (p0 = 0; p0 + UP <= P; p0 += UP)
+            update_group(std::false_type{}, p0);
+        if (UP > 1 && p0 < P)
+            update_group(std::true_type{}, p0);
     }
     if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
         const uint64_t k = (nvec << 2) + tid;
@@ -1020,26 +1019,31 @@ __global__ __launch_bounds__(BLOCK) void k_lazy_apply(const PtrTable tab, float 
         vf4 *w4 = reinterpret_cast<vf4 *>(w) + i;
         const vf4 wv = ld4<NT>(w4);
         vf4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-        uint32_t p0 = 0;
-        for (; p0 + UP <= P; p0 += UP) {
+        auto group = [&](auto partial, const uint32_t p0) {  // up to UP workers; PARTIAL: the last, short group
+            constexpr bool PARTIAL = decltype(partial)::value;
             vf4 v[UP];
             float nmp[UP], mn[UP];
 #pragma unroll
-            for (int u = 0; u < UP; ++u) {
-                nmp[u] = neg_mu_pos[p0 + u];
-                mn[u] = mu_neg[p0 + u];
-            }
+            for (int u = 0; u < UP; ++u)
+                if (!PARTIAL || p0 + u < P) {
+                    nmp[u] = neg_mu_pos[p0 + u];
+                    mn[u] = mu_neg[p0 + u];
+                }
 #pragma unroll
             for (int u = 0; u < UP; ++u)
-                v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0 + u]) + i);
+                if (!PARTIAL || p0 + u < P)
+                    v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0 + u]) + i);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < UP; ++u)
-                (void)apply4<MODE>(v[u], acc, nmp[u], mn[u], gmu_pos, neg_gmu_neg);
-        }
-        for (; p0 < P; ++p0)
-            (void)apply4<MODE>(ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0]) + i), acc, neg_mu_pos[p0], mu_neg[p0],
-                               gmu_pos, neg_gmu_neg);
+                if (!PARTIAL || p0 + u < P)
+                    (void)apply4<MODE>(v[u], acc, nmp[u], mn[u], gmu_pos, neg_gmu_neg);
+        };
+        uint32_t p0 = 0;
+        for (; p0 + UP <= P; p0 += UP)
+            group(std::false_type{}, p0);
+        if (UP > 1 && p0 < P)
+            group(std::true_type{}, p0);
         const vf4 wn = wv - eta_over_P * acc;
         st4<NT>(w4, wn);
     }
