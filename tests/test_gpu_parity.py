@@ -276,6 +276,43 @@ def test_dense_step(A):
         assert_array_close(wd.cpu().numpy(), O.dense_step(g, w, 0.1), f"dense n={n} P={P}")
 
 
+@pytest.mark.parametrize("n,P", [(8_000_003, 3), (3_500_003, 7), (2_100_001, 12), (1_700_003, 15), (1_000_001, 33)])
+def test_streaming_path_with_worker_counts_that_leave_a_short_group(A, n, P):
+    """Footprints above the cache limit take the streaming kernels (non-temporal loads, write-through stores, capped
+    residency); these P are not multiples of the group size, so the last group of workers is a short one.  Eager
+    step in both modes, the dense step, the replica step and the lazy step (literal mode reads v in groups too)."""
+    assert (2 * P + 1) * 4 * n > 192 << 20
+    g, e, w = make_case(n + P, n, P)
+    for mode in (0, 1):
+        check_against_oracle(A, g, e, w, 0.1, mode, want_mask=False)
+    plan = A.a2sgd_plan(n, P, 1)
+    ws = A.alloc_workspace(plan)
+    gd = [dev(x) for x in g]
+    wd = dev(w)
+    A.a2sgd_dense_step(plan, gd, wd, 0.1)
+    assert_array_close(wd.cpu().numpy(), O.dense_step(g, w, 0.1), "dense w")
+    # replicas (all starting from w) in literal mode, then the dense step on replicas
+    ed, wr = [dev(x) for x in e], [dev(w) for _ in range(P)]
+    A.a2sgd_step_replicas(plan, gd, ed, wr, 0.1, ws)
+    _, _, e_ref, w_ref = O.step_replicas(g, e, [w] * P, 0.1, 1)
+    for p in range(P):
+        assert_array_close(ed[p].cpu().numpy(), e_ref[p], f"replica e[{p}]")
+        assert_array_close(wr[p].cpu().numpy(), w_ref[p], f"replica w[{p}]")
+    A.a2sgd_dense_step_replicas(plan, gd, wr, 0.05)
+    ref = O.dense_step_replicas(g, w_ref, 0.05)
+    for p in range(P):
+        assert_array_close(wr[p].cpu().numpy(), ref[p], f"dense replica w[{p}]")
+    # lazy step, literal mode, from the same inputs
+    s, wl_ = [dev(x) for x in e], dev(w)
+    A.a2sgd_lazy_reset(plan, ws)
+    A.a2sgd_lazy_step(plan, gd, s, wl_, 0.1, ws)
+    A.a2sgd_lazy_materialize(plan, s, ws)
+    ref1 = O.step(g, e, w, 0.1, 1)
+    assert_array_close(wl_.cpu().numpy(), ref1.w_new, "lazy w")
+    for p in range(P):
+        assert_array_close(s[p].cpu().numpy(), ref1.e_new[p], f"lazy e[{p}]")
+
+
 def test_runs_on_a_side_stream_and_respects_stream_order(A):
     g, e, w = make_case(4242, 1_000_003, 4)
     ref = O.step(g, e, w, 0.1, 0)
