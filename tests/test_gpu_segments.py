@@ -91,6 +91,17 @@ def test_segment_layouts(A, seg):
         run_case(A, g, e if with_e else None, w, 0.1, mode, seg, split_calls=split)
 
 
+@pytest.mark.parametrize("P,mode", [(7, 0), (12, 1)])
+def test_streaming_size_with_a_short_group_of_workers(A, P, mode):
+    """A footprint above the cache limit (streaming kernels) with tensor boundaries of every alignment and a worker
+    count that is not a multiple of the group size."""
+    seg = [1_000_003, 5, 777_777, 64, 1_300_001, 131_072, 2, 291_079]
+    n = sum(seg)
+    assert (2 * P + 1) * 4 * n > 192 << 20
+    g, e, w = make_case(n + P, n, P, scales_for(seg, P))
+    run_case(A, g, e, w, 0.1, mode, seg)
+
+
 @pytest.mark.parametrize("k", [2, 3, 4, 5])
 def test_small_model_shapes(A, k):
     wl = workloads.small(k)
