@@ -485,6 +485,46 @@ def test_step_captured_in_a_hip_graph(A, n, P, calls):
         assert torch.equal(w, expected[k][1]), f"replay {k}: w differs from eager"
 
 
+def test_random_shapes_against_the_oracle(A):
+    """Seeded random draws of (n, P, mode, e present, blocks per worker, which calls): the combinations nobody
+    thought of.  Sizes are skewed towards the small and ragged, where the bounds logic lives."""
+    rng = np.random.default_rng(20260607)
+    for case in range(60):
+        P = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 11, 13, 16, 17, 31, 32, 33, 47, 63, 64]))
+        n = int(rng.choice([rng.integers(1, 70), rng.integers(70, 5000), rng.integers(5000, 2_000_000 // P + 5001)]))
+        mode = int(rng.integers(0, 2))
+        with_e = bool(mode == 0 or rng.integers(0, 2))
+        bpw = int(rng.choice([0, 0, 1, 3, 64, 1000]))
+        path = str(rng.choice(["three", "step", "lazy", "replicas"]))
+        print(f"case {case}: n={n} P={P} mode={mode} e={with_e} blocks_per_worker={bpw} path={path}", flush=True)
+        g, e, w = make_case(case, n, P)
+        if path in ("three", "step"):
+            check_against_oracle(A, g, e if with_e else None, w, 0.1, mode, blocks_per_worker=bpw,
+                                 split_calls=(path == "three"))
+            continue
+        plan = A.a2sgd_plan(n, P, mode, bpw)
+        ws = A.alloc_workspace(plan)
+        gd, ed = [dev(x) for x in g], [dev(x) for x in e]
+        if path == "lazy":
+            wd = dev(w)
+            A.a2sgd_lazy_reset(plan, ws)
+            A.a2sgd_lazy_step(plan, gd, ed, wd, 0.1, ws)
+            stats, gmu = A.a2sgd_read_stats(plan, ws)
+            A.a2sgd_lazy_materialize(plan, ed, ws)
+            ref = O.step(g, e, w, 0.1, mode)
+            compare_stats(stats, gmu, ref)
+            assert_array_close(wd.cpu().numpy(), ref.w_new, "lazy w")
+            for p in range(P):
+                assert_array_close(ed[p].cpu().numpy(), ref.e_new[p], f"lazy e[{p}]")
+        else:
+            wr = [dev(w + f32(1e-3) * f32(p)) for p in range(P)]
+            A.a2sgd_step_replicas(plan, gd, ed, wr, 0.1, ws)
+            _, _, e_ref, w_ref = O.step_replicas(g, e, [w + f32(1e-3) * f32(p) for p in range(P)], 0.1, mode)
+            for p in range(P):
+                assert_array_close(ed[p].cpu().numpy(), e_ref[p], f"replica e[{p}]")
+                assert_array_close(wr[p].cpu().numpy(), w_ref[p], f"replica w[{p}]")
+
+
 def test_grid_barrier_gives_up_instead_of_hanging(A):
     """The bounded wait of the single-launch step's barrier, forced from the host on a spare cell: all workgroups
     pass a complete barrier; all give up, and exit, when one arrival is missing.  Steps still work afterwards."""
