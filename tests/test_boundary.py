@@ -166,3 +166,12 @@ def test_product_does_not_import_the_oracle():
         if f.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2006_07405_amd" not in text and "a2sgd.h" not in text
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU is all this build uses: the benchmark says so and exits before it touches torch or the device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=60)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout == ""
