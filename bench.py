@@ -196,13 +196,9 @@ def main() -> int:
     ev1.record()
     torch.cuda.synchronize()
     del scratch
-    props = torch.cuda.get_device_properties(0)
-    clock_khz, bus_bits = getattr(props, "memory_clock_rate", None), getattr(props, "memory_bus_width", None)
     out["hbm_reference"] = {"published_peak_gbps": HBM_PEAK_GBPS, "used_for_frac": "published_peak_gbps",
                             "plain_copy_gbps": 8 * n / (ev0.elapsed_time(ev1) / 5 * 1e-3) / 1e9,
-                            "device_props": {"memory_clock_khz": clock_khz, "memory_bus_bits": bus_bits,
-                                             "ddr_peak_gbps": None if not (clock_khz and bus_bits)
-                                             else 2 * clock_khz * 1e3 * bus_bits / 8 / 1e9}}
+                            "device_reports": A.a2sgd_device_info()}
 
     if plan.num_segments:  # the lazy state is not offered with per-tensor means
         if not args.no_cpu_baseline:

@@ -226,6 +226,20 @@ a2sgd_status_t a2sgd_selftest_barrier(void *scratch, a2sgd_stream_t stream);
 /* Geometry the plan chose, for reports: blocks per worker of the first-level reduction. */
 uint32_t a2sgd_plan_blocks_per_worker(const a2sgd_plan_t *plan);
 
+/* What the current HIP device reports about itself, for benchmark reports: compute units, memory clock (kHz) and
+ * bus width (bits), total device memory and L2 size in bytes.  (An MI355X reports 2,000,000 kHz and 8192 bits; its
+ * HBM3E moves 4 bits per pin and reported clock, 8192 GB/s, which the published 8000 GB/s rounds.)  Host call;
+ * `out` is host memory. */
+typedef struct {
+    uint32_t compute_units;
+    uint32_t memory_clock_khz;
+    uint32_t memory_bus_bits;
+    uint32_t reserved;
+    uint64_t total_memory_bytes;
+    uint64_t l2_bytes;
+} a2sgd_device_info_t;
+a2sgd_status_t a2sgd_device_info(a2sgd_device_info_t *out);
+
 const char *a2sgd_status_string(a2sgd_status_t status);
 
 #ifdef __cplusplus

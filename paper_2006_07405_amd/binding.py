@@ -36,6 +36,12 @@ class a2sgd_global_stats_t(C.Structure):
     _fields_ = [("gmu_pos", C.c_float), ("gmu_neg", C.c_float)]
 
 
+class a2sgd_device_info_t(C.Structure):
+    _fields_ = [("compute_units", C.c_uint32), ("memory_clock_khz", C.c_uint32), ("memory_bus_bits", C.c_uint32),
+                ("reserved", C.c_uint32), ("total_memory_bytes", C.c_uint64),
+                ("l2_bytes", C.c_uint64)]
+
+
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
@@ -70,6 +76,7 @@ def _load():
     L.a2sgd_read_segment_stats.argtypes = [vp, vp, vp, C.POINTER(a2sgd_worker_stats_t),
                                            C.POINTER(a2sgd_global_stats_t)]
     L.a2sgd_read_segment_stats.restype = C.c_int
+    L.a2sgd_device_info.argtypes = [C.POINTER(a2sgd_device_info_t)]
     L.a2sgd_status_string.argtypes = [C.c_int]
     L.a2sgd_status_string.restype = C.c_char_p
     for name in ("a2sgd_plan", "a2sgd_plan_destroy", "a2sgd_local_averages", "a2sgd_global_average",
@@ -153,6 +160,12 @@ def a2sgd_plan(n: int, num_workers: int, mode: int = A2SGD_MODE_RETAINED_ERROR, 
 
 def a2sgd_workspace_bytes(plan: Plan) -> int:
     return int(raw.a2sgd_workspace_bytes(plan.handle))
+
+
+def a2sgd_device_info() -> dict:
+    info = a2sgd_device_info_t()
+    _check(raw.a2sgd_device_info(C.byref(info)), "a2sgd_device_info")
+    return {name: getattr(info, name) for name, _ in a2sgd_device_info_t._fields_ if name != "reserved"}
 
 
 def a2sgd_plan_blocks_per_worker(plan: Plan) -> int:

@@ -689,6 +689,23 @@ a2sgd_status_t a2sgd_read_segment_stats(const a2sgd_plan_t *plan, const void *wo
     return A2SGD_OK;
 }
 
+a2sgd_status_t a2sgd_device_info(a2sgd_device_info_t *out)
+{
+    if (out == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    int device = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&device) != hipSuccess || hipGetDeviceProperties(&prop, device) != hipSuccess)
+        return A2SGD_ERR_DEVICE;
+    out->compute_units = static_cast<uint32_t>(prop.multiProcessorCount);
+    out->memory_clock_khz = static_cast<uint32_t>(prop.memoryClockRate);
+    out->memory_bus_bits = static_cast<uint32_t>(prop.memoryBusWidth);
+    out->reserved = 0;
+    out->total_memory_bytes = prop.totalGlobalMem;
+    out->l2_bytes = static_cast<uint64_t>(prop.l2CacheSize);
+    return A2SGD_OK;
+}
+
 const char *a2sgd_status_string(a2sgd_status_t status)
 {
     switch (status) {

@@ -44,6 +44,8 @@ def test_struct_layouts_match_header(A):
     assert C.sizeof(B.a2sgd_worker_stats_t) == 40
     assert C.sizeof(B.a2sgd_config_t) == 32
     assert C.sizeof(B.a2sgd_global_stats_t) == 8
+    assert C.sizeof(B.a2sgd_device_info_t) == 32
+    assert A.raw.a2sgd_device_info(None) == A.A2SGD_ERR_INVALID_ARG
 
 
 @pytest.mark.parametrize("n,P,mode,bpw", [(0, 4, 0, 0), (10, 0, 0, 0), (10, 65, 0, 0), (10, 4, 2, 0), (10, 4, -1, 0),

@@ -525,6 +525,12 @@ def test_random_shapes_against_the_oracle(A):
                 assert_array_close(wr[p].cpu().numpy(), w_ref[p], f"replica w[{p}]")
 
 
+def test_device_info(A):
+    info = A.a2sgd_device_info()
+    assert info["compute_units"] >= 64 and info["total_memory_bytes"] > 64 << 30
+    assert info["memory_bus_bits"] >= 1024 and info["memory_clock_khz"] > 100_000 and info["l2_bytes"] > 0
+
+
 def test_grid_barrier_gives_up_instead_of_hanging(A):
     """The bounded wait of the single-launch step's barrier, forced from the host on a spare cell: all workgroups
     pass a complete barrier; all give up, and exit, when one arrival is missing.  Steps still work afterwards."""
