@@ -56,7 +56,7 @@ typedef enum {
 
 typedef enum {
     /* v = fl32(g + e_old); the update applied is the global-mean vector alone; e_new = v - enc(v) is kept
-     * for the next step.  (Abstract and Sec. 3: the method "retains local errors" in a local error vector.) */
+     * for the next step.  (Abstract and Sec. 3: each worker keeps its errors in a local error vector.) */
     A2SGD_MODE_RETAINED_ERROR = 0,
     /* Algorithm 1 lines 4-7 as printed: the error is added back in the same step, update = e_new + global-mean
      * vector, which is Theorem 1's g + (net gain of the means).  e may be NULL (then v = g and no error is

@@ -17,7 +17,7 @@
  * Readings where the paper is silent or at odds with itself:
  *   - Retained-error mode (default): the vector that is encoded is v = fl32(g + e_old); the new error
  *     v - enc(v) is stored for the next step and only the global-mean vector is applied (abstract and
- *     Sec. 3: "retains local errors", error feedback through a local error vector).
+ *     Sec. 3: the local errors are kept, error feedback through a local error vector).
  *   - Algorithm-1-literal mode: the error is added back in the same step, update = error + global-mean vector
  *     (Algorithm 1 lines 4-7 as printed; this is Theorem 1's g + grad-mu form).
  *   - Empty group: its mean is 0 and enters the global average as 0.
