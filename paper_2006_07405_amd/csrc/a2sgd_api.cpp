@@ -20,15 +20,25 @@ constexpr uint32_t kReduceBlocksPerCU = 2;
 constexpr uint32_t kFusedGridMax = 256;
 
 // The apply pass runs single-wavefront workgroups and caps how many share a CU through its dynamic-LDS request
-// (160 KiB per CU; the request sits in the middle of the range that yields the wanted count).  A wavefront
-// has 2 * up + 1 float4 loads per lane in flight, so fewer wavefronts are wanted when up is larger.
+// (160 KiB per CU; the request sits in the middle of the range that yields the wanted count).  A wavefront has
+// items * (2 * up + 1) float4 loads per lane in flight, so fewer wavefronts are wanted when up is larger: the
+// product stays at 50 to 70 KiB in flight per CU.
 uint32_t apply_lds_bytes(uint32_t P)
 {
     if (P >= 16)
         return 48 * 1024;  // 3 per CU
     if (P >= 8)
         return 36 * 1024;  // 4 per CU
-    return 25 * 1024;      // 6 per CU
+    if (P >= 4)
+        return 25 * 1024;  // 6 per CU
+    return 16 * 1024;      // 10 per CU
+}
+// The dense step has items * (up + 1) loads per lane in flight (items = 2).
+uint32_t dense_lds_bytes(uint32_t P)
+{
+    if (P >= 4)
+        return apply_lds_bytes(P);
+    return P >= 2 ? 16 * 1024 : 12 * 1024;  // 10 and 13 per CU
 }
 // Above this many bytes of g + e + w the step cannot live in the 256 MiB last-level cache between its two
 // passes, and every load and store is issued as non-temporal.
@@ -251,6 +261,7 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
     pl->streaming = (2ull * pl->P + 1) * 4ull * pl->n > kStreamingBytes;
     pl->apply.up = pl->P >= 8 ? 8 : pl->P >= 4 ? 4 : pl->P >= 2 ? 2 : 1;
     pl->apply.lds_bytes = pl->streaming ? apply_lds_bytes(pl->P) : 0;
+    pl->apply.dense_lds_bytes = pl->streaming ? dense_lds_bytes(pl->P) : 0;
     // Single-launch step while everything fits the caches: one workgroup of kFusedBlock threads per 4096
     // elements, at most one per two CUs, all resident at once (the kernel's grid-wide barrier relies on that).
     pl->barrier_slot = g_next_slot.fetch_add(1) % kBarrierSlots;

@@ -83,6 +83,7 @@ namespace a2sgd {
 struct ApplyGeom {
     int up;
     uint32_t lds_bytes;
+    uint32_t dense_lds_bytes;  // the same for the dense step
 };
 }  // namespace a2sgd
 

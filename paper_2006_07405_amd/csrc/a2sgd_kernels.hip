@@ -1265,15 +1265,15 @@ static hipError_t launch_apply_shape(const a2sgd_plan_t &pl, const PtrTable &tab
                                      const WsHeader *hdr, hipStream_t s)
 {
     const ApplyGeom &ge = pl.apply;
-    // single-wavefront workgroups; about 8 float4 loads of g and as many of e in flight per thread
+    // single-wavefront workgroups; one float4 group per thread and worker (two at P = 1)
     if (ge.up == 8)
         return launch_apply_geom<MODE, HAS_E, NT, 8, 1, 1, 64>(pl, tab, w, eop, hdr, ge.lds_bytes, s);
     if (ge.up == 4)
         return launch_apply_geom<MODE, HAS_E, NT, 4, 1, 1, 64>(pl, tab, w, eop, hdr, ge.lds_bytes, s);
     if (ge.up == 2)
-        return launch_apply_geom<MODE, HAS_E, NT, 2, 2, 1, 64>(pl, tab, w, eop, hdr, ge.lds_bytes, s);
+        return launch_apply_geom<MODE, HAS_E, NT, 2, 1, 1, 64>(pl, tab, w, eop, hdr, ge.lds_bytes, s);
     if (ge.up == 1)
-        return launch_apply_geom<MODE, HAS_E, NT, 1, 4, 1, 64>(pl, tab, w, eop, hdr, ge.lds_bytes, s);
+        return launch_apply_geom<MODE, HAS_E, NT, 1, 2, 1, 64>(pl, tab, w, eop, hdr, ge.lds_bytes, s);
     return hipErrorInvalidValue;
 }
 
@@ -1535,7 +1535,7 @@ static hipError_t launch_dense_inst(const a2sgd_plan_t &pl, const PtrTable &tab,
     constexpr int kItems = 2, kThreads = 64;
     const uint64_t nvec = (pl.n + 3) >> 2, per = static_cast<uint64_t>(kThreads) * kItems;
     const dim3 grid(static_cast<uint32_t>((nvec + per - 1) / per)), block(kThreads);
-    k_dense_step<NT, UP, kItems, kThreads><<<grid, block, pl.apply.lds_bytes, s>>>(tab, w, pl.n, pl.P, eop);
+    k_dense_step<NT, UP, kItems, kThreads><<<grid, block, pl.apply.dense_lds_bytes, s>>>(tab, w, pl.n, pl.P, eop);
     return hipGetLastError();
 }
 
