@@ -486,6 +486,8 @@ a2sgd_status_t a2sgd_apply_and_update_error_replicas(const a2sgd_plan_t *plan, c
     PtrTable tab;
     ReplicaTable wt;
     fill_table(tab, plan->P, g, has_e ? e : nullptr);
+    if (plan->P == 1)  // one worker: its own replica is the shared vector, and that pass is the tuned one
+        return dev(launch_apply(*plan, tab, has_e, w[0], eta, workspace, static_cast<hipStream_t>(stream)));
     fill_replicas(wt, plan->P, w);
     return dev(launch_apply_replicas(*plan, tab, wt, has_e, eta, workspace, static_cast<hipStream_t>(stream)));
 }
