@@ -65,7 +65,7 @@ typedef enum {
 } a2sgd_mode_t;
 
 typedef struct {
-    uint64_t n;                 /* model size, 1 <= n <= 2^40 */
+    uint64_t n;                 /* model size, 1 <= n <= 2^38 */
     uint32_t num_workers;       /* P, 1 <= P <= A2SGD_MAX_WORKERS */
     int32_t mode;               /* an a2sgd_mode_t */
     uint32_t blocks_per_worker; /* 0 = let the plan choose; else the first-level reduction's grid width */

@@ -11,7 +11,9 @@ using namespace a2sgd;
 
 namespace {
 
-constexpr uint64_t kMaxN = 1ull << 40;
+// One workgroup of the apply-type passes covers as little as 64 float4 groups and a grid holds fewer than 2^31
+// workgroups: n up to 2^38 (1 TiB per buffer) keeps every grid below 2^30.
+constexpr uint64_t kMaxN = 1ull << 38;
 // Compute units of one MI355X.  Both big passes run fastest with few wavefronts per compute unit, each with
 // many 128-bit loads in flight (about 60 KiB in flight per CU); more wavefronts only widen the span of addresses
 // that is open at once and HBM efficiency drops.  The reduction keeps 2 workgroups of 256 threads per CU.
@@ -428,7 +430,7 @@ a2sgd_status_t a2sgd_read_stats(const a2sgd_plan_t *plan, const void *workspace,
 a2sgd_status_t a2sgd_export_mask(const a2sgd_plan_t *plan, const float *const *g, const float *const *e,
                                  uint64_t *mask, a2sgd_stream_t stream)
 {
-    if (plan == nullptr || plan->n > (1ull << 38))
+    if (plan == nullptr)
         return A2SGD_ERR_INVALID_ARG;
     bool has_g = false, has_e = false;
     a2sgd_status_t st = check_table(g, plan->P, true, &has_g);

@@ -49,7 +49,7 @@ def test_struct_layouts_match_header(A):
 
 
 @pytest.mark.parametrize("n,P,mode,bpw", [(0, 4, 0, 0), (10, 0, 0, 0), (10, 65, 0, 0), (10, 4, 2, 0), (10, 4, -1, 0),
-                                          ((1 << 40) + 1, 4, 0, 0), (10, 4, 0, 65537)])
+                                          ((1 << 38) + 1, 4, 0, 0), (10, 4, 0, 65537)])
 def test_plan_rejects_bad_config(A, n, P, mode, bpw):
     with pytest.raises(A.A2sgdError) as ei:
         A.a2sgd_plan(n, P, mode, bpw)
@@ -79,6 +79,9 @@ def test_plan_geometry(A):
     assert A.a2sgd_workspace_bytes(p) == -(-records // 256) * 256 + 4 * blocks * 2048 // 8
     p = A.a2sgd_plan(5, 3)
     assert A.a2sgd_plan_blocks_per_worker(p) == 1
+    p = A.a2sgd_plan(1 << 38, 64)  # the largest plan: host arithmetic only, sizes stay in 64 bits
+    assert A.a2sgd_plan_blocks_per_worker(p) == 8
+    assert A.a2sgd_workspace_bytes(p) > 64 * (1 << 38) // 8
     p = A.a2sgd_plan(1000, 2, blocks_per_worker=7)
     assert A.a2sgd_plan_blocks_per_worker(p) == 7
 
