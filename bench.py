@@ -218,9 +218,12 @@ def main() -> int:
     ev1.record()
     torch.cuda.synchronize()
     ms_lazy = ev0.elapsed_time(ev1) / 5
+    ev0.record()
     A.a2sgd_lazy_materialize(plan, e, ws)
+    ev1.record()
+    torch.cuda.synchronize()
     out["lazy_step"] = {"ms": ms_lazy, "gbps": (12.25 * n * P + 8 * n) / (ms_lazy * 1e-3) / 1e9,
-                        "params_per_s": n / (ms_lazy * 1e-3)}
+                        "params_per_s": n / (ms_lazy * 1e-3), "materialize_ms": ev0.elapsed_time(ev1)}
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, g, w, min(args.cpu_sample, n))

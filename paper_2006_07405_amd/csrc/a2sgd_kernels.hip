@@ -1155,20 +1155,40 @@ __global__ __launch_bounds__(64) void k_lazy_apply_signs(const PtrTable tab, con
     }
 }
 
-// s <- pending error of s, in place, for every worker: grid = (blocks, P), grid-stride over float4 groups.
+// s <- pending error of s, in place, for every worker: grid = (workgroups, P) of single wavefronts launched once,
+// kMaterializeItems float4 groups per thread, all loads ahead of the first store (the shape of the other passes
+// that store).
+constexpr int kMaterializeItems = 4;
 template <bool NT>
-__global__ __launch_bounds__(kBlock) void k_lazy_materialize(const PtrTable tab, const uint64_t n,
-                                                             const WsHeader *__restrict__ hdr)
+__global__ __launch_bounds__(64) void k_lazy_materialize(const PtrTable tab, const uint64_t n,
+                                                         const WsHeader *__restrict__ hdr)
 {
     const uint32_t p = blockIdx.y, tid = threadIdx.x;
+    const uint32_t lz = opaque_zero();
+    const float nmp = hdr->neg_mu_pos[p + lz], mn = hdr->mu_neg[p + lz];
     float *s = tab.e[p];
     vf4 *s4 = reinterpret_cast<vf4 *>(s);
-    const float nmp = hdr->neg_mu_pos[p], mn = hdr->mu_neg[p];
     const uint64_t nvec = n >> 2;
-    for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * kBlock + tid; i < nvec;
-         i += static_cast<uint64_t>(gridDim.x) * kBlock) {
-        const vf4 e = pending_error4(ld4<NT>(s4 + i), nmp, mn);
-        st4<NT>(s4 + i, e);
+    const uint64_t base = static_cast<uint64_t>(blockIdx.x) * (64 * kMaterializeItems) + tid;
+    if ((static_cast<uint64_t>(blockIdx.x) + 1) * (64 * kMaterializeItems) <= nvec) {
+        vf4 v[kMaterializeItems];
+#pragma unroll
+        for (int u = 0; u < kMaterializeItems; ++u)
+            v[u] = ld4<NT>(s4 + base + u * 64);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < kMaterializeItems; ++u) {
+            const vf4 e = pending_error4(v[u], nmp, mn);
+            st4<NT>(s4 + base + u * 64, e);
+        }
+    } else {
+        for (int u = 0; u < kMaterializeItems; ++u) {
+            const uint64_t i = base + static_cast<uint64_t>(u) * 64;
+            if (i < nvec) {
+                const vf4 e = pending_error4(ld4<NT>(s4 + i), nmp, mn);
+                st4<NT>(s4 + i, e);
+            }
+        }
     }
     if (blockIdx.x == 0 && tid < (n & 3)) {
         const uint64_t i = (nvec << 2) + tid;
@@ -1491,14 +1511,11 @@ hipError_t launch_lazy_apply(const a2sgd_plan_t &pl, const PtrTable &tab, float 
 
 hipError_t launch_lazy_materialize(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s)
 {
-    const uint64_t nvec = (pl.n + 3) >> 2;
-    uint64_t blocks = (nvec + kBlock - 1) / kBlock;
-    if (blocks > 2048)
-        blocks = 2048;
-    const dim3 grid(static_cast<uint32_t>(blocks), pl.P), block(kBlock);
+    const uint64_t nvec = pl.n >> 2, per = 64ull * kMaterializeItems;
+    const dim3 grid(static_cast<uint32_t>(nvec ? (nvec + per - 1) / per : 1), pl.P), block(64);
     const WsHeader *hdr = static_cast<const WsHeader *>(ws);
     if (pl.streaming)
-        k_lazy_materialize<true><<<grid, block, 0, s>>>(tab, pl.n, hdr);
+        k_lazy_materialize<true><<<grid, block, 12 * 1024, s>>>(tab, pl.n, hdr);  // 13 workgroups per CU
     else
         k_lazy_materialize<false><<<grid, block, 0, s>>>(tab, pl.n, hdr);
     hipError_t err = hipGetLastError();
