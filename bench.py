@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--single-call", action="store_true",
                     help="time a2sgd_step (one call per step; a single cooperative launch when the model fits the "
                          "caches) instead of the three calls with events between them")
+    ap.add_argument("--replicas", action="store_true",
+                    help="also time the step with one weight vector per worker (outside the timed region)")
     ap.add_argument("--hip-graph", action="store_true",
                     help="capture one step in a HIP graph and time its replays (no events inside the step)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -185,6 +187,20 @@ def main() -> int:
     ms_dense = ev0.elapsed_time(ev1) / 5
     out["dense_step"] = {"ms": ms_dense, "gbps": (4 * n * P + 8 * n) / (ms_dense * 1e-3) / 1e9,
                          "params_per_s": n / (ms_dense * 1e-3)}
+
+    if args.replicas and not plan.num_segments:
+        # Algorithm 1 line 7 as each worker runs it: 8nP bytes for the reduction, 20nP for the apply pass
+        wr = [w.clone() for _ in range(P)]
+        A.a2sgd_step_replicas(plan, g, e, wr, wl.eta, ws)
+        ev0.record()
+        for _ in range(5):
+            A.a2sgd_step_replicas(plan, g, e, wr, wl.eta, ws)
+        ev1.record()
+        torch.cuda.synchronize()
+        ms_rep = ev0.elapsed_time(ev1) / 5
+        out["replica_step"] = {"ms": ms_rep, "gbps": 28 * n * P / (ms_rep * 1e-3) / 1e9,
+                               "params_per_s": n / (ms_rep * 1e-3)}
+        del wr
 
     # A plain device-to-device copy of n floats (torch's, 8n bytes): the measured ceiling for a stream that reads
     # and writes, next to the published peak; and the peak that the device properties give.

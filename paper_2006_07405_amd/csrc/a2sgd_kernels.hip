@@ -1353,8 +1353,9 @@ static hipError_t launch_apply_replicas_shape(const a2sgd_plan_t &pl, const PtrT
     constexpr int kThreads = 64;
     const uint64_t nvec = (pl.n + 3) >> 2;
     const dim3 grid(static_cast<uint32_t>((nvec + kThreads - 1) / kThreads)), block(kThreads);
-    const uint32_t lds = pl.apply.lds_bytes;
-    // 3 loads per worker instead of 2: groups of 4 workers at most
+    // 3 loads per worker instead of 2: groups of 4 workers at most, and then 6 workgroups per CU whatever P is
+    // (the shared pass has groups of 8 for P >= 8 and caps residency lower)
+    const uint32_t lds = pl.apply.lds_bytes > 25 * 1024 ? 25 * 1024 : pl.apply.lds_bytes;
     if (pl.apply.up >= 4)
         k_apply_replicas<MODE, HAS_E, NT, 4, kThreads><<<grid, block, lds, s>>>(tab, wt, pl.n, pl.P, eta, hdr);
     else if (pl.apply.up == 2)
