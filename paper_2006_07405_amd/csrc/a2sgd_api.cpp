@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <atomic>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "a2sgd_internal.h"
@@ -79,6 +80,41 @@ void build_segments(a2sgd_plan_t &pl, uint32_t S, const uint64_t *len)
             ++s;
         sp.coarse[c] = s;
     }
+    // Which workgroup of the reduction takes which items: the items differ in size (a tensor's last item, small
+    // tensors), so they are dealt out largest first, each to the workgroup with the least work so far; a workgroup
+    // then walks its items in address order.  The result does not depend on the deal: every item has its own record.
+    const uint32_t num_items = static_cast<uint32_t>(sp.item.size());
+    sp.blocks = pl.B < num_items ? pl.B : num_items;
+    {
+        std::vector<uint32_t> order(num_items);
+        for (uint32_t i = 0; i < num_items; ++i)
+            order[i] = i;
+        std::stable_sort(order.begin(), order.end(),
+                         [&](uint32_t a, uint32_t b) { return sp.item[a].count > sp.item[b].count; });
+        std::vector<std::vector<uint32_t>> mine(sp.blocks);
+        // (load, workgroup) min-heap
+        std::vector<std::pair<uint64_t, uint32_t>> heap(sp.blocks);
+        for (uint32_t b = 0; b < sp.blocks; ++b)
+            heap[b] = {0, b};
+        auto later = [](const std::pair<uint64_t, uint32_t> &x, const std::pair<uint64_t, uint32_t> &y) { return x > y; };
+        std::make_heap(heap.begin(), heap.end(), later);
+        for (uint32_t i : order) {
+            std::pop_heap(heap.begin(), heap.end(), later);
+            auto &least = heap.back();
+            mine[least.second].push_back(i);
+            least.first += sp.item[i].count + 256;  // a fixed cost per item for its block reduction and record
+            std::push_heap(heap.begin(), heap.end(), later);
+        }
+        sp.sched_lo.assign(sp.blocks + 1, 0);
+        sp.sched_item.clear();
+        sp.sched_item.reserve(num_items);
+        for (uint32_t b = 0; b < sp.blocks; ++b) {
+            std::sort(mine[b].begin(), mine[b].end());
+            sp.sched_lo[b] = static_cast<uint32_t>(sp.sched_item.size());
+            sp.sched_item.insert(sp.sched_item.end(), mine[b].begin(), mine[b].end());
+        }
+        sp.sched_lo[sp.blocks] = static_cast<uint32_t>(sp.sched_item.size());
+    }
     size_t o = pl.workspace_bytes;  // after the header and the whole-model partials region
     o = align_up(o, 256);
     sp.off_seg_end = o;
@@ -89,6 +125,10 @@ void build_segments(a2sgd_plan_t &pl, uint32_t S, const uint64_t *len)
     o = align_up(o + 4ull * (S + 1), 256);
     sp.off_coarse = o;
     o = align_up(o + 4ull * chunks, 256);
+    sp.off_sched_lo = o;
+    o = align_up(o + 4ull * (sp.blocks + 1), 256);
+    sp.off_sched_item = o;
+    o = align_up(o + 4ull * num_items, 256);
     sp.off_stats = o;
     o = align_up(o + sizeof(a2sgd_worker_stats_t) * pl.P * S, 256);
     sp.off_nmp = o;
@@ -667,7 +707,9 @@ a2sgd_status_t a2sgd_workspace_init(const a2sgd_plan_t *plan, void *workspace, a
     } parts[] = {{sp.off_seg_end, sp.seg_end.data(), 8ull * sp.seg_end.size()},
                  {sp.off_item, sp.item.data(), sizeof(SegItem) * sp.item.size()},
                  {sp.off_item_lo, sp.item_lo.data(), 4ull * sp.item_lo.size()},
-                 {sp.off_coarse, sp.coarse.data(), 4ull * sp.coarse.size()}};
+                 {sp.off_coarse, sp.coarse.data(), 4ull * sp.coarse.size()},
+                 {sp.off_sched_lo, sp.sched_lo.data(), 4ull * sp.sched_lo.size()},
+                 {sp.off_sched_item, sp.sched_item.data(), 4ull * sp.sched_item.size()}};
     for (const auto &part : parts)
         if (hipMemcpyAsync(b + part.off, part.src, part.bytes, hipMemcpyHostToDevice, s) != hipSuccess)
             return A2SGD_ERR_DEVICE;

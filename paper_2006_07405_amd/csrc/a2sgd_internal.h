@@ -107,6 +107,8 @@ struct SegView {
     const SegItem *item;       // [num_items], ascending start
     const uint32_t *item_lo;   // [S + 1]: items of segment s are item_lo[s] .. item_lo[s + 1] - 1
     const uint32_t *coarse;    // [ceil(n / 2^8)]: segment of element k * 2^8
+    const uint32_t *sched_lo;  // [blocks + 1]: workgroup b of the reduction takes sched_item[sched_lo[b] .. sched_lo[b + 1])
+    const uint32_t *sched_item;  // [num_items]
     a2sgd_worker_stats_t *stats;  // [P][S]
     float *neg_mu_pos, *mu_neg;   // [S][P], packed for the apply pass
     float *gmu;                   // [S][2]: gmu_pos, -gmu_neg
@@ -119,9 +121,11 @@ struct SegPlan {
     std::vector<uint64_t> seg_end;
     std::vector<SegItem> item;
     std::vector<uint32_t> item_lo, coarse;
+    uint32_t blocks = 0;  // workgroups per worker of the reduction
+    std::vector<uint32_t> sched_lo, sched_item;
     // byte offsets into the workspace
-    size_t off_seg_end = 0, off_item = 0, off_item_lo = 0, off_coarse = 0, off_stats = 0, off_nmp = 0, off_mn = 0,
-           off_gmu = 0, off_records = 0, end = 0;
+    size_t off_seg_end = 0, off_item = 0, off_item_lo = 0, off_coarse = 0, off_sched_lo = 0, off_sched_item = 0,
+           off_stats = 0, off_nmp = 0, off_mn = 0, off_gmu = 0, off_records = 0, end = 0;
 };
 
 }  // namespace a2sgd

@@ -24,6 +24,8 @@ SegView seg_view(const a2sgd_plan_t &pl, void *ws)
     v.item = reinterpret_cast<const SegItem *>(b + sp.off_item);
     v.item_lo = reinterpret_cast<const uint32_t *>(b + sp.off_item_lo);
     v.coarse = reinterpret_cast<const uint32_t *>(b + sp.off_coarse);
+    v.sched_lo = reinterpret_cast<const uint32_t *>(b + sp.off_sched_lo);
+    v.sched_item = reinterpret_cast<const uint32_t *>(b + sp.off_sched_item);
     v.stats = reinterpret_cast<a2sgd_worker_stats_t *>(b + sp.off_stats);
     v.neg_mu_pos = reinterpret_cast<float *>(b + sp.off_nmp);
     v.mu_neg = reinterpret_cast<float *>(b + sp.off_mn);
@@ -38,13 +40,13 @@ SegView seg_view(const a2sgd_plan_t &pl, void *ws)
 
 // ---------------------------------------------------------------------------------------------------------
 // Reduction, first level (Algorithm 1 line 3 per tensor).  grid = (B, P); block b of worker p takes the items
-// b, b + B, ...  An item starts and ends anywhere: elements up to the first 16-byte boundary and after the
+// that the plan's schedule gives it (about equal work per block).  An item starts and ends anywhere: elements up to the first 16-byte boundary and after the
 // last one are taken one per thread, the float4 groups in between kSegUnroll per thread per trip.
 // ---------------------------------------------------------------------------------------------------------
 constexpr int kSegUnroll = 4;
 
 template <bool HAS_E, bool NT>
-__global__ __launch_bounds__(kBlock) void k_seg_partials(const PtrTable tab, const uint32_t B, const SegView sv)
+__global__ __launch_bounds__(kBlock) void k_seg_partials(const PtrTable tab, const SegView sv)
 {
     const uint32_t p = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *__restrict__ g = tab.g[p];
@@ -53,7 +55,9 @@ __global__ __launch_bounds__(kBlock) void k_seg_partials(const PtrTable tab, con
     __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
     __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
 
-    for (uint32_t it = blockIdx.x; it < sv.num_items; it += B) {
+    const uint32_t k_end = sv.sched_lo[blockIdx.x + 1];
+    for (uint32_t k = sv.sched_lo[blockIdx.x]; k < k_end; ++k) {
+        const uint32_t it = sv.sched_item[k];
         const SegItem item = sv.item[it];
         const uint64_t lo = item.start, hi = item.start + item.count;
         uint64_t a = (lo + 3) & ~static_cast<uint64_t>(3);  // first element on a 16-byte boundary
@@ -320,20 +324,17 @@ __global__ __launch_bounds__(BLOCK) void k_seg_apply(const PtrTable tab, float *
 hipError_t launch_seg_partials(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, void *ws, hipStream_t s)
 {
     const SegView sv = seg_view(pl, ws);
-    uint32_t B = pl.B;
-    if (B > sv.num_items)
-        B = sv.num_items;
-    const dim3 grid(B, pl.P), block(kBlock);
+    const dim3 grid(pl.seg.blocks, pl.P), block(kBlock);
     if (has_e) {
         if (pl.streaming)
-            k_seg_partials<true, true><<<grid, block, 0, s>>>(tab, B, sv);
+            k_seg_partials<true, true><<<grid, block, 0, s>>>(tab, sv);
         else
-            k_seg_partials<true, false><<<grid, block, 0, s>>>(tab, B, sv);
+            k_seg_partials<true, false><<<grid, block, 0, s>>>(tab, sv);
     } else {
         if (pl.streaming)
-            k_seg_partials<false, true><<<grid, block, 0, s>>>(tab, B, sv);
+            k_seg_partials<false, true><<<grid, block, 0, s>>>(tab, sv);
         else
-            k_seg_partials<false, false><<<grid, block, 0, s>>>(tab, B, sv);
+            k_seg_partials<false, false><<<grid, block, 0, s>>>(tab, sv);
     }
     return hipGetLastError();
 }
@@ -360,8 +361,11 @@ static hipError_t launch_seg_apply_shape(const a2sgd_plan_t &pl, const PtrTable 
     const uint64_t nvec = (pl.n + 3) >> 2;
     const dim3 grid(static_cast<uint32_t>((nvec + kThreads - 1) / kThreads)), block(kThreads);
     // The segment lookup sits between a workgroup's big loads and its arithmetic and makes it live longer, so more
-    // workgroups per CU are wanted than in k_apply for the same bytes in flight (measured: 10 instead of 6 at P = 4).
-    const uint32_t lds = pl.apply.lds_bytes * 5 / 8;
+    // workgroups per CU are wanted than in k_apply for the same bytes in flight (measured best: 11 instead of 6 at
+    // P = 4, 11 instead of 4 at P = 8, 8 instead of 3 at P = 16).
+    uint32_t lds = 0;
+    if (pl.streaming)
+        lds = pl.P >= 16 ? 20 * 1024 : pl.P >= 4 ? 14 * 1024 : 10 * 1024;
     if (pl.apply.up == 8)
         k_seg_apply<MODE, HAS_E, NT, 8, kThreads><<<grid, block, lds, s>>>(tab, w, pl.n, pl.P, eop, sv);
     else
