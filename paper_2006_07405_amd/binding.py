@@ -108,6 +108,7 @@ class Plan:
     def __init__(self, handle: int, n: int, num_workers: int, mode: int, num_segments: int = 0):
         self.handle, self.n, self.num_workers, self.mode = handle, n, num_workers, mode
         self.num_segments = num_segments
+        self.workspace_bytes = int(raw.a2sgd_workspace_bytes(handle))  # fixed by the plan
 
     def __del__(self):
         if getattr(self, "handle", None):
@@ -139,7 +140,7 @@ def _table(plan: Plan, ts: Optional[Sequence[torch.Tensor]], what: str):
 
 
 def _workspace(plan: Plan, ws: torch.Tensor) -> int:
-    need = a2sgd_workspace_bytes(plan)
+    need = plan.workspace_bytes
     if not (isinstance(ws, torch.Tensor) and ws.is_cuda and ws.is_contiguous()):
         raise TypeError("workspace: expected a contiguous CUDA tensor")
     if ws.numel() * ws.element_size() < need:
