@@ -14,15 +14,17 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def asm():
     from paper_2006_07405_amd import build as B
     flags = [f for f in B.FLAGS if f not in ("-shared", "-fPIC")]
+    text = ""
     with tempfile.TemporaryDirectory() as d:
-        out = os.path.join(d, "k.s")
-        subprocess.check_call(["/opt/rocm/bin/hipcc"] + flags + ["--cuda-device-only", "-S", "-o", out, B.SOURCES[0]],
-                              stderr=subprocess.DEVNULL)
-        text = open(out).read()
+        for k, src in enumerate(x for x in B.SOURCES if x.endswith(".hip")):
+            out = os.path.join(d, f"k{k}.s")
+            subprocess.check_call(["/opt/rocm/bin/hipcc"] + flags + ["--cuda-device-only", "-S", "-o", out, src],
+                                  stderr=subprocess.DEVNULL)
+            text += open(out).read()
     kernels = {}
     for m in re.finditer(r"^(_ZN5a2sgd\w+):.*?s_endpgm", text, flags=re.S | re.M):
         kernels[m.group(1)] = m.group(0)
-    assert kernels
+    assert any("k_seg_apply" in k for k in kernels) and any("k_apply" in k for k in kernels)
     return text, kernels
 
 
@@ -48,6 +50,27 @@ def test_streaming_apply_stores_are_all_write_through_non_temporal(asm):
         for k, l in enumerate(lines):
             if l.startswith("global_store_dwordx4") and l.endswith(" sc1 nt"):
                 assert lines[k + 1].startswith("s_nop 1"), f"{name}: store without its wait states"
+
+
+def test_every_hand_written_store_has_its_wait_states(asm):
+    """All kernels of both files: the 128-bit store spelled in assembly must be followed by its two wait states, and
+    the streaming instantiations of every pass that stores (NT = true: Lb1 among the template arguments) use it."""
+    _, kernels = asm
+    seen = 0
+    for name, body in kernels.items():
+        lines = [l.strip() for l in body.splitlines() if l.strip() and not l.strip().startswith(";")]
+        for k, l in enumerate(lines):
+            if l.startswith("global_store_dwordx4") and l.endswith(" sc1 nt"):
+                seen += 1
+                assert lines[k + 1].startswith("s_nop 1"), f"{name}: store without its wait states"
+    assert seen > 100
+    for pat in (r"_ZN5a2sgd15k_lazy_partialsILb1E", r"_ZN5a2sgd18k_lazy_materializeILb1E", r"_ZN5a2sgd18k_lazy_apply_signsILb1E",
+                r"_ZN5a2sgd12k_dense_stepILb1E", r"_ZN5a2sgd11k_seg_applyILi[01]ELb[01]ELb1E"):
+        names = [k for k in kernels if re.match(pat, k)]
+        assert names, pat
+        for name in names:
+            stores = re.findall(r"global_store_dwordx4[^\n]*", kernels[name])
+            assert stores and all(x.rstrip().endswith(" sc1 nt") for x in stores), name
 
 
 def test_streaming_reduction_loads_are_non_temporal_and_batched(asm):
