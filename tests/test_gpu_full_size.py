@@ -109,3 +109,61 @@ def test_full_size_config(A, k, lazy):
         bound = 4.0 * n * max(stats[p].mu_pos, stats[p].mu_neg) * 2.0 ** -24
         assert abs(total) <= bound, f"config {k} worker {p}: sum of new errors {total:.3e} exceeds {bound:.3e}"
     print(f"  total {time.time() - t0:.1f}s", flush=True)
+
+
+def oracle_step_threaded(g, e, w, eta, chunk=1 << 22, threads=16):
+    """One whole oracle step on host arrays, the oracle's own calls spread over host threads: one accumulator per
+    worker fed in index order, then the elementwise pass chunk by chunk.  Returns (stats, gmu, e_new, w_new)."""
+    P, n = len(g), int(w.shape[0])
+
+    def pass_a(p):
+        acc = O.LocalAccumulator()
+        for lo in range(0, n, chunk):
+            acc.feed(g[p][lo:lo + chunk], e[p][lo:lo + chunk])
+        return acc.stats()
+
+    e_new = [np.empty(n, f32) for _ in range(P)]
+    w_new = np.empty(n, f32)
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        stats = list(pool.map(pass_a, range(P)))
+        gp, gn = O.global_means(stats)
+
+        def pass_b(lo):
+            hi = min(n, lo + chunk)
+            en, wn, _ = O.apply_chunk([x[lo:hi] for x in g], [x[lo:hi] for x in e], w[lo:hi], stats, gp, gn, eta,
+                                      O.RETAINED_ERROR)
+            for p in range(P):
+                e_new[p][lo:hi] = en[p]
+            w_new[lo:hi] = wn
+
+        list(pool.map(pass_b, range(0, n, chunk)))
+    return stats, (gp, gn), e_new, w_new
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_full_size_four_steps_free_running(A, k):
+    """Four steps at full size with fresh gradients, each side carrying its own error and weights from e = 0 (the
+    workload's start): counts equal and means within tolerance at every step, every element of e and w within
+    tolerance at the end."""
+    t0 = time.time()
+    wl = workloads.FULL[k]()
+    n, P = wl.n, wl.num_workers
+    e_d = [torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(P)]
+    w_d = wl.weights(device="cuda")
+    e_o = [np.zeros(n, f32) for _ in range(P)]
+    w_o = w_d.cpu().numpy()
+    plan = A.a2sgd_plan(n, P, 0)
+    ws = A.alloc_workspace(plan)
+    g_d = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(P)]
+    for t in range(4):
+        for p in range(P):
+            wl.gradient(p, t, out=g_d[p])
+        g_h = [x.cpu().numpy() for x in g_d]
+        A.a2sgd_step(plan, g_d, e_d, w_d, wl.eta, ws)
+        stats, gmu = A.a2sgd_read_stats(plan, ws)
+        stats_ref, gmu_ref, e_o, w_o = oracle_step_threaded(g_h, e_o, w_o, wl.eta)
+        compare_stats(stats, gmu, O.StepResult(stats_ref, gmu_ref[0], gmu_ref[1], [], np.empty(0, f32), []))
+        print(f"  config {k} step {t}: counts equal, {time.time() - t0:.1f}s", flush=True)
+    for p in range(P):
+        assert_array_close(e_d[p].cpu().numpy(), e_o[p], f"config {k} e[{p}] after 4 steps")
+    assert_array_close(w_d.cpu().numpy(), w_o, f"config {k} w after 4 steps")
