@@ -525,6 +525,44 @@ def test_random_shapes_against_the_oracle(A):
                 assert_array_close(wr[p].cpu().numpy(), w_ref[p], f"replica w[{p}]")
 
 
+def test_buffers_at_the_minimum_alignment(A):
+    """g, e and w as views that start 16 bytes (and for one buffer 48 bytes) into larger allocations: 16 bytes is
+    all the interface asks for.  Eager three calls, single launch, lazy step."""
+    n, P = 70_003, 3
+    g, e, w = make_case(5, n, P)
+    ref = O.step(g, e, w, 0.1, 0)
+
+    def view(a, off):
+        big = torch.zeros(n + 64, dtype=torch.float32, device="cuda")
+        v = big[off:off + n]
+        v.copy_(torch.from_numpy(a))
+        assert v.data_ptr() % 16 == 0 and v.data_ptr() % 64 != 0
+        return v
+
+    for path in ("three", "step", "lazy"):
+        gd = [view(x, 4) for x in g]
+        ed = [view(x, 12 if p == 1 else 4) for p, x in enumerate(e)]
+        wd = view(w, 4)
+        plan = A.a2sgd_plan(n, P, 0)
+        ws_big = torch.zeros(A.a2sgd_workspace_bytes(plan) // 8 + 8, dtype=torch.int64, device="cuda")
+        ws = ws_big[2:]  # 16 bytes in
+        if path == "three":
+            A.a2sgd_local_averages(plan, gd, ed, ws)
+            A.a2sgd_global_average(plan, ws)
+            A.a2sgd_apply_and_update_error(plan, gd, ed, wd, 0.1, ws)
+        elif path == "step":
+            A.a2sgd_step(plan, gd, ed, wd, 0.1, ws)
+        else:
+            A.a2sgd_lazy_reset(plan, ws)
+            A.a2sgd_lazy_step(plan, gd, ed, wd, 0.1, ws)
+            A.a2sgd_lazy_materialize(plan, ed, ws)
+        stats, gmu = A.a2sgd_read_stats(plan, ws)
+        compare_stats(stats, gmu, ref)
+        assert_array_close(wd.cpu().numpy(), ref.w_new, f"{path}: w")
+        for p in range(P):
+            assert_array_close(ed[p].cpu().numpy(), ref.e_new[p], f"{path}: e[{p}]")
+
+
 def test_device_info(A):
     info = A.a2sgd_device_info()
     assert info["compute_units"] >= 64 and info["total_memory_bytes"] > 64 << 30
