@@ -491,56 +491,36 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused_step(const PtrTable tab, 
         return;
     }
 
-    // ---- phase 2: every workgroup combines the G records of each worker, all in the same order
-    for (uint32_t p = 0; p < P; ++p) {
+    // ---- phase 2: every workgroup combines the G records of each worker, all in the same order: one wavefront
+    // per worker (wavefront k takes workers k, k + 8, ...), records strided over its lanes, then the shuffle tree
+    for (uint32_t p = wave; p < P; p += kFusedBlock / 64) {
         const size_t row = static_cast<size_t>(p) * G;
         double sp = 0.0, sn = 0.0;
         uint64_t cp = 0, cn = 0, cz = 0;
-        for (uint32_t j = tid; j < G; j += kFusedBlock) {
+        for (uint32_t j = lane; j < G; j += 64) {
             sp += load_device(part.s_pos + row + j);
             sn += load_device(part.s_neg + row + j);
             cp += load_device(part.n_pos + row + j);
             cn += load_device(part.n_neg + row + j);
             cz += load_device(part.n_zero + row + j);
         }
-        sp = wave_sum(sp);
-        sn = wave_sum(sn);
-        cp = wave_sum(cp);
-        cn = wave_sum(cn);
-        cz = wave_sum(cz);
+        const double tp = wave_sum(sp), tn = wave_sum(sn);
+        const uint64_t np = wave_sum(cp), nn = wave_sum(cn), nz = wave_sum(cz);
         if (lane == 0) {
-            sh_pos[p][wave] = sp;
-            sh_neg[p][wave] = sn;
-            sh_cp[p][wave] = cp;
-            sh_cn[p][wave] = cn;
-            sh_cz[p][wave] = cz;
-        }
-    }
-    __syncthreads();
-    if (tid < P) {
-        double tp = 0.0, tn = 0.0;
-        uint64_t np = 0, nn = 0, nz = 0;
-#pragma unroll
-        for (int k = 0; k < kFusedBlock / 64; ++k) {
-            tp += sh_pos[tid][k];
-            tn += sh_neg[tid][k];
-            np += sh_cp[tid][k];
-            nn += sh_cn[tid][k];
-            nz += sh_cz[tid][k];
-        }
-        a2sgd_worker_stats_t st;
-        st.mu_pos = np ? static_cast<float>(tp / static_cast<double>(np)) : 0.0f;
-        st.mu_neg = nn ? static_cast<float>(tn / static_cast<double>(nn)) : 0.0f;
-        st.n_pos = np;
-        st.n_neg = nn;
-        st.n_zero = nz;
-        st.n_nan = n - np - nn;
-        s_neg_mu_pos[tid] = -st.mu_pos;
-        s_mu_neg[tid] = st.mu_neg;
-        if (b == 0) {
-            hdr->workers[tid] = st;
-            hdr->neg_mu_pos[tid] = -st.mu_pos;
-            hdr->mu_neg[tid] = st.mu_neg;
+            a2sgd_worker_stats_t st;
+            st.mu_pos = np ? static_cast<float>(tp / static_cast<double>(np)) : 0.0f;
+            st.mu_neg = nn ? static_cast<float>(tn / static_cast<double>(nn)) : 0.0f;
+            st.n_pos = np;
+            st.n_neg = nn;
+            st.n_zero = nz;
+            st.n_nan = n - np - nn;
+            s_neg_mu_pos[p] = -st.mu_pos;
+            s_mu_neg[p] = st.mu_neg;
+            if (b == 0) {
+                hdr->workers[p] = st;
+                hdr->neg_mu_pos[p] = -st.mu_pos;
+                hdr->mu_neg[p] = st.mu_neg;
+            }
         }
     }
     __syncthreads();
