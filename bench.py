@@ -40,6 +40,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-tensor", action="store_true",
                     help="one pair of means per worker and tensor of the workload's layout instead of per worker")
+    ap.add_argument("--pooled", action="store_true",
+                    help="with --per-tensor: the plan knows the tensors but every worker has one pair of means over all "
+                         "of them together (the whole-model method on the tensor path)")
     ap.add_argument("--single-call", action="store_true",
                     help="time a2sgd_step (one call per step; a single cooperative launch when the model fits the "
                          "caches) instead of the three calls with events between them")
@@ -75,7 +78,8 @@ def main() -> int:
         wl.gradient(p, 0, out=g[p])
     wl.weights(out=w)
     seg = [numel for _, numel in wl.tensors] if args.per_tensor else None
-    plan = A.a2sgd_plan(n, P, A.A2SGD_MODE_RETAINED_ERROR, args.blocks_per_worker, seg_lengths=seg)
+    plan = A.a2sgd_plan(n, P, A.A2SGD_MODE_RETAINED_ERROR, args.blocks_per_worker, seg_lengths=seg,
+                        pooled_means=bool(seg) and args.pooled)
     ws = A.alloc_workspace(plan)
 
     def step(ev=None):
@@ -158,7 +162,7 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"config{args.config}:{wl.name}", "n": n, "num_workers": P, "seed": wl.seed,
-                   "recipe": wl.recipe, "mode": "retained_error", "eta": wl.eta, "per_tensor_means": plan.num_segments,
+                   "recipe": wl.recipe, "mode": "retained_error", "eta": wl.eta, "per_tensor_means": plan.num_segments, "pooled_means": bool(seg) and args.pooled,
                    "blocks_per_worker": A.a2sgd_plan_blocks_per_worker(plan),
                    "launch": ("one_call" if args.single_call else "three_calls") + ("+hip_graph_replay" if args.hip_graph else "")},
         "ms_per_step_median_events": ms_median,

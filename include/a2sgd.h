@@ -69,10 +69,19 @@ typedef struct {
     uint32_t num_workers;       /* P, 1 <= P <= A2SGD_MAX_WORKERS */
     int32_t mode;               /* an a2sgd_mode_t */
     uint32_t blocks_per_worker; /* 0 = let the plan choose; else the first-level reduction's grid width */
-    uint32_t num_segments;      /* 0 or 1: one pair of means per worker over the whole model (the paper's method);
-                                   S > 1: per-tensor means, see below.  At most 2^20. */
-    const uint64_t *seg_length; /* HOST array of num_segments tensor sizes (each >= 1) in packing order, summing to
-                                   n; read during a2sgd_plan only; ignored (may be NULL) when num_segments <= 1 */
+    uint32_t num_segments;      /* 0: the whole range [0, n) is the model (the paper's method, one pair of means per
+                                   worker).  S >= 1: the model consists of S tensors (segments) inside [0, n), see
+                                   "Tensors" below.  At most 2^20. */
+    const uint64_t *seg_length; /* HOST array of num_segments tensor sizes (each >= 1) in ascending address order; read
+                                   during a2sgd_plan only; ignored (may be NULL) when num_segments is 0 */
+    const uint64_t *seg_offset; /* HOST array of num_segments start indices, or NULL: the tensors are packed back to
+                                   back from 0 and their sizes sum to n.  With offsets the tensors must not overlap
+                                   and must end by n; elements outside every tensor are padding: neither counted nor
+                                   read for the means nor written */
+    uint32_t pooled_means;      /* with num_segments >= 1: 0 = one pair of means per worker and tensor; 1 = one pair
+                                   per worker over all tensors together (the paper's whole-model means on a buffer
+                                   that has padding).  Must be 0 when num_segments is 0 */
+    uint32_t reserved;          /* 0 */
 } a2sgd_config_t;
 
 /* Per-worker result of the reduction (Sec. 3.1; the pair (mu_pos, mu_neg) is the worker's 64-bit message of
@@ -144,17 +153,20 @@ a2sgd_status_t a2sgd_export_mask(const a2sgd_plan_t *plan, const float *const *g
 a2sgd_status_t a2sgd_dense_step(const a2sgd_plan_t *plan, const float *const *g, float *w, float eta,
                                 a2sgd_stream_t stream);
 
-/* ---- Per-tensor means -----------------------------------------------------------------------------------------
- * A plan made with num_segments = S > 1 applies the operator of Eq. 2 and Algorithm 1 lines 3-7 to every tensor
- * (segment) of the flat gradient on its own: worker p has one pair of local means per tensor, the global means
- * are averaged over the workers per tensor, and each element is encoded with the means of its tensor (2S scalars
- * per worker and step instead of 2).  a2sgd_local_averages, a2sgd_global_average, a2sgd_apply_and_update_error
- * and a2sgd_step work as described above, per tensor; a2sgd_dense_step and a2sgd_export_mask do not depend on
- * the segments.  Not available on such a plan (A2SGD_ERR_INVALID_ARG): a2sgd_read_stats, the replica calls and
- * the lazy calls.  The workspace of such a plan holds static lookup tables: */
+/* ---- Tensors: per-tensor means, and buffers with padding -------------------------------------------------------
+ * A plan made with num_segments = S >= 1 treats the flat buffers as S tensors (segments).  With pooled_means = 0 it
+ * applies the operator of Eq. 2 and Algorithm 1 lines 3-7 to every tensor on its own: worker p has one pair of
+ * local means per tensor, the global means are averaged over the workers per tensor, and each element is encoded
+ * with the means of its tensor (2S scalars per worker and step instead of 2).  With pooled_means = 1 every worker
+ * has one pair of means over all its tensors together, as in the paper, and the tensors only say which elements of
+ * the buffers belong to the model.  Elements outside every tensor (possible with seg_offset) are left alone by every
+ * call except a2sgd_dense_step and a2sgd_export_mask, which do not depend on the segments.
+ * a2sgd_local_averages, a2sgd_global_average, a2sgd_apply_and_update_error and a2sgd_step work as described above.
+ * Not available on such a plan (A2SGD_ERR_INVALID_ARG): the replica calls and the lazy calls, and a2sgd_read_stats
+ * unless the means are pooled.  The workspace of such a plan holds static lookup tables: */
 
 /* Uploads the plan's segment tables into the workspace.  Required once per workspace, before its first use, when
- * the plan has num_segments > 1; a no-op otherwise.  Asynchronous on `stream`; the plan must outlive the copy. */
+ * the plan has num_segments >= 1; a no-op otherwise.  Asynchronous on `stream`; the plan must outlive the copy. */
 a2sgd_status_t a2sgd_workspace_init(const a2sgd_plan_t *plan, void *workspace, a2sgd_stream_t stream);
 
 /* Per-tensor results of the last completed reduction: out_workers[p * S + s] for worker p and tensor s (host array

@@ -262,25 +262,47 @@ def replica_drift(w: Sequence[np.ndarray]):
 
 
 def step_segmented(g: Sequence[np.ndarray], e: Optional[Sequence[Optional[np.ndarray]]], w: np.ndarray, eta: float,
-                   mode: int, seg_lengths: Sequence[int]):
-    """Per-tensor variant: the whole-model step applied to each tensor on its own, i.e. one pair of local means per
-    worker AND tensor, averaged over the workers per tensor (the paper's operator of Eq. 2 and Algorithm 1 lines
-    3-7 with v restricted to one tensor).  seg_lengths are the tensor sizes in packing order; they cover [0, n).
-    Returns (list of StepResult per tensor, e_new list, w_new)."""
+                   mode: int, seg_lengths: Sequence[int], seg_offsets: Optional[Sequence[int]] = None,
+                   pooled: bool = False):
+    """The step on buffers that consist of tensors (and possibly padding between them).
+
+    pooled = False: the whole-model step applied to each tensor on its own, i.e. one pair of local means per worker
+    AND tensor, averaged over the workers per tensor (the paper's operator of Eq. 2 and Algorithm 1 lines 3-7 with v
+    restricted to one tensor).  pooled = True: the whole-model step applied to the tensors laid end to end, i.e.
+    the paper's method on the model that the buffers hold, padding left out.  seg_lengths are the tensor sizes in
+    address order, seg_offsets their start indices (None: packed back to back from 0, covering [0, n)).  Elements
+    outside every tensor come back unchanged.  Returns (list of StepResult per tensor, or one-element list when
+    pooled; e_new list; w_new)."""
     P = len(g)
     n = int(np.asarray(w).shape[0])
-    assert sum(int(x) for x in seg_lengths) == n and all(int(x) > 0 for x in seg_lengths)
-    e_new = [np.empty(n, dtype=np.float32) for _ in range(P)]
-    w_new = np.empty(n, dtype=np.float32)
+    lengths = [int(x) for x in seg_lengths]
+    if seg_offsets is None:
+        offsets = [int(x) for x in np.concatenate([[0], np.cumsum(lengths)[:-1]])]
+        assert sum(lengths) == n
+    else:
+        offsets = [int(x) for x in seg_offsets]
+    assert all(x > 0 for x in lengths) and all(offsets[k] + lengths[k] <= (offsets[k + 1] if k + 1 < len(offsets) else n)
+                                              for k in range(len(offsets)))
+    e_new = [np.array(x, dtype=np.float32, copy=True) if x is not None else np.zeros(n, np.float32) for x in e] \
+        if e is not None else [np.zeros(n, np.float32) for _ in range(P)]
+    w_new = np.array(w, dtype=np.float32, copy=True)
+    ranges = [(o, o + l) for o, l in zip(offsets, lengths)]
+    if pooled:
+        cat = lambda x: np.concatenate([x[lo:hi] for lo, hi in ranges])
+        r = step([cat(x) for x in g], [cat(x) for x in e] if e is not None else None, cat(w), eta, mode)
+        pos = 0
+        for lo, hi in ranges:
+            for p in range(P):
+                e_new[p][lo:hi] = r.e_new[p][pos:pos + hi - lo]
+            w_new[lo:hi] = r.w_new[pos:pos + hi - lo]
+            pos += hi - lo
+        return [r], e_new, w_new
     per_seg = []
-    off = 0
-    for length in seg_lengths:
-        lo, hi = off, off + int(length)
+    for lo, hi in ranges:
         es = [x[lo:hi] for x in e] if e is not None else None
         r = step([x[lo:hi] for x in g], es, w[lo:hi], eta, mode)
         for p in range(P):
             e_new[p][lo:hi] = r.e_new[p]
         w_new[lo:hi] = r.w_new
         per_seg.append(r)
-        off = hi
     return per_seg, e_new, w_new

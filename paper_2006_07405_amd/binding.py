@@ -24,7 +24,8 @@ A2SGD_MODE_RETAINED_ERROR, A2SGD_MODE_ALG1_LITERAL = 0, 1
 class a2sgd_config_t(C.Structure):
     _fields_ = [("n", C.c_uint64), ("num_workers", C.c_uint32), ("mode", C.c_int32),
                 ("blocks_per_worker", C.c_uint32), ("num_segments", C.c_uint32),
-                ("seg_length", C.POINTER(C.c_uint64))]
+                ("seg_length", C.POINTER(C.c_uint64)), ("seg_offset", C.POINTER(C.c_uint64)),
+                ("pooled_means", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class a2sgd_worker_stats_t(C.Structure):
@@ -149,14 +150,20 @@ def _workspace(plan: Plan, ws: torch.Tensor) -> int:
 
 
 def a2sgd_plan(n: int, num_workers: int, mode: int = A2SGD_MODE_RETAINED_ERROR, blocks_per_worker: int = 0,
-               seg_lengths: Optional[Sequence[int]] = None) -> Plan:
-    """seg_lengths: tensor sizes in packing order (summing to n) for per-tensor means; None = whole-model means."""
+               seg_lengths: Optional[Sequence[int]] = None, seg_offsets: Optional[Sequence[int]] = None,
+               pooled_means: bool = False) -> Plan:
+    """seg_lengths: tensor sizes in address order; None = the whole range [0, n) with whole-model means.
+    seg_offsets: their start indices (None = packed back to back from 0, sizes summing to n); elements outside every
+    tensor are padding.  pooled_means: one pair of means per worker over all tensors instead of one per tensor."""
     S = len(seg_lengths) if seg_lengths is not None else 0
     arr = (C.c_uint64 * S)(*[int(x) for x in seg_lengths]) if S else None
-    cfg = a2sgd_config_t(n, num_workers, mode, blocks_per_worker, S, arr)
+    if seg_offsets is not None and len(seg_offsets) != S:
+        raise ValueError("seg_offsets: one start index per tensor")
+    off = (C.c_uint64 * S)(*[int(x) for x in seg_offsets]) if (S and seg_offsets is not None) else None
+    cfg = a2sgd_config_t(n, num_workers, mode, blocks_per_worker, S, arr, off, 1 if pooled_means else 0, 0)
     h = C.c_void_p()
     _check(raw.a2sgd_plan(C.byref(cfg), C.byref(h)), "a2sgd_plan")
-    return Plan(h.value, n, num_workers, mode, S if S > 1 else 0)
+    return Plan(h.value, n, num_workers, mode, S)
 
 
 def a2sgd_workspace_bytes(plan: Plan) -> int:

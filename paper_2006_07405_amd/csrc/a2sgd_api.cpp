@@ -54,31 +54,43 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // Static tables of a per-tensor plan: segment ends, work items of at most kSegItemElems elements that stay
 // inside one segment, the items of each segment, a coarse element -> segment lookup; and where all of that, the
 // per-segment results and the partial records live in the workspace.
-void build_segments(a2sgd_plan_t &pl, uint32_t S, const uint64_t *len)
+void build_segments(a2sgd_plan_t &pl, uint32_t S, const uint64_t *len, const uint64_t *start, bool pooled)
 {
     SegPlan &sp = pl.seg;
     sp.S = S;
-    sp.seg_end.resize(S);
+    sp.pooled = pooled;
+    sp.seg_start.resize(S + 1);
+    sp.seg_end.resize(S + 1);
     sp.item_lo.resize(S + 1);
-    uint64_t off = 0;
+    uint64_t packed = 0;
+    sp.covered = 0;
     for (uint32_t s = 0; s < S; ++s) {
+        const uint64_t off = start ? start[s] : packed;
         sp.item_lo[s] = static_cast<uint32_t>(sp.item.size());
         for (uint64_t lo = off; lo < off + len[s]; lo += kSegItemElems) {
             const uint64_t left = off + len[s] - lo;
             sp.item.push_back(SegItem{lo, static_cast<uint32_t>(left < kSegItemElems ? left : kSegItemElems), s});
         }
-        off += len[s];
-        sp.seg_end[s] = off;
+        sp.seg_start[s] = off;
+        sp.seg_end[s] = off + len[s];
+        packed = off + len[s];
+        sp.covered += len[s];
     }
+    sp.seg_start[S] = sp.seg_end[S] = ~0ull;  // sentinel: ends the forward scans, contains no element
     sp.item_lo[S] = static_cast<uint32_t>(sp.item.size());
     const uint64_t chunks = (pl.n + (1ull << kSegCoarseShift) - 1) >> kSegCoarseShift;
     sp.coarse.resize(chunks);
     uint32_t s = 0;
+    const uint64_t vec_end = pl.n & ~3ull;  // the apply pass takes the last n % 4 elements one by one
     for (uint64_t c = 0; c < chunks; ++c) {
         const uint64_t idx = c << kSegCoarseShift;
         while (sp.seg_end[s] <= idx)
             ++s;
-        sp.coarse[c] = s;
+        // top bit: the chunk's float4 groups all lie inside segment s (the apply pass then needs no bounds)
+        uint64_t last = idx + (1ull << kSegCoarseShift);
+        last = (last < vec_end ? last : vec_end) - 1;
+        const bool inside = vec_end > idx && sp.seg_start[s] <= idx && sp.seg_end[s] > last;
+        sp.coarse[c] = s | (inside ? kSegInsideBit : 0u);
     }
     // Which workgroup of the reduction takes which items: the items differ in size (a tensor's last item, small
     // tensors), so they are dealt out largest first, each to the workgroup with the least work so far; a workgroup
@@ -117,8 +129,10 @@ void build_segments(a2sgd_plan_t &pl, uint32_t S, const uint64_t *len)
     }
     size_t o = pl.workspace_bytes;  // after the header and the whole-model partials region
     o = align_up(o, 256);
+    sp.off_seg_start = o;
+    o = align_up(o + 8ull * (S + 1), 256);
     sp.off_seg_end = o;
-    o = align_up(o + 8ull * S, 256);
+    o = align_up(o + 8ull * (S + 1), 256);
     sp.off_item = o;
     o = align_up(o + sizeof(SegItem) * sp.item.size(), 256);
     sp.off_item_lo = o;
@@ -142,7 +156,7 @@ void build_segments(a2sgd_plan_t &pl, uint32_t S, const uint64_t *len)
     sp.end = o;
 }
 
-inline bool segmented(const a2sgd_plan_t *plan) { return plan->seg.S > 1; }
+inline bool segmented(const a2sgd_plan_t *plan) { return plan->seg.S > 0; }
 
 std::atomic<uint32_t> g_next_slot{0};
 std::atomic<uint32_t> g_next_token{1};
@@ -281,16 +295,21 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
         return A2SGD_ERR_INVALID_ARG;
     if (cfg->blocks_per_worker > kMaxBlocksPerWorker || cfg->num_segments > kMaxSegments)
         return A2SGD_ERR_INVALID_ARG;
-    if (cfg->num_segments > 1) {
+    if (cfg->num_segments == 0 && (cfg->pooled_means != 0 || cfg->seg_offset != nullptr))
+        return A2SGD_ERR_INVALID_ARG;
+    if (cfg->pooled_means > 1 || cfg->reserved != 0)
+        return A2SGD_ERR_INVALID_ARG;
+    if (cfg->num_segments >= 1) {
         if (cfg->seg_length == nullptr)
             return A2SGD_ERR_INVALID_ARG;
-        uint64_t total = 0;
+        uint64_t end = 0;  // end of the previous tensor
         for (uint32_t s = 0; s < cfg->num_segments; ++s) {
-            if (cfg->seg_length[s] == 0 || cfg->seg_length[s] > cfg->n - total)
+            const uint64_t off = cfg->seg_offset ? cfg->seg_offset[s] : end;
+            if (off < end || off >= cfg->n || cfg->seg_length[s] == 0 || cfg->seg_length[s] > cfg->n - off)
                 return A2SGD_ERR_INVALID_ARG;
-            total += cfg->seg_length[s];
+            end = off + cfg->seg_length[s];
         }
-        if (total != cfg->n)
+        if (cfg->seg_offset == nullptr && end != cfg->n)
             return A2SGD_ERR_INVALID_ARG;
     }
     a2sgd_plan_t *pl = new (std::nothrow) a2sgd_plan_t;
@@ -319,7 +338,7 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
     pl->workspace_bytes = kHeaderBytes + (partials > drift ? partials : drift);
     pl->lazy_blocks = pl->lazy_folded = 0;
     pl->lazy_offset = pl->lazy_sign_offset = 0;
-    if (cfg->num_segments <= 1) {
+    if (cfg->num_segments == 0) {
         // one record per workgroup of the lazy state's one-shot reduction pass, and their folded table
         const uint64_t per = 64ull * kLazyItems, nvec = pl->n >> 2;
         pl->lazy_blocks = static_cast<uint32_t>(nvec ? (nvec + per - 1) / per : 1);
@@ -329,9 +348,9 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
         pl->lazy_sign_offset = (pl->lazy_sign_offset + 255) & ~static_cast<size_t>(255);
         pl->workspace_bytes = pl->lazy_sign_offset + 4ull * pl->P * (64ull * pl->lazy_blocks);
     }
-    if (cfg->num_segments > 1) {
+    if (cfg->num_segments >= 1) {
         try {
-            build_segments(*pl, cfg->num_segments, cfg->seg_length);
+            build_segments(*pl, cfg->num_segments, cfg->seg_length, cfg->seg_offset, cfg->pooled_means != 0);
         } catch (const std::bad_alloc &) {
             delete pl;
             return A2SGD_ERR_NOMEM;
@@ -447,9 +466,28 @@ a2sgd_status_t a2sgd_step(const a2sgd_plan_t *plan, const float *const *g, float
 a2sgd_status_t a2sgd_read_stats(const a2sgd_plan_t *plan, const void *workspace, a2sgd_stream_t stream,
                                 a2sgd_worker_stats_t *out_workers, a2sgd_global_stats_t *out_global)
 {
-    if (plan == nullptr || workspace == nullptr || segmented(plan))
+    if (plan == nullptr || workspace == nullptr || (segmented(plan) && !plan->seg.pooled))
         return A2SGD_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (segmented(plan)) {
+        // pooled means: every tensor's row of the tables holds the same pair; read tensor 0's
+        const SegPlan &sp = plan->seg;
+        const char *b = static_cast<const char *>(workspace);
+        float gmu[2] = {0.0f, 0.0f};
+        for (uint32_t p = 0; out_workers && p < plan->P; ++p)
+            if (hipMemcpyAsync(out_workers + p, b + sp.off_stats + sizeof(a2sgd_worker_stats_t) * p * sp.S,
+                               sizeof(a2sgd_worker_stats_t), hipMemcpyDeviceToHost, s) != hipSuccess)
+                return A2SGD_ERR_DEVICE;
+        if (out_global && hipMemcpyAsync(gmu, b + sp.off_gmu, sizeof(gmu), hipMemcpyDeviceToHost, s) != hipSuccess)
+            return A2SGD_ERR_DEVICE;
+        if (hipStreamSynchronize(s) != hipSuccess)
+            return A2SGD_ERR_DEVICE;
+        if (out_global) {
+            out_global->gmu_pos = gmu[0];
+            out_global->gmu_neg = -gmu[1];  // the table keeps the negated value for the apply pass
+        }
+        return A2SGD_OK;
+    }
     WsHeader hdr;
     if (hipMemcpyAsync(&hdr, workspace, sizeof(WsHeader), hipMemcpyDeviceToHost, s) != hipSuccess)
         return A2SGD_ERR_DEVICE;
@@ -704,7 +742,8 @@ a2sgd_status_t a2sgd_workspace_init(const a2sgd_plan_t *plan, void *workspace, a
         size_t off;
         const void *src;
         size_t bytes;
-    } parts[] = {{sp.off_seg_end, sp.seg_end.data(), 8ull * sp.seg_end.size()},
+    } parts[] = {{sp.off_seg_start, sp.seg_start.data(), 8ull * sp.seg_start.size()},
+                 {sp.off_seg_end, sp.seg_end.data(), 8ull * sp.seg_end.size()},
                  {sp.off_item, sp.item.data(), sizeof(SegItem) * sp.item.size()},
                  {sp.off_item_lo, sp.item_lo.data(), 4ull * sp.item_lo.size()},
                  {sp.off_coarse, sp.coarse.data(), 4ull * sp.coarse.size()},

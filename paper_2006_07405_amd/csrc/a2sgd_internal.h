@@ -91,6 +91,7 @@ namespace a2sgd {
 
 // ---- per-tensor means: static tables the plan builds on the host and a2sgd_workspace_init uploads --------------
 constexpr uint32_t kSegItemElems = 65536;  // a work item of the segmented reduction covers at most this many elements
+constexpr uint32_t kSegInsideBit = 1u << 31;  // in a lookup entry: the whole chunk lies inside that segment
 constexpr uint32_t kSegCoarseShift = 8;    // the lookup table has one entry per 2^8 elements: one per apply workgroup
 
 struct SegItem {  // one work item: a run of elements inside one segment
@@ -103,10 +104,12 @@ struct SegItem {  // one work item: a run of elements inside one segment
 struct SegView {
     uint32_t S;
     uint32_t num_items;
-    const uint64_t *seg_end;   // [S] exclusive end of every segment
+    const uint64_t *seg_start;  // [S + 1] first element of every segment; entry S is a sentinel (2^64 - 1)
+    const uint64_t *seg_end;    // [S + 1] exclusive end of every segment; entry S is a sentinel (2^64 - 1)
     const SegItem *item;       // [num_items], ascending start
     const uint32_t *item_lo;   // [S + 1]: items of segment s are item_lo[s] .. item_lo[s + 1] - 1
-    const uint32_t *coarse;    // [ceil(n / 2^8)]: segment of element k * 2^8
+    const uint32_t *coarse;    // [ceil(n / 2^8)]: the first segment that ends after element k * 2^8 (S if none),
+                               // with kSegInsideBit set if the chunk's float4 groups all lie inside it
     const uint32_t *sched_lo;  // [blocks + 1]: workgroup b of the reduction takes sched_item[sched_lo[b] .. sched_lo[b + 1])
     const uint32_t *sched_item;  // [num_items]
     a2sgd_worker_stats_t *stats;  // [P][S]
@@ -117,14 +120,16 @@ struct SegView {
 };
 
 struct SegPlan {
-    uint32_t S = 0;  // 0 = whole-model means
-    std::vector<uint64_t> seg_end;
+    uint32_t S = 0;  // 0 = the plan has no segments: whole-model means over [0, n)
+    bool pooled = false;  // one pair of means per worker over all segments together
+    uint64_t covered = 0;  // elements inside segments
+    std::vector<uint64_t> seg_start, seg_end;
     std::vector<SegItem> item;
     std::vector<uint32_t> item_lo, coarse;
     uint32_t blocks = 0;  // workgroups per worker of the reduction
     std::vector<uint32_t> sched_lo, sched_item;
     // byte offsets into the workspace
-    size_t off_seg_end = 0, off_item = 0, off_item_lo = 0, off_coarse = 0, off_sched_lo = 0, off_sched_item = 0,
+    size_t off_seg_start = 0, off_seg_end = 0, off_item = 0, off_item_lo = 0, off_coarse = 0, off_sched_lo = 0, off_sched_item = 0,
            off_stats = 0, off_nmp = 0, off_mn = 0, off_gmu = 0, off_records = 0, end = 0;
 };
 

@@ -20,6 +20,7 @@ SegView seg_view(const a2sgd_plan_t &pl, void *ws)
     SegView v;
     v.S = sp.S;
     v.num_items = static_cast<uint32_t>(sp.item.size());
+    v.seg_start = reinterpret_cast<const uint64_t *>(b + sp.off_seg_start);
     v.seg_end = reinterpret_cast<const uint64_t *>(b + sp.off_seg_end);
     v.item = reinterpret_cast<const SegItem *>(b + sp.off_item);
     v.item_lo = reinterpret_cast<const uint32_t *>(b + sp.off_item_lo);
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(64) void k_seg_finalize(const SegView sv)
     cn = wave_sum(cn);
     cz = wave_sum(cz);
     if (lane == 0) {
-        const uint64_t len = sv.seg_end[s] - (s ? sv.seg_end[s - 1] : 0);
+        const uint64_t len = sv.seg_end[s] - sv.seg_start[s];
         a2sgd_worker_stats_t r;
         r.mu_pos = cp ? static_cast<float>(sp / static_cast<double>(cp)) : 0.0f;
         r.mu_neg = cn ? static_cast<float>(sn / static_cast<double>(cn)) : 0.0f;
@@ -155,6 +156,64 @@ __global__ __launch_bounds__(64) void k_seg_finalize(const SegView sv)
         r.n_nan = len - cp - cn;
         sv.stats[static_cast<size_t>(p) * sv.S + s] = r;
     }
+}
+
+// Second level with pooled means: grid = P, one block per worker: all of its records in a fixed order (strided per
+// thread, shuffle tree, wavefronts in index order), one pair of means over all tensors together, and that result
+// into every tensor's row so that the following passes need not know the difference.
+__global__ __launch_bounds__(kBlock) void k_seg_finalize_pooled(const SegView sv, const uint64_t covered)
+{
+    const uint32_t p = blockIdx.x, tid = threadIdx.x;
+    const size_t row = static_cast<size_t>(p) * sv.num_items;
+    double sp = 0.0, sn = 0.0;
+    uint64_t cp = 0, cn = 0, cz = 0;
+    for (uint32_t j = tid; j < sv.num_items; j += kBlock) {
+        sp += sv.r_spos[row + j];
+        sn += sv.r_sneg[row + j];
+        cp += sv.r_npos[row + j];
+        cn += sv.r_nneg[row + j];
+        cz += sv.r_nzero[row + j];
+    }
+    __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
+    __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
+    __shared__ a2sgd_worker_stats_t sh_result;
+    sp = wave_sum(sp);
+    sn = wave_sum(sn);
+    cp = wave_sum(cp);
+    cn = wave_sum(cn);
+    cz = wave_sum(cz);
+    const uint32_t lane = tid & 63, wave = tid >> 6;
+    if (lane == 0) {
+        sh_pos[wave] = sp;
+        sh_neg[wave] = sn;
+        sh_cp[wave] = cp;
+        sh_cn[wave] = cn;
+        sh_cz[wave] = cz;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double tp = 0.0, tn = 0.0;
+        uint64_t np = 0, nn = 0, nz = 0;
+#pragma unroll
+        for (int k = 0; k < kBlock / 64; ++k) {
+            tp += sh_pos[k];
+            tn += sh_neg[k];
+            np += sh_cp[k];
+            nn += sh_cn[k];
+            nz += sh_cz[k];
+        }
+        a2sgd_worker_stats_t r;
+        r.mu_pos = np ? static_cast<float>(tp / static_cast<double>(np)) : 0.0f;
+        r.mu_neg = nn ? static_cast<float>(tn / static_cast<double>(nn)) : 0.0f;
+        r.n_pos = np;
+        r.n_neg = nn;
+        r.n_zero = nz;
+        r.n_nan = covered - np - nn;
+        sh_result = r;
+    }
+    __syncthreads();
+    for (uint32_t s = tid; s < sv.S; s += kBlock)
+        sv.stats[static_cast<size_t>(p) * sv.S + s] = sh_result;
 }
 
 // Algorithm 1 line 5 per segment, and the tables the apply pass reads: one thread per segment.
@@ -218,9 +277,6 @@ __global__ __launch_bounds__(BLOCK) void k_seg_apply(const PtrTable tab, float *
     const uint64_t first = static_cast<uint64_t>(blockIdx.x) * BLOCK;  // first float4 group of the workgroup
     const uint64_t i = first + tid;
     if (first < nvec) {
-        uint64_t e_last = ((first + BLOCK) << 2) - 1;  // last element of the workgroup's float4 groups
-        if (e_last > (nvec << 2) - 1)
-            e_last = (nvec << 2) - 1;
         const bool live = i < nvec;
         vf4 *w4 = reinterpret_cast<vf4 *>(w) + i;
         vf4 wv, v[UP], ev[UP];
@@ -240,8 +296,9 @@ __global__ __launch_bounds__(BLOCK) void k_seg_apply(const PtrTable tab, float *
         __builtin_amdgcn_sched_barrier(0);
         // the table has exactly one entry per workgroup: the segment of its first element
         static_assert(BLOCK * 4 == (1 << kSegCoarseShift), "one lookup entry per apply workgroup");
-        const uint32_t s0 = sv.coarse[blockIdx.x];
-        if (sv.seg_end[s0] > e_last) {
+        const uint32_t entry = sv.coarse[blockIdx.x];
+        const uint32_t s0 = entry & ~kSegInsideBit;  // the first segment that ends after the workgroup's first element
+        if (entry & kSegInsideBit) {
             // the whole workgroup lies in segment s0
             if (live) {
                 const uint32_t lz = opaque_zero();
@@ -279,41 +336,54 @@ __global__ __launch_bounds__(BLOCK) void k_seg_apply(const PtrTable tab, float *
                 st4<NT>(w4, wn);
             }
         } else if (live) {
-            // A boundary inside the workgroup: each of the lane's four elements has its own segment.  Still one
-            // float4 per worker and array; only the means are gathered per element.  (What was loaded above is
-            // reloaded, from the cache, to keep this rare path simple.)
+            // A boundary inside the workgroup: each of the lane's four elements has its own segment, or none (padding
+            // between tensors).  A float4 group that lies wholly inside segments still goes as one float4 per
+            // worker and array, only the means are gathered per element; a group with padding in it goes element by
+            // element, and padding is not touched.  (What was loaded above is reloaded, from the cache, to keep
+            // this rare path simple.)
             uint32_t sc[4];
+            bool in[4];
             uint32_t sx = s0;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 sx = seg_of(sv, sx, (i << 2) + c);
                 sc[c] = sx;
+                in[c] = sv.seg_start[sx] <= (i << 2) + c;
             }
-            vf4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-            for (uint32_t p = 0; p < P; ++p) {
-                vf4 vv = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p]) + i);
-                if (HAS_E)
-                    vv += ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p]) + i);
-                float x[4] = {vv.x, vv.y, vv.z, vv.w}, a[4] = {acc.x, acc.y, acc.z, acc.w};
+            if (in[0] && in[1] && in[2] && in[3]) {
+                vf4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+                for (uint32_t p = 0; p < P; ++p) {
+                    vf4 vv = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p]) + i);
+                    if (HAS_E)
+                        vv += ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p]) + i);
+                    float x[4] = {vv.x, vv.y, vv.z, vv.w}, a[4] = {acc.x, acc.y, acc.z, acc.w};
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const size_t k = static_cast<size_t>(sc[c]) * P + p;
-                    a[c] += apply1<MODE>(x[c], sv.neg_mu_pos[k], sv.mu_neg[k], sv.gmu[2 * sc[c]], sv.gmu[2 * sc[c] + 1]);
+                    for (int c = 0; c < 4; ++c) {
+                        const size_t k = static_cast<size_t>(sc[c]) * P + p;
+                        a[c] += apply1<MODE>(x[c], sv.neg_mu_pos[k], sv.mu_neg[k], sv.gmu[2 * sc[c]],
+                                             sv.gmu[2 * sc[c] + 1]);
+                    }
+                    acc = vf4{a[0], a[1], a[2], a[3]};
+                    if (HAS_E) {
+                        const vf4 err = vf4{x[0], x[1], x[2], x[3]};
+                        st4<NT>(reinterpret_cast<vf4 *>(tab.e[p]) + i, err);
+                    }
                 }
-                acc = vf4{a[0], a[1], a[2], a[3]};
-                if (HAS_E) {
-                    const vf4 err = vf4{x[0], x[1], x[2], x[3]};
-                    st4<NT>(reinterpret_cast<vf4 *>(tab.e[p]) + i, err);
-                }
+                const vf4 wn = wv - eta_over_P * acc;
+                st4<NT>(w4, wn);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (in[c])
+                        seg_apply_element<MODE, HAS_E>(tab, w, (i << 2) + c, sc[c], P, eta_over_P, sv);
             }
-            const vf4 wn = wv - eta_over_P * acc;
-            st4<NT>(w4, wn);
         }
     }
     if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
         const uint64_t idx = (nvec << 2) + tid;
-        const uint32_t s = seg_of(sv, sv.coarse[idx >> kSegCoarseShift], idx);
-        seg_apply_element<MODE, HAS_E>(tab, w, idx, s, P, eta_over_P, sv);
+        const uint32_t s = seg_of(sv, sv.coarse[idx >> kSegCoarseShift] & ~kSegInsideBit, idx);
+        if (sv.seg_start[s] <= idx)
+            seg_apply_element<MODE, HAS_E>(tab, w, idx, s, P, eta_over_P, sv);
     }
 }
 
@@ -342,7 +412,10 @@ hipError_t launch_seg_partials(const a2sgd_plan_t &pl, const PtrTable &tab, bool
 hipError_t launch_seg_finalize(const a2sgd_plan_t &pl, void *ws, hipStream_t s)
 {
     const SegView sv = seg_view(pl, ws);
-    k_seg_finalize<<<dim3(sv.S, pl.P), dim3(64), 0, s>>>(sv);
+    if (pl.seg.pooled)
+        k_seg_finalize_pooled<<<dim3(pl.P), dim3(kBlock), 0, s>>>(sv, pl.seg.covered);
+    else
+        k_seg_finalize<<<dim3(sv.S, pl.P), dim3(64), 0, s>>>(sv);
     return hipGetLastError();
 }
 

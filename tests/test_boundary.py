@@ -42,7 +42,7 @@ def test_binding_has_the_same_names(A):
 def test_struct_layouts_match_header(A):
     from paper_2006_07405_amd import binding as B
     assert C.sizeof(B.a2sgd_worker_stats_t) == 40
-    assert C.sizeof(B.a2sgd_config_t) == 32
+    assert C.sizeof(B.a2sgd_config_t) == 48
     assert C.sizeof(B.a2sgd_global_stats_t) == 8
     assert C.sizeof(B.a2sgd_device_info_t) == 32
     assert A.raw.a2sgd_device_info(None) == A.A2SGD_ERR_INVALID_ARG
@@ -95,8 +95,25 @@ def test_segmented_plan_validation_and_workspace(A):
     seg = A.a2sgd_plan(1_000_000, 4, 0, 0, seg_lengths=[1, 70_000, 3, 929_996])
     # the tables of the per-tensor plan come after the header and the whole-model partial records
     assert A.a2sgd_workspace_bytes(seg) > 4096 + 5 * 8 * 4 * A.a2sgd_plan_blocks_per_worker(whole)
-    one = A.a2sgd_plan(1_000_000, 4, 0, 0, seg_lengths=[1_000_000])  # a single segment is the whole-model method
-    assert A.a2sgd_workspace_bytes(one) == A.a2sgd_workspace_bytes(whole) and one.num_segments == 0
+    one = A.a2sgd_plan(1_000_000, 4, 0, 0, seg_lengths=[1_000_000])  # one tensor: the same means, the tensor path
+    assert one.num_segments == 1
+    # with offsets: ascending, not overlapping, inside [0, n); sizes need not add up to n
+    ok = A.a2sgd_plan(100, 2, 0, 0, seg_lengths=[10, 20, 5], seg_offsets=[3, 13, 90])
+    assert ok.num_segments == 3
+    for lengths, offsets in (([10, 20], [5, 14]), ([10, 20], [20, 0]), ([10, 20], [0, 81]), ([10], [100]), ([0], [5])):
+        with pytest.raises(A.A2sgdError) as ei:
+            A.a2sgd_plan(100, 2, 0, 0, seg_lengths=lengths, seg_offsets=offsets)
+        assert ei.value.status == A.A2SGD_ERR_INVALID_ARG
+    # pooled means and offsets belong to plans with tensors
+    from paper_2006_07405_amd import binding as B
+    h = C.c_void_p()
+    for cfg in (B.a2sgd_config_t(10, 2, 0, 0, 0, None, None, 1, 0),
+                B.a2sgd_config_t(10, 2, 0, 0, 0, None, (C.c_uint64 * 1)(0), 0, 0),
+                B.a2sgd_config_t(10, 2, 0, 0, 1, (C.c_uint64 * 1)(10), None, 2, 0),
+                B.a2sgd_config_t(10, 2, 0, 0, 1, (C.c_uint64 * 1)(10), None, 0, 7)):
+        assert A.raw.a2sgd_plan(C.byref(cfg), C.byref(h)) == A.A2SGD_ERR_INVALID_ARG
+    pooled = A.a2sgd_plan(100, 2, 0, 0, seg_lengths=[10, 20], seg_offsets=[4, 50], pooled_means=True)
+    assert A.raw.a2sgd_read_stats(pooled.handle, None, None, None, None) == A.A2SGD_ERR_INVALID_ARG  # NULL workspace
     R = A.raw
     assert R.a2sgd_read_stats(seg.handle, 0x30000, None, None, None) == A.A2SGD_ERR_INVALID_ARG
     assert R.a2sgd_read_segment_stats(whole.handle, 0x30000, None, None, None) == A.A2SGD_ERR_INVALID_ARG

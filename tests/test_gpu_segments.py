@@ -6,7 +6,7 @@ import torch
 
 import workloads
 from oracle import a2sgd_oracle as O
-from tests.helpers import assert_array_close, close, dev
+from tests.helpers import assert_array_close, close, compare_stats, dev
 
 pytestmark = pytest.mark.gpu
 f32 = np.float32
@@ -91,6 +91,100 @@ def test_segment_layouts(A, seg):
         run_case(A, g, e if with_e else None, w, 0.1, mode, seg, split_calls=split)
 
 
+def run_padded_case(A, seed, n, P, mode, lengths, offsets, pooled, with_e=True):
+    """Tensors at `offsets` inside buffers of n elements; everything outside them is padding, filled with NaN in g,
+    e and w: it must come back bit for bit and must not enter any count or sum."""
+    rng = np.random.default_rng(seed)
+    member = np.zeros(n, bool)
+    scale = np.ones(n, f32)
+    for k, (o, l) in enumerate(zip(offsets, lengths)):
+        member[o:o + l] = True
+        scale[o:o + l] = 10.0 ** rng.uniform(-5, -2)
+    g = [(rng.standard_normal(n).astype(f32) * scale) for _ in range(P)]
+    e = [(rng.standard_normal(n).astype(f32) * scale * f32(0.5)) for _ in range(P)]
+    w = (rng.standard_normal(n) * 0.02).astype(f32)
+    for x in g + e + [w]:
+        x[~member] = np.nan
+    plan = A.a2sgd_plan(n, P, mode, 0, seg_lengths=lengths, seg_offsets=offsets, pooled_means=pooled)
+    ws = A.alloc_workspace(plan)
+    gd = [dev(x) for x in g]
+    ed = [dev(x) for x in e] if with_e else None
+    wd = dev(w)
+    A.a2sgd_step(plan, gd, ed, wd, 0.1, ws)
+    res, e_ref, w_ref = O.step_segmented(g, e if with_e else None, w, 0.1, mode, lengths, offsets, pooled)
+    stats, gmu = A.a2sgd_read_segment_stats(plan, ws)
+    for s in range(len(lengths)):
+        r = res[0] if pooled else res[s]
+        for p in range(P):
+            a, b = stats[p][s], r.workers[p]
+            assert (a.n_pos, a.n_neg, a.n_zero, a.n_nan) == (b.n_pos, b.n_neg, b.n_zero, b.n_nan), f"tensor {s} worker {p}"
+            close(a.mu_pos, b.mu_pos, f"tensor {s} worker {p} mu_pos")
+            close(a.mu_neg, b.mu_neg, f"tensor {s} worker {p} mu_neg")
+        close(gmu[s][0], r.gmu_pos, f"tensor {s} gmu_pos")
+        close(gmu[s][1], r.gmu_neg, f"tensor {s} gmu_neg")
+    if pooled:
+        st, gm = A.a2sgd_read_stats(plan, ws)
+        compare_stats(st, gm, res[0])
+    w_got = wd.cpu().numpy()
+    assert np.isnan(w_got[~member]).all(), "padding of w was written"
+    for o, l in zip(offsets, lengths):
+        assert_array_close(w_got[o:o + l], w_ref[o:o + l], f"w tensor at {o}")
+    if with_e:
+        for p in range(P):
+            e_got = ed[p].cpu().numpy()
+            assert np.isnan(e_got[~member]).all(), "padding of e was written"
+            for o, l in zip(offsets, lengths):
+                assert_array_close(e_got[o:o + l], e_ref[p][o:o + l], f"e[{p}] tensor at {o}")
+
+
+PADDED = [  # (n, lengths, offsets)
+    (10, [3], [4]),
+    (64, [1, 1, 1], [0, 2, 63]),
+    (1000, [5, 250, 3, 100], [1, 7, 300, 900]),
+    (5000, [255, 1, 256, 3, 257, 1024], [3, 258, 259, 1027, 1030, 2000]),
+    (70_000, [4096, 1, 4095, 30_000], [4, 4100, 8192, 20_001]),
+    (400_000, [65_536, 65_537, 131_073], [0, 65_536, 200_003]),
+    (300_000, [299_000], [1000]),
+]
+
+
+@pytest.mark.parametrize("case", PADDED, ids=[f"padded{i}" for i in range(len(PADDED))])
+def test_tensors_with_padding(A, case):
+    n, lengths, offsets = case
+    for P, mode, pooled, with_e in ((1, 0, False, True), (3, 0, True, True), (4, 1, False, True), (5, 1, True, False),
+                                    (9, 0, True, True)):
+        print(f"case n={n} S={len(lengths)} P={P} mode={mode} pooled={pooled} e={with_e}", flush=True)
+        run_padded_case(A, n + P, n, P, mode, lengths, offsets, pooled, with_e)
+
+
+def test_pooled_means_on_packed_tensors_equal_the_whole_model_step(A):
+    """Without padding, pooled means are the paper's whole-model means: same counts as the plain plan, means equal
+    to the tolerance of the sums' grouping, same e and w."""
+    seg = [1000, 1, 70_001, 4096, 300_000]
+    n, P = sum(seg), 4
+    g, e, w = make_case(n, n, P, scales_for(seg, 3))
+    ref = O.step(g, e, w, 0.1, 0)
+    plan = A.a2sgd_plan(n, P, 0, 0, seg_lengths=seg, pooled_means=True)
+    ws = A.alloc_workspace(plan)
+    gd, ed, wd = [dev(x) for x in g], [dev(x) for x in e], dev(w)
+    A.a2sgd_local_averages(plan, gd, ed, ws)
+    A.a2sgd_global_average(plan, ws)
+    A.a2sgd_apply_and_update_error(plan, gd, ed, wd, 0.1, ws)
+    st, gm = A.a2sgd_read_stats(plan, ws)
+    compare_stats(st, gm, ref)
+    assert_array_close(wd.cpu().numpy(), ref.w_new, "w")
+    for p in range(P):
+        assert_array_close(ed[p].cpu().numpy(), ref.e_new[p], f"e[{p}]")
+
+
+def test_streaming_size_with_padding(A):
+    seg = [1_000_003, 5, 777_777, 64, 1_300_001]
+    off = [7, 1_000_013, 1_000_020, 1_800_000, 1_800_257]
+    n = 3_500_003
+    run_padded_case(A, 11, n, 7, 0, seg, off, pooled=False)
+    run_padded_case(A, 12, n, 7, 0, seg, off, pooled=True)
+
+
 @pytest.mark.parametrize("P,mode", [(7, 0), (12, 1)])
 def test_streaming_size_with_a_short_group_of_workers(A, P, mode):
     """A footprint above the cache limit (streaming kernels) with tensor boundaries of every alignment and a worker
@@ -122,10 +216,13 @@ def test_empty_groups_and_nan_per_segment(A):
     assert stats[0][2].n_nan == 1 and stats[0][2].n_pos == 2 and stats[0][2].n_neg == 2
 
 
-def test_one_segment_is_the_whole_model_method(A):
-    g, e, w = make_case(3, 50_001, 3, np.full(50_001, 1e-3, f32))
-    plan_seg = A.a2sgd_plan(50_001, 3, 0, 0, seg_lengths=[50_001])
-    assert plan_seg.num_segments == 0  # treated as whole-model
+def test_one_tensor_is_the_whole_model_method(A):
+    """One tensor that covers the buffers: the tensor path must give what the whole-model oracle gives."""
+    n = 50_001
+    g, e, w = make_case(3, n, 3, np.full(n, 1e-3, f32))
+    stats, gmu = run_case(A, g, e, w, 0.1, 0, [n])
+    ref = O.step(g, e, w, 0.1, 0)
+    compare_stats([row[0] for row in stats], gmu[0], ref)
 
 
 def test_config2_full_size_per_tensor(A):

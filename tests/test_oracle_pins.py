@@ -177,6 +177,54 @@ def test_per_tensor_variant_worked_example_and_brute_force():
                 off += length
 
 
+def test_tensors_with_padding_and_pooled_means():
+    """Buffers that hold tensors with padding between them: per tensor, each tensor is the brute force on its own
+    slice; pooled, all tensors laid end to end are one brute-force vector; padding comes back bit for bit, whatever it
+    holds (here NaN, which would poison any sum it entered)."""
+    rng = np.random.default_rng(78)
+    for _ in range(25):
+        P, S = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        lengths = [int(x) for x in rng.integers(1, 6, S)]
+        gaps = [int(x) for x in rng.integers(0, 4, S + 1)]
+        offsets, pos = [], gaps[0]
+        for k in range(S):
+            offsets.append(pos)
+            pos += lengths[k] + gaps[k + 1]
+        n = pos if pos > 0 else 1
+        member = np.zeros(n, bool)
+        for o, l in zip(offsets, lengths):
+            member[o:o + l] = True
+        g = [arr(rng.integers(-32, 33, n) / 8.0) for _ in range(P)]
+        e = [arr(rng.integers(-16, 17, n) / 8.0) for _ in range(P)]
+        w = arr(rng.integers(-64, 65, n) / 16.0)
+        for x in g + e + [w]:
+            x[~member] = np.nan
+        for mode in (O.RETAINED_ERROR, O.ALG1_LITERAL):
+            for pooled in (False, True):
+                res, e_new, w_new = O.step_segmented(g, e, w, 0.25, mode, lengths, offsets, pooled)
+                for p in range(P):
+                    assert np.isnan(e_new[p][~member]).all() and not np.isnan(e_new[p][member]).any()
+                assert np.isnan(w_new[~member]).all() and not np.isnan(w_new[member]).any()
+                if pooled:
+                    cat = lambda x: np.concatenate([x[o:o + l] for o, l in zip(offsets, lengths)])
+                    mu_pos, mu_neg, gp, gn, err, wn = brute_force([cat(x) for x in g], [cat(x) for x in e], cat(w), 0.25, mode)
+                    assert len(res) == 1 and [s.mu_pos for s in res[0].workers] == [float(x) for x in mu_pos]
+                    assert [s.n_nan for s in res[0].workers] == [0] * P
+                    assert (res[0].gmu_pos, res[0].gmu_neg) == (float(gp), float(gn))
+                    for p in range(P):
+                        assert cat(e_new[p]).tolist() == [float(x) for x in err[p]]
+                    assert cat(w_new).tolist() == [float(x) for x in wn]
+                else:
+                    for k, (o, l) in enumerate(zip(offsets, lengths)):
+                        sl = slice(o, o + l)
+                        mu_pos, mu_neg, gp, gn, err, wn = brute_force([x[sl] for x in g], [x[sl] for x in e], w[sl], 0.25, mode)
+                        assert [s.mu_neg for s in res[k].workers] == [float(x) for x in mu_neg]
+                        assert (res[k].gmu_pos, res[k].gmu_neg) == (float(gp), float(gn))
+                        for p in range(P):
+                            assert e_new[p][sl].tolist() == [float(x) for x in err[p]]
+                        assert w_new[sl].tolist() == [float(x) for x in wn]
+
+
 # ---------------------------------------------------------------------------------------------------------
 # exactly rounded means: math.fsum is an exact sum, so fl32(fsum/n) is the definition's value
 # ---------------------------------------------------------------------------------------------------------
