@@ -197,3 +197,15 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=60)
     assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout == ""
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/a2sgd.h compiles as C99 with no extensions and no other headers than the two standard ones."""
+    import subprocess
+    src = tmp_path / "client.c"
+    src.write_text('#include "a2sgd.h"\n'
+                   "int main(void)\n{\n    a2sgd_config_t cfg;\n    a2sgd_worker_stats_t st;\n"
+                   "    cfg.n = 1;\n    st.n_pos = 0;\n"
+                   "    return (int)(cfg.n + st.n_pos) - 1 + (int)sizeof(a2sgd_device_info_t) - 32;\n}\n")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only",
+                           "-I", os.path.join(ROOT, "include"), str(src)])
