@@ -29,5 +29,21 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+CLIENT_SRC = os.path.join(ROOT, "tests", "c_client", "client.cpp")
+CLIENT = os.path.join(ROOT, "tests", "c_client", "client")
+
+
+def build_client() -> str:
+    """The test program that calls the C ABI without Python or torch (tests/c_client): host code only, linked
+    against the library next to this file."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-O2", "-std=c++17", "-Wall", "-Wextra", "-I" + os.path.join(ROOT, "include"), CLIENT_SRC, "-o", CLIENT,
+           "-L" + HERE, "-la2sgd", "-Wl,-rpath,$ORIGIN/../../paper_2006_07405_amd"]
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed on the client:\n" + proc.stdout)
+    return CLIENT
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

@@ -563,6 +563,36 @@ def test_buffers_at_the_minimum_alignment(A):
             assert_array_close(ed[p].cpu().numpy(), ref.e_new[p], f"{path}: e[{p}]")
 
 
+@pytest.mark.parametrize("n,P,mode,three", [(100_003, 3, 0, 0), (100_003, 3, 1, 1), (6_000_001, 4, 0, 0)])
+def test_c_client_without_python_in_the_path(A, tmp_path, n, P, mode, three):
+    """tests/c_client/client.cpp calls the C ABI with memory from hipMalloc and a stream of its own; this test only
+    writes its input file and reads its output file.  Sizes: a single-launch step, the three calls, a streaming size."""
+    import subprocess
+    client = os.path.join(os.path.dirname(__file__), "c_client", "client")
+    assert os.path.exists(client), "build() compiles the client"
+    g, e, w = make_case(n + mode, n, P)
+    fin, fout = tmp_path / "in.bin", tmp_path / "out.bin"
+    np.concatenate(g + e + [w]).astype(f32).tofile(fin)
+    subprocess.run([client, str(fin), str(fout), str(n), str(P), str(mode), "0.1", str(three)], check=True, timeout=120)
+    raw = np.fromfile(fout, dtype=np.uint8)
+    rec = np.dtype([("mu_pos", f32), ("mu_neg", f32), ("n_pos", np.uint64), ("n_neg", np.uint64),
+                    ("n_zero", np.uint64), ("n_nan", np.uint64)])
+    stats = raw[:40 * P].view(rec)
+    gmu = raw[40 * P:40 * P + 8].view(f32)
+    body = raw[40 * P + 8:].view(f32)
+    assert body.size == (P + 1) * n
+    ref = O.step(g, e, w, 0.1, mode)
+    for p in range(P):
+        r = ref.workers[p]
+        assert (int(stats[p]["n_pos"]), int(stats[p]["n_neg"]), int(stats[p]["n_zero"]), int(stats[p]["n_nan"])) == \
+            (r.n_pos, r.n_neg, r.n_zero, r.n_nan)
+        assert abs(float(stats[p]["mu_pos"]) - r.mu_pos) <= 1e-5 * abs(r.mu_pos)
+        assert abs(float(stats[p]["mu_neg"]) - r.mu_neg) <= 1e-5 * abs(r.mu_neg)
+        assert_array_close(body[p * n:(p + 1) * n], ref.e_new[p], f"e[{p}]")
+    assert abs(float(gmu[0]) - ref.gmu_pos) <= 1e-5 * abs(ref.gmu_pos) and abs(float(gmu[1]) - ref.gmu_neg) <= 1e-5 * abs(ref.gmu_neg)
+    assert_array_close(body[P * n:], ref.w_new, "w")
+
+
 def test_device_info(A):
     info = A.a2sgd_device_info()
     assert info["compute_units"] >= 64 and info["total_memory_bytes"] > 64 << 30
