@@ -228,6 +228,23 @@ a2sgd_status_t a2sgd_lazy_step(const a2sgd_plan_t *plan, const float *const *g, 
 a2sgd_status_t a2sgd_lazy_materialize(const a2sgd_plan_t *plan, float *const *s, void *workspace,
                                       a2sgd_stream_t stream);
 
+/* ---- Where a real collective goes: Algorithm 1 line 5 done by the caller ------------------------------------
+ * When the workers live on different GPUs (one process per GPU, each with a plan of its own workers, typically
+ * P = 1), the average of line 5 is the caller's collective over 2 floats per worker.  The two calls below replace
+ * a2sgd_global_average for that: a2sgd_local_averages, a2sgd_export_local_means, the caller's all-reduce (average)
+ * or all-gather of the pairs on the same stream, a2sgd_import_global_means, a2sgd_apply_and_update_error.  Both only
+ * enqueue a small kernel; nothing comes to the host.  Whole-model plans only. */
+
+/* Writes this plan's P pairs (mu_pos^p, mu_neg^p), as left by a2sgd_local_averages, to `out`: a DEVICE array of
+ * 2 * P floats, out[2p] = mu_pos^p, out[2p + 1] = mu_neg^p. */
+a2sgd_status_t a2sgd_export_local_means(const a2sgd_plan_t *plan, const void *workspace, float *out,
+                                        a2sgd_stream_t stream);
+
+/* Takes the global means from `gmu`, a DEVICE array of 2 floats (gmu_pos, gmu_neg: the average over ALL workers of
+ * the job of their local means, formed by the caller), instead of averaging this plan's own workers. */
+a2sgd_status_t a2sgd_import_global_means(const a2sgd_plan_t *plan, void *workspace, const float *gmu,
+                                         a2sgd_stream_t stream);
+
 /* Diagnostic: exercises the grid-wide barrier of the single-launch step on a cell of its own.  First 128
  * workgroups must all pass one barrier; then 128 workgroups wait, with a limit of 64 polls, for an arrival that
  * never comes: every one of them must give up, exit normally and leave the cell marked failed.  Returns A2SGD_OK

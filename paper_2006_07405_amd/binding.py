@@ -78,6 +78,8 @@ def _load():
                                            C.POINTER(a2sgd_global_stats_t)]
     L.a2sgd_read_segment_stats.restype = C.c_int
     L.a2sgd_device_info.argtypes = [C.POINTER(a2sgd_device_info_t)]
+    L.a2sgd_export_local_means.argtypes = [vp, vp, vp, vp]
+    L.a2sgd_import_global_means.argtypes = [vp, vp, vp, vp]
     L.a2sgd_status_string.argtypes = [C.c_int]
     L.a2sgd_status_string.restype = C.c_char_p
     for name in ("a2sgd_plan", "a2sgd_plan_destroy", "a2sgd_local_averages", "a2sgd_global_average",
@@ -213,6 +215,20 @@ def a2sgd_local_averages(plan: Plan, g, e, workspace: torch.Tensor, stream=None)
 def a2sgd_global_average(plan: Plan, workspace: torch.Tensor, stream=None) -> None:
     _check(raw.a2sgd_global_average(plan.handle, _workspace(plan, workspace), _stream(stream)),
            "a2sgd_global_average")
+
+
+def a2sgd_export_local_means(plan: Plan, workspace: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    """out: a CUDA float32 tensor of 2 * P elements; receives (mu_pos, mu_neg) of every worker of this plan."""
+    _check(raw.a2sgd_export_local_means(plan.handle, _workspace(plan, workspace),
+                                        _dev_ptr(out, 2 * plan.num_workers, torch.float32, "out"), _stream(stream)),
+           "a2sgd_export_local_means")
+
+
+def a2sgd_import_global_means(plan: Plan, workspace: torch.Tensor, gmu: torch.Tensor, stream=None) -> None:
+    """gmu: a CUDA float32 tensor of 2 elements, (gmu_pos, gmu_neg) averaged over all workers of the job."""
+    _check(raw.a2sgd_import_global_means(plan.handle, _workspace(plan, workspace),
+                                         _dev_ptr(gmu, 2, torch.float32, "gmu"), _stream(stream)),
+           "a2sgd_import_global_means")
 
 
 def a2sgd_apply_and_update_error(plan: Plan, g, e, w: torch.Tensor, eta: float, workspace: torch.Tensor,

@@ -413,6 +413,27 @@ a2sgd_status_t a2sgd_global_average(const a2sgd_plan_t *plan, void *workspace, a
     return dev(launch_global_average(*plan, workspace, static_cast<hipStream_t>(stream)));
 }
 
+a2sgd_status_t a2sgd_export_local_means(const a2sgd_plan_t *plan, const void *workspace, float *out,
+                                        a2sgd_stream_t stream)
+{
+    if (plan == nullptr || segmented(plan) || workspace == nullptr || out == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(out) & 3u) != 0)
+        return A2SGD_ERR_ALIGNMENT;
+    return dev(launch_export_local_means(*plan, workspace, out, static_cast<hipStream_t>(stream)));
+}
+
+a2sgd_status_t a2sgd_import_global_means(const a2sgd_plan_t *plan, void *workspace, const float *gmu,
+                                         a2sgd_stream_t stream)
+{
+    if (plan == nullptr || segmented(plan) || workspace == nullptr || gmu == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(gmu) & 3u) != 0)
+        return A2SGD_ERR_ALIGNMENT;
+    plan->last_token = 0;
+    return dev(launch_import_global_means(*plan, workspace, gmu, static_cast<hipStream_t>(stream)));
+}
+
 a2sgd_status_t a2sgd_apply_and_update_error(const a2sgd_plan_t *plan, const float *const *g, float *const *e,
                                             float *w, float eta, void *workspace, a2sgd_stream_t stream)
 {

@@ -159,6 +159,8 @@ namespace a2sgd {
 hipError_t launch_local_partials(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, void *ws, hipStream_t s);
 hipError_t launch_local_finalize(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
 hipError_t launch_global_average(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
+hipError_t launch_export_local_means(const a2sgd_plan_t &pl, const void *ws, float *out, hipStream_t s);
+hipError_t launch_import_global_means(const a2sgd_plan_t &pl, void *ws, const float *gmu, hipStream_t s);
 hipError_t launch_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
                         hipStream_t s);
 hipError_t launch_fused_step(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,

@@ -173,6 +173,32 @@ __global__ void k_global_average(const uint32_t P, WsHeader *__restrict__ hdr)
     }
 }
 
+// Algorithm 1 line 5 when the caller does the averaging (workers on several GPUs): the local pairs out, the global
+// pair in.  The import also fills what k_global_average fills besides the global means.
+__global__ void k_export_local_means(const uint32_t P, const WsHeader *__restrict__ hdr, float *__restrict__ out)
+{
+    for (uint32_t p = threadIdx.x; p < P && blockIdx.x == 0; p += blockDim.x) {
+        out[2 * p] = hdr->workers[p].mu_pos;
+        out[2 * p + 1] = hdr->workers[p].mu_neg;
+    }
+}
+
+__global__ void k_import_global_means(const uint32_t P, WsHeader *__restrict__ hdr, const float *__restrict__ gmu)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        hdr->gmu_pos = gmu[0];
+        hdr->gmu_neg = gmu[1];
+        uint32_t any_nan = 0;
+        for (uint32_t p = 0; p < P; ++p)
+            any_nan |= hdr->workers[p].n_nan != 0 ? 1u : 0u;
+        hdr->any_nan = any_nan;
+    }
+    for (uint32_t p = threadIdx.x; p < P && blockIdx.x == 0; p += blockDim.x) {
+        hdr->neg_mu_pos[p] = -hdr->workers[p].mu_pos;
+        hdr->mu_neg[p] = hdr->workers[p].mu_neg;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // Fused apply pass (Algorithm 1 lines 4, 6, 7; Eq. 2 for the encoding; Eq. 1 for the average over workers)
 // ---------------------------------------------------------------------------------------------------------
@@ -1231,6 +1257,18 @@ hipError_t launch_local_finalize(const a2sgd_plan_t &pl, void *ws, hipStream_t s
 {
     k_local_finalize<<<dim3(pl.P), dim3(kBlock), 0, s>>>(pl.n, pl.B, partials_of(ws, pl.P, pl.B),
                                                         static_cast<WsHeader *>(ws));
+    return hipGetLastError();
+}
+
+hipError_t launch_export_local_means(const a2sgd_plan_t &pl, const void *ws, float *out, hipStream_t s)
+{
+    k_export_local_means<<<dim3(1), dim3(64), 0, s>>>(pl.P, static_cast<const WsHeader *>(ws), out);
+    return hipGetLastError();
+}
+
+hipError_t launch_import_global_means(const a2sgd_plan_t &pl, void *ws, const float *gmu, hipStream_t s)
+{
+    k_import_global_means<<<dim3(1), dim3(64), 0, s>>>(pl.P, static_cast<WsHeader *>(ws), gmu);
     return hipGetLastError();
 }
 

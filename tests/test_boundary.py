@@ -153,6 +153,10 @@ def test_step_calls_validate_before_launch(A):
     assert R.a2sgd_dense_step(h, None, w, 0.1, None) == INV
     assert R.a2sgd_dense_step(h, good, w + 2, 0.1, None) == ALN
     assert R.a2sgd_read_stats(h, None, None, None, None) == INV
+    assert R.a2sgd_export_local_means(h, ws, None, None) == INV
+    assert R.a2sgd_export_local_means(h, ws, 0x50002, None) == ALN
+    assert R.a2sgd_import_global_means(h, None, 0x50000, None) == INV
+    assert R.a2sgd_import_global_means(h, ws + 8, 0x50000, None) == ALN
     # aliasing: a written buffer may not overlap anything else of the call; read-only ones may coincide
     other = _tab([0x50000, 0x60000])
     same_g = _tab([0x10000, 0x10000])

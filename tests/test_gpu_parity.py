@@ -594,6 +594,44 @@ def test_c_client_without_python_in_the_path(A, tmp_path, n, P, mode, three):
     assert_array_close(body[P * n:], ref.w_new, "w")
 
 
+@pytest.mark.parametrize("ranks,per_rank,n,mode", [(4, 1, 70_003, 0), (3, 1, 4099, 1), (2, 2, 300_001, 0),
+                                                     (4, 1, 14_000_003, 0)])
+def test_line_5_done_by_the_caller_as_on_several_gpus(A, ranks, per_rank, n, mode):
+    """The multi-GPU shape on one GPU: every "rank" has a plan, a workspace and a weight replica of its own for its
+    per_rank workers; the ranks exchange only their local pairs, here through a device-side average that stands in
+    for the all-reduce (summed in rank order in fp64, one rounding, as Algorithm 1 line 5 is defined).  With one
+    worker per rank this is Algorithm 1 as each worker runs it: checked against the oracle's per-replica step;
+    with several workers per rank each rank's w is the mean of its own workers' updates."""
+    P = ranks * per_rank
+    g, e, w = make_case(n + P, n, P)
+    plans = [A.a2sgd_plan(n, per_rank, mode) for _ in range(ranks)]
+    wss = [A.alloc_workspace(pl) for pl in plans]
+    gd, ed = [dev(x) for x in g], [dev(x) for x in e]
+    wd = [dev(w) for _ in range(ranks)]
+    pairs = torch.empty(ranks, 2 * per_rank, dtype=torch.float32, device="cuda")
+    for r in range(ranks):
+        sl = slice(r * per_rank, (r + 1) * per_rank)
+        A.a2sgd_local_averages(plans[r], gd[sl], ed[sl], wss[r])
+        A.a2sgd_export_local_means(plans[r], wss[r], pairs[r])
+    allp = pairs.view(P, 2).double()
+    gmu = (allp.sum(dim=0) / P).float().contiguous()  # the stand-in for the all-reduce (average) of 2 floats
+    for r in range(ranks):
+        sl = slice(r * per_rank, (r + 1) * per_rank)
+        A.a2sgd_import_global_means(plans[r], wss[r], gmu)
+        A.a2sgd_apply_and_update_error(plans[r], gd[sl], ed[sl], wd[r], 0.1, wss[r])
+    workers, gmu_ref, e_ref, w_ref = O.step_replicas(g, e, [w] * P, 0.1, mode)
+    assert abs(float(gmu[0]) - gmu_ref[0]) <= 1e-5 * abs(gmu_ref[0]) and abs(float(gmu[1]) - gmu_ref[1]) <= 1e-5 * abs(gmu_ref[1])
+    for r in range(ranks):
+        st, gm = A.a2sgd_read_stats(plans[r], wss[r])
+        for q in range(per_rank):
+            p = r * per_rank + q
+            assert (st[q].n_pos, st[q].n_neg, st[q].n_zero) == (workers[p].n_pos, workers[p].n_neg, workers[p].n_zero)
+            assert_array_close(ed[p].cpu().numpy(), e_ref[p], f"e[{p}]")
+        assert gm == (float(gmu[0]), float(gmu[1]))
+        mine = np.mean(np.stack([w_ref[r * per_rank + q].astype(np.float64) for q in range(per_rank)]), axis=0)
+        assert_array_close(wd[r].cpu().numpy(), mine.astype(f32), f"w of rank {r}")
+
+
 def test_device_info(A):
     info = A.a2sgd_device_info()
     assert info["compute_units"] >= 64 and info["total_memory_bytes"] > 64 << 30
