@@ -213,13 +213,25 @@ a2sgd_status_t a2sgd_replica_drift(const a2sgd_plan_t *plan, const float *const 
  * differ from its in the last bit (the sums are grouped differently) and w by an ulp; the errors once
  * materialised are those of a2sgd_step within that.
  * A workspace in lazy use carries state: between a2sgd_lazy_reset and a2sgd_lazy_materialize it must see no other
- * calls than a2sgd_lazy_step and a2sgd_read_stats.  s is required. */
+ * calls than the a2sgd_lazy_* ones, a2sgd_global_average, the export/import pair and a2sgd_read_stats.  s is
+ * required. */
 
 /* Declares that the buffers that will be passed as s hold true errors (for a fresh run: zeros): clears the local
  * means carried in the workspace.  Call once before the first a2sgd_lazy_step on a workspace. */
 a2sgd_status_t a2sgd_lazy_reset(const a2sgd_plan_t *plan, void *workspace, a2sgd_stream_t stream);
 
-/* One step of Algorithm 1's loop body (lines 3-7) on the lazy state. */
+/* Algorithm 1 line 3 on the lazy state: forms every worker's pending error, folds it into the gradient, stores the
+ * new v in s and leaves the local means, counts (and, in retained-error mode, sign bits) in the workspace.
+ * a2sgd_global_average, or a2sgd_export_local_means / a2sgd_import_global_means, follows. */
+a2sgd_status_t a2sgd_lazy_local_averages(const a2sgd_plan_t *plan, const float *const *g, float *const *s,
+                                         void *workspace, a2sgd_stream_t stream);
+
+/* Algorithm 1 lines 6-7 on the lazy state: updates w from the sign groups; s is only read. */
+a2sgd_status_t a2sgd_lazy_apply(const a2sgd_plan_t *plan, const float *const *s, float *w, float eta, void *workspace,
+                                a2sgd_stream_t stream);
+
+/* One step of Algorithm 1's loop body (lines 3-7) on the lazy state: a2sgd_lazy_local_averages,
+ * a2sgd_global_average and a2sgd_lazy_apply, in order. */
 a2sgd_status_t a2sgd_lazy_step(const a2sgd_plan_t *plan, const float *const *g, float *const *s, float *w, float eta,
                                void *workspace, a2sgd_stream_t stream);
 

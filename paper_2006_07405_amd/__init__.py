@@ -6,5 +6,5 @@ from .binding import (A2SGD_MAX_WORKERS, A2SGD_MODE_ALG1_LITERAL, A2SGD_MODE_RET
                       alloc_workspace, a2sgd_local_averages, a2sgd_global_average, a2sgd_apply_and_update_error,
                       a2sgd_step, a2sgd_read_stats, a2sgd_export_mask, a2sgd_dense_step,
                       a2sgd_apply_and_update_error_replicas, a2sgd_step_replicas, a2sgd_dense_step_replicas,
-                      a2sgd_replica_drift, a2sgd_lazy_reset, a2sgd_lazy_step, a2sgd_lazy_materialize, a2sgd_selftest_barrier, a2sgd_workspace_init, a2sgd_read_segment_stats, raw,
+                      a2sgd_replica_drift, a2sgd_lazy_reset, a2sgd_lazy_step, a2sgd_lazy_local_averages, a2sgd_lazy_apply, a2sgd_lazy_materialize, a2sgd_selftest_barrier, a2sgd_workspace_init, a2sgd_read_segment_stats, raw,
                       LIB_PATH)

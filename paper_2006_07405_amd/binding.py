@@ -69,6 +69,8 @@ def _load():
     L.a2sgd_replica_drift.argtypes = [vp, tab, vp, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     L.a2sgd_lazy_reset.argtypes = [vp, vp, vp]
     L.a2sgd_lazy_step.argtypes = [vp, tab, tab, vp, C.c_float, vp, vp]
+    L.a2sgd_lazy_local_averages.argtypes = [vp, tab, tab, vp, vp]
+    L.a2sgd_lazy_apply.argtypes = [vp, tab, vp, C.c_float, vp, vp]
     L.a2sgd_lazy_materialize.argtypes = [vp, tab, vp, vp]
     L.a2sgd_selftest_barrier.argtypes = [vp, vp]
     L.a2sgd_selftest_barrier.restype = C.c_int
@@ -310,6 +312,16 @@ def a2sgd_lazy_step(plan: Plan, g, s, w: torch.Tensor, eta: float, workspace: to
     _check(raw.a2sgd_lazy_step(plan.handle, _table(plan, g, "g"), _table(plan, s, "s"),
                                _dev_ptr(w, plan.n, torch.float32, "w"), C.c_float(eta), _workspace(plan, workspace),
                                _stream(stream)), "a2sgd_lazy_step")
+
+
+def a2sgd_lazy_local_averages(plan: Plan, g, s, workspace: torch.Tensor, stream=None) -> None:
+    _check(raw.a2sgd_lazy_local_averages(plan.handle, _table(plan, g, "g"), _table(plan, s, "s"),
+                                         _workspace(plan, workspace), _stream(stream)), "a2sgd_lazy_local_averages")
+
+
+def a2sgd_lazy_apply(plan: Plan, s, w: torch.Tensor, eta: float, workspace: torch.Tensor, stream=None) -> None:
+    _check(raw.a2sgd_lazy_apply(plan.handle, _table(plan, s, "s"), _dev_ptr(w, plan.n, torch.float32, "w"),
+                                C.c_float(eta), _workspace(plan, workspace), _stream(stream)), "a2sgd_lazy_apply")
 
 
 def a2sgd_lazy_materialize(plan: Plan, s, workspace: torch.Tensor, stream=None) -> None:

@@ -676,9 +676,55 @@ a2sgd_status_t a2sgd_lazy_reset(const a2sgd_plan_t *plan, void *workspace, a2sgd
     return dev(launch_lazy_reset(*plan, workspace, static_cast<hipStream_t>(stream)));
 }
 
+a2sgd_status_t a2sgd_lazy_local_averages(const a2sgd_plan_t *plan, const float *const *g, float *const *s,
+                                         void *workspace, a2sgd_stream_t stream)
+{
+    if (plan == nullptr || segmented(plan))
+        return A2SGD_ERR_INVALID_ARG;
+    bool has_g = false, has_s = false;
+    a2sgd_status_t st = check_table(g, plan->P, true, &has_g);
+    if (st != A2SGD_OK)
+        return st;
+    if ((st = check_table(s, plan->P, true, &has_s)) != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(workspace)) != A2SGD_OK)
+        return st;
+    if ((st = check_step_ranges(plan, g, s, nullptr, nullptr, workspace)) != A2SGD_OK)
+        return st;
+    PtrTable tab;
+    fill_table(tab, plan->P, g, s);
+    plan->last_token = 0;
+    return dev(launch_lazy_partials(*plan, tab, workspace, static_cast<hipStream_t>(stream)));
+}
+
+a2sgd_status_t a2sgd_lazy_apply(const a2sgd_plan_t *plan, const float *const *s, float *w, float eta, void *workspace,
+                                a2sgd_stream_t stream)
+{
+    if (plan == nullptr || segmented(plan))
+        return A2SGD_ERR_INVALID_ARG;
+    bool has_s = false;
+    a2sgd_status_t st = check_table(s, plan->P, true, &has_s);
+    if (st != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(w)) != A2SGD_OK)
+        return st;
+    if ((st = check_buffer(workspace)) != A2SGD_OK)
+        return st;
+    Ranges rg;
+    rg.add_table(s, plan->P, plan->n, false);
+    rg.add(w, 4 * plan->n, true);
+    rg.add(workspace, plan->workspace_bytes, true);
+    if (!rg.disjoint())
+        return A2SGD_ERR_INVALID_ARG;
+    PtrTable tab;
+    fill_table(tab, plan->P, s, s);  // the pass reads the state buffers only
+    return dev(launch_lazy_apply(*plan, tab, w, eta, workspace, static_cast<hipStream_t>(stream)));
+}
+
 a2sgd_status_t a2sgd_lazy_step(const a2sgd_plan_t *plan, const float *const *g, float *const *s, float *w, float eta,
                                void *workspace, a2sgd_stream_t stream)
 {
+    // validate everything first so that a failed step has enqueued nothing
     if (plan == nullptr || segmented(plan))
         return A2SGD_ERR_INVALID_ARG;
     bool has_g = false, has_s = false;
@@ -693,15 +739,11 @@ a2sgd_status_t a2sgd_lazy_step(const a2sgd_plan_t *plan, const float *const *g, 
         return st;
     if ((st = check_step_ranges(plan, g, s, w, nullptr, workspace)) != A2SGD_OK)
         return st;
-    PtrTable tab;
-    fill_table(tab, plan->P, g, s);
-    plan->last_token = 0;
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    if ((st = dev(launch_lazy_partials(*plan, tab, workspace, hs))) != A2SGD_OK)
+    if ((st = a2sgd_lazy_local_averages(plan, g, s, workspace, stream)) != A2SGD_OK)
         return st;
-    if ((st = dev(launch_global_average(*plan, workspace, hs))) != A2SGD_OK)
+    if ((st = a2sgd_global_average(plan, workspace, stream)) != A2SGD_OK)
         return st;
-    return dev(launch_lazy_apply(*plan, tab, w, eta, workspace, hs));
+    return a2sgd_lazy_apply(plan, s, w, eta, workspace, stream);
 }
 
 a2sgd_status_t a2sgd_lazy_materialize(const a2sgd_plan_t *plan, float *const *s, void *workspace,

@@ -619,7 +619,28 @@ def test_line_5_done_by_the_caller_as_on_several_gpus(A, ranks, per_rank, n, mod
         sl = slice(r * per_rank, (r + 1) * per_rank)
         A.a2sgd_import_global_means(plans[r], wss[r], gmu)
         A.a2sgd_apply_and_update_error(plans[r], gd[sl], ed[sl], wd[r], 0.1, wss[r])
+    # the same exchange on the lazy state (fresh buffers; materialised afterwards): same weights, same errors
+    sd = [dev(x) for x in e]
+    wl_ = [dev(w) for _ in range(ranks)]
+    wsl = [A.alloc_workspace(pl) for pl in plans]
+    pairs_l = torch.empty_like(pairs)
+    for r in range(ranks):
+        sl = slice(r * per_rank, (r + 1) * per_rank)
+        A.a2sgd_lazy_reset(plans[r], wsl[r])
+        A.a2sgd_lazy_local_averages(plans[r], gd[sl], sd[sl], wsl[r])
+        A.a2sgd_export_local_means(plans[r], wsl[r], pairs_l[r])
+    gmu_l = (pairs_l.view(P, 2).double().sum(dim=0) / P).float().contiguous()
+    for r in range(ranks):
+        sl = slice(r * per_rank, (r + 1) * per_rank)
+        A.a2sgd_import_global_means(plans[r], wsl[r], gmu_l)
+        A.a2sgd_lazy_apply(plans[r], sd[sl], wl_[r], 0.1, wsl[r])
+        A.a2sgd_lazy_materialize(plans[r], sd[sl], wsl[r])
     workers, gmu_ref, e_ref, w_ref = O.step_replicas(g, e, [w] * P, 0.1, mode)
+    for r in range(ranks):
+        mine = np.mean(np.stack([w_ref[r * per_rank + q].astype(np.float64) for q in range(per_rank)]), axis=0)
+        assert_array_close(wl_[r].cpu().numpy(), mine.astype(f32), f"lazy w of rank {r}")
+        for q in range(per_rank):
+            assert_array_close(sd[r * per_rank + q].cpu().numpy(), e_ref[r * per_rank + q], f"lazy e[{r * per_rank + q}]")
     assert abs(float(gmu[0]) - gmu_ref[0]) <= 1e-5 * abs(gmu_ref[0]) and abs(float(gmu[1]) - gmu_ref[1]) <= 1e-5 * abs(gmu_ref[1])
     for r in range(ranks):
         st, gm = A.a2sgd_read_stats(plans[r], wss[r])
