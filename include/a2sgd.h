@@ -51,7 +51,10 @@ typedef enum {
     A2SGD_ERR_INVALID_ARG = 1, /* NULL where a pointer is required, n == 0, P out of range, bad mode */
     A2SGD_ERR_ALIGNMENT = 2,   /* a device pointer is not 16-byte aligned */
     A2SGD_ERR_DEVICE = 3,      /* a HIP call or kernel launch failed */
-    A2SGD_ERR_NOMEM = 4        /* host allocation of the plan failed */
+    A2SGD_ERR_NOMEM = 4,       /* host allocation of the plan failed */
+    A2SGD_ERR_WORKSPACE_TOO_SMALL = 5, /* a2sgd_workspace_check: fewer bytes than a2sgd_workspace_bytes */
+    A2SGD_ERR_WORKSPACE_STATE = 6      /* a plan with tensors found a workspace that a2sgd_workspace_init has not
+                                          prepared for it; the calls since then have computed nothing */
 } a2sgd_status_t;
 
 typedef enum {
@@ -81,7 +84,9 @@ typedef struct {
     uint32_t pooled_means;      /* with num_segments >= 1: 0 = one pair of means per worker and tensor; 1 = one pair
                                    per worker over all tensors together (the paper's whole-model means on a buffer
                                    that has padding).  Must be 0 when num_segments is 0 */
-    uint32_t reserved;          /* 0 */
+    int32_t device;             /* HIP device index the plan is made for: every call that enqueues work first checks
+                                   that this device is the current one (else A2SGD_ERR_DEVICE, nothing enqueued).
+                                   -1: no check, the calls run on whichever device is current */
 } a2sgd_config_t;
 
 /* Per-worker result of the reduction (Sec. 3.1; the pair (mu_pos, mu_neg) is the worker's 64-bit message of
@@ -97,7 +102,10 @@ typedef struct {
 } a2sgd_global_stats_t;
 
 /* Host only, launches nothing.  Validates cfg and fixes the launch geometry and the workspace layout.
- * *out_plan is written only on success and must be released with a2sgd_plan_destroy. */
+ * *out_plan is written only on success and must be released with a2sgd_plan_destroy.
+ * Thread safety: different plans may be used from different host threads at once.  One plan must not be used by
+ * two host threads at the same time (a call notes in the plan what it enqueued), and must not be destroyed
+ * while work enqueued with it is still running. */
 a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan);
 a2sgd_status_t a2sgd_plan_destroy(a2sgd_plan_t *plan);
 
@@ -106,6 +114,11 @@ a2sgd_status_t a2sgd_plan_destroy(a2sgd_plan_t *plan);
  * one call of a step to the next.  For a whole-model plan it includes the records of the lazy calls' reduction
  * pass (40 bytes per 2048 elements and worker).  Returns 0 for a NULL plan. */
 size_t a2sgd_workspace_bytes(const a2sgd_plan_t *plan);
+
+/* Host only.  The step calls take a workspace pointer without a size; a caller that wants the size checked passes
+ * the buffer here once: A2SGD_ERR_INVALID_ARG for a NULL plan or pointer, A2SGD_ERR_ALIGNMENT, and
+ * A2SGD_ERR_WORKSPACE_TOO_SMALL if `bytes` is less than a2sgd_workspace_bytes(plan). */
+a2sgd_status_t a2sgd_workspace_check(const a2sgd_plan_t *plan, const void *workspace, size_t bytes);
 
 /* Algorithm 1 line 3.  For every worker p: one pass over v^p = fl32(g^p + e^p) giving n_pos = #{v >= 0},
  * n_neg = #{v < 0}, the two sums, and from them mu_pos = fl32(S_pos / n_pos), mu_neg = fl32(S_neg / n_neg)
@@ -131,10 +144,13 @@ a2sgd_status_t a2sgd_apply_and_update_error(const a2sgd_plan_t *plan, const floa
  * in order (to the tolerance of the sums' grouping: the counts are identical, the fp64 sums are combined in
  * another fixed order).  When g, e and w together are small enough to stay in the on-chip caches (below 192 MiB)
  * the step is ONE kernel launch with a grid-wide barrier inside; larger models run the three passes.  The
- * barrier's cell is library-owned device memory, one of 64 cells handed out to plans in turn: calls with the
- * same plan must not overlap (they share the workspace anyway), and at most 64 plans may have a step in flight
- * on one GPU at once.  The barrier's wait is bounded; should it ever run out, the step's outputs are invalid,
- * a2sgd_read_stats returns A2SGD_ERR_DEVICE, and that cell refuses further steps. */
+ * barrier's cell is library-owned device memory, one of 64 cells: such a plan owns one from a2sgd_plan to
+ * a2sgd_plan_destroy, so no two live plans share a cell and their steps may run at the same time on different
+ * streams; a plan made while all 64 are taken runs the three passes, as does any plan on a device with fewer
+ * compute units than its grid has workgroups (a2sgd_plan_single_launch_cell tells).  Calls with the same plan must
+ * not overlap (they share the workspace anyway).  The barrier's wait is bounded; should it ever run out, that
+ * step's outputs are invalid and later single-launch steps of the plan do nothing, until a2sgd_read_stats reports
+ * it once with A2SGD_ERR_DEVICE; from then on the plan runs the three passes. */
 a2sgd_status_t a2sgd_step(const a2sgd_plan_t *plan, const float *const *g, float *const *e, float *w, float eta,
                           void *workspace, a2sgd_stream_t stream);
 
@@ -165,8 +181,11 @@ a2sgd_status_t a2sgd_dense_step(const a2sgd_plan_t *plan, const float *const *g,
  * Not available on such a plan (A2SGD_ERR_INVALID_ARG): the replica calls and the lazy calls, and a2sgd_read_stats
  * unless the means are pooled.  The workspace of such a plan holds static lookup tables: */
 
-/* Uploads the plan's segment tables into the workspace.  Required once per workspace, before its first use, when
- * the plan has num_segments >= 1; a no-op otherwise.  Asynchronous on `stream`; the plan must outlive the copy. */
+/* Uploads the plan's segment tables into the workspace, and last a tag that identifies them.  Required once per
+ * workspace, before its first use, when the plan has num_segments >= 1; a no-op otherwise.  Asynchronous on
+ * `stream`; the plan must outlive the copy.  A step call on a workspace that does not carry this plan's tag reads
+ * no table and writes no output: its kernels exit at once and leave a mark, which a2sgd_read_segment_stats (and
+ * a2sgd_read_stats with pooled means) reports as A2SGD_ERR_WORKSPACE_STATE until a2sgd_workspace_init has run. */
 a2sgd_status_t a2sgd_workspace_init(const a2sgd_plan_t *plan, void *workspace, a2sgd_stream_t stream);
 
 /* Per-tensor results of the last completed reduction: out_workers[p * S + s] for worker p and tensor s (host array
@@ -260,12 +279,17 @@ a2sgd_status_t a2sgd_import_global_means(const a2sgd_plan_t *plan, void *workspa
 /* Diagnostic: exercises the grid-wide barrier of the single-launch step on a cell of its own.  First 128
  * workgroups must all pass one barrier; then 128 workgroups wait, with a limit of 64 polls, for an arrival that
  * never comes: every one of them must give up, exit normally and leave the cell marked failed.  Returns A2SGD_OK
- * if both behaved, A2SGD_ERR_DEVICE otherwise.  `scratch` is at least 4 KiB of device memory (a workspace
+ * if both behaved, A2SGD_ERR_DEVICE otherwise.  `buffer` is at least 4 KiB of device memory (a workspace
  * will do; its contents are overwritten).  Synchronises `stream`. */
-a2sgd_status_t a2sgd_selftest_barrier(void *scratch, a2sgd_stream_t stream);
+a2sgd_status_t a2sgd_selftest_barrier(void *buffer, a2sgd_stream_t stream);
 
 /* Geometry the plan chose, for reports: blocks per worker of the first-level reduction. */
 uint32_t a2sgd_plan_blocks_per_worker(const a2sgd_plan_t *plan);
+
+/* The grid-barrier cell (0..63) that a2sgd_step's single launch uses with this plan, or -1 if the plan runs the
+ * three passes (model too large for the caches, a plan with tensors, no free cell when it was made, or a step
+ * that gave up at its barrier).  Host call. */
+int32_t a2sgd_plan_single_launch_cell(const a2sgd_plan_t *plan);
 
 /* What the current HIP device reports about itself, for benchmark reports: compute units, memory clock (kHz) and
  * bus width (bits), total device memory and L2 size in bytes.  (An MI355X reports 2,000,000 kHz and 8192 bits; its

@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liba2sgd.so")
 
 A2SGD_MAX_WORKERS = 64
-A2SGD_OK, A2SGD_ERR_INVALID_ARG, A2SGD_ERR_ALIGNMENT, A2SGD_ERR_DEVICE, A2SGD_ERR_NOMEM = range(5)
+(A2SGD_OK, A2SGD_ERR_INVALID_ARG, A2SGD_ERR_ALIGNMENT, A2SGD_ERR_DEVICE, A2SGD_ERR_NOMEM, A2SGD_ERR_WORKSPACE_TOO_SMALL,
+ A2SGD_ERR_WORKSPACE_STATE) = range(7)
 A2SGD_MODE_RETAINED_ERROR, A2SGD_MODE_ALG1_LITERAL = 0, 1
 
 
@@ -25,7 +26,7 @@ class a2sgd_config_t(C.Structure):
     _fields_ = [("n", C.c_uint64), ("num_workers", C.c_uint32), ("mode", C.c_int32),
                 ("blocks_per_worker", C.c_uint32), ("num_segments", C.c_uint32),
                 ("seg_length", C.POINTER(C.c_uint64)), ("seg_offset", C.POINTER(C.c_uint64)),
-                ("pooled_means", C.c_uint32), ("reserved", C.c_uint32)]
+                ("pooled_means", C.c_uint32), ("device", C.c_int32)]
 
 
 class a2sgd_worker_stats_t(C.Structure):
@@ -56,6 +57,10 @@ def _load():
     L.a2sgd_workspace_bytes.restype = C.c_size_t
     L.a2sgd_plan_blocks_per_worker.argtypes = [vp]
     L.a2sgd_plan_blocks_per_worker.restype = C.c_uint32
+    L.a2sgd_plan_single_launch_cell.argtypes = [vp]
+    L.a2sgd_plan_single_launch_cell.restype = C.c_int32
+    L.a2sgd_workspace_check.argtypes = [vp, vp, C.c_size_t]
+    L.a2sgd_workspace_check.restype = C.c_int
     L.a2sgd_local_averages.argtypes = [vp, tab, tab, vp, vp]
     L.a2sgd_global_average.argtypes = [vp, vp, vp]
     L.a2sgd_apply_and_update_error.argtypes = [vp, tab, tab, vp, C.c_float, vp, vp]
@@ -145,26 +150,30 @@ def _table(plan: Plan, ts: Optional[Sequence[torch.Tensor]], what: str):
 
 
 def _workspace(plan: Plan, ws: torch.Tensor) -> int:
-    need = plan.workspace_bytes
     if not (isinstance(ws, torch.Tensor) and ws.is_cuda and ws.is_contiguous()):
         raise TypeError("workspace: expected a contiguous CUDA tensor")
-    if ws.numel() * ws.element_size() < need:
-        raise ValueError(f"workspace: {ws.numel() * ws.element_size()} bytes, the plan needs {need}")
+    _check(raw.a2sgd_workspace_check(plan.handle, ws.data_ptr(), ws.numel() * ws.element_size()), "workspace")
     return ws.data_ptr()
+
+
+def a2sgd_workspace_check(plan: Plan, workspace: torch.Tensor) -> None:
+    """Raises A2sgdError (A2SGD_ERR_WORKSPACE_TOO_SMALL, ...) unless the tensor can serve as the plan's workspace."""
+    _workspace(plan, workspace)
 
 
 def a2sgd_plan(n: int, num_workers: int, mode: int = A2SGD_MODE_RETAINED_ERROR, blocks_per_worker: int = 0,
                seg_lengths: Optional[Sequence[int]] = None, seg_offsets: Optional[Sequence[int]] = None,
-               pooled_means: bool = False) -> Plan:
+               pooled_means: bool = False, device: int = -1) -> Plan:
     """seg_lengths: tensor sizes in address order; None = the whole range [0, n) with whole-model means.
     seg_offsets: their start indices (None = packed back to back from 0, sizes summing to n); elements outside every
-    tensor are padding.  pooled_means: one pair of means per worker over all tensors instead of one per tensor."""
+    tensor are padding.  pooled_means: one pair of means per worker over all tensors instead of one per tensor.
+    device: HIP device index that every launching call must find current, or -1 for no check."""
     S = len(seg_lengths) if seg_lengths is not None else 0
     arr = (C.c_uint64 * S)(*[int(x) for x in seg_lengths]) if S else None
     if seg_offsets is not None and len(seg_offsets) != S:
         raise ValueError("seg_offsets: one start index per tensor")
     off = (C.c_uint64 * S)(*[int(x) for x in seg_offsets]) if (S and seg_offsets is not None) else None
-    cfg = a2sgd_config_t(n, num_workers, mode, blocks_per_worker, S, arr, off, 1 if pooled_means else 0, 0)
+    cfg = a2sgd_config_t(n, num_workers, mode, blocks_per_worker, S, arr, off, 1 if pooled_means else 0, device)
     h = C.c_void_p()
     _check(raw.a2sgd_plan(C.byref(cfg), C.byref(h)), "a2sgd_plan")
     return Plan(h.value, n, num_workers, mode, S)
@@ -182,6 +191,10 @@ def a2sgd_device_info() -> dict:
 
 def a2sgd_plan_blocks_per_worker(plan: Plan) -> int:
     return int(raw.a2sgd_plan_blocks_per_worker(plan.handle))
+
+
+def a2sgd_plan_single_launch_cell(plan: Plan) -> int:
+    return int(raw.a2sgd_plan_single_launch_cell(plan.handle))
 
 
 def alloc_workspace(plan: Plan, device="cuda") -> torch.Tensor:

@@ -1,7 +1,10 @@
 // Host side of the C ABI declared in include/a2sgd.h: plan construction, argument validation, and the
 // sequencing of the kernels of one step.  No device memory is allocated here.
+#include <stddef.h>
+
 #include <algorithm>
 #include <atomic>
+#include <mutex>
 #include <new>
 #include <utility>
 #include <vector>
@@ -15,11 +18,15 @@ namespace {
 // One workgroup of the apply-type passes covers as little as 64 float4 groups and a grid holds fewer than 2^31
 // workgroups: n up to 2^38 (1 TiB per buffer) keeps every grid below 2^30.
 constexpr uint64_t kMaxN = 1ull << 38;
-// Compute units of one MI355X.  Both big passes run fastest with few wavefronts per compute unit, each with
-// many 128-bit loads in flight (about 60 KiB in flight per CU); more wavefronts only widen the span of addresses
-// that is open at once and HBM efficiency drops.  The reduction keeps 2 workgroups of 256 threads per CU.
+// Compute units of one MI355X, for the geometry that a plan fixes on the host.  Both big passes run fastest with
+// few wavefronts per compute unit, each with many 128-bit loads in flight (about 60 KiB in flight per CU); more
+// wavefronts only widen the span of addresses that is open at once and HBM efficiency drops.  The reduction keeps
+// 2 workgroups of 256 threads per CU.
 constexpr uint32_t kComputeUnits = 256;
 constexpr uint32_t kReduceBlocksPerCU = 2;
+// The single-launch step asks for at most this many workgroups of kFusedBlock threads; a2sgd_step launches it only
+// on a device that has at least as many compute units as the plan's grid has workgroups (one per CU, where four
+// would fit: the whole grid is resident at once, which its grid-wide barrier relies on).
 constexpr uint32_t kFusedGridMax = 256;
 
 // The apply pass runs single-wavefront workgroups and caps how many share a CU through its dynamic-LDS request
@@ -158,8 +165,97 @@ void build_segments(a2sgd_plan_t &pl, uint32_t S, const uint64_t *len, const uin
 
 inline bool segmented(const a2sgd_plan_t *plan) { return plan->seg.S > 0; }
 
-std::atomic<uint32_t> g_next_slot{0};
+// Checksum of a per-tensor plan's tables and of the sizes that fix where they lie in the workspace (FNV-1a over
+// 64-bit words).  a2sgd_workspace_init leaves it in the workspace; the kernels that index through the tables
+// compare it first.  Never 0, which is what fresh device memory most often holds.
+uint64_t tag_words(uint64_t h, const void *data, size_t bytes)
+{
+    const unsigned char *p = static_cast<const unsigned char *>(data);
+    for (size_t i = 0; i < bytes; i += 8) {
+        uint64_t word = 0;
+        for (size_t k = 0; k < 8 && i + k < bytes; ++k)
+            word |= static_cast<uint64_t>(p[i + k]) << (8 * k);
+        h = (h ^ word) * 0x100000001b3ull;
+    }
+    return h;
+}
+
+uint64_t tables_tag(const a2sgd_plan_t &pl)
+{
+    const SegPlan &sp = pl.seg;
+    const uint64_t sizes[] = {pl.n, pl.P, sp.S, sp.item.size(), sp.blocks, sp.pooled ? 1u : 0u, sp.end};
+    uint64_t h = 0xcbf29ce484222325ull;
+    h = tag_words(h, sizes, sizeof(sizes));
+    h = tag_words(h, sp.seg_start.data(), 8 * sp.seg_start.size());
+    h = tag_words(h, sp.seg_end.data(), 8 * sp.seg_end.size());
+    h = tag_words(h, sp.item.data(), sizeof(SegItem) * sp.item.size());
+    h = tag_words(h, sp.item_lo.data(), 4 * sp.item_lo.size());
+    h = tag_words(h, sp.coarse.data(), 4 * sp.coarse.size());
+    h = tag_words(h, sp.sched_lo.data(), 4 * sp.sched_lo.size());
+    h = tag_words(h, sp.sched_item.data(), 4 * sp.sched_item.size());
+    return h != 0 ? h : 1;
+}
+
+// The grid-barrier cells of the single-launch step: kBarrierSlots of them in device memory (every GPU has its own
+// copy of the array; the hand-out is per process, which is the stricter rule).  A plan that can use the single
+// launch takes a free cell when it is made and gives it back when it is destroyed, so no two live plans ever
+// share one; a plan that finds none runs the three passes, which give the same results.
+class CellPool {
+public:
+    int take()
+    {
+        std::lock_guard<std::mutex> lock(mutex_);
+        for (uint32_t c = 0; c < kBarrierSlots; ++c)
+            if (!(busy_ >> c & 1ull)) {
+                busy_ |= 1ull << c;
+                return static_cast<int>(c);
+            }
+        return -1;
+    }
+    void give(int c)
+    {
+        std::lock_guard<std::mutex> lock(mutex_);
+        if (c >= 0 && c < static_cast<int>(kBarrierSlots))
+            busy_ &= ~(1ull << c);
+    }
+
+private:
+    static_assert(kBarrierSlots == 64, "one bit per cell");
+    std::mutex mutex_;
+    uint64_t busy_ = 0;
+};
+CellPool g_cells;
 std::atomic<uint32_t> g_next_token{1};
+
+// Compute units of the current device, asked once per device; 0 if it cannot be told.
+uint32_t current_device_compute_units()
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<uint32_t> cached[kMaxDevices];
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices)
+        return 0;
+    uint32_t cu = cached[device].load(std::memory_order_relaxed);
+    if (cu == 0) {
+        int value = 0;
+        if (hipDeviceGetAttribute(&value, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || value <= 0)
+            return 0;
+        cu = static_cast<uint32_t>(value);
+        cached[device].store(cu, std::memory_order_relaxed);
+    }
+    return cu;
+}
+
+// A plan made for one device refuses to launch while another one is current.
+a2sgd_status_t check_device(const a2sgd_plan_t *plan)
+{
+    if (plan->device < 0)
+        return A2SGD_OK;
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device != plan->device)
+        return A2SGD_ERR_DEVICE;
+    return A2SGD_OK;
+}
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -251,6 +347,15 @@ struct Ranges {
     }
 };
 
+// What the kernels of a plan with tensors leave in the workspace header about the tables: the tag of the tables
+// that a2sgd_workspace_init uploaded, and whether a kernel has refused to use them since.
+struct SegState {
+    uint64_t tag;
+    uint32_t fault;
+    uint32_t reserved;
+};
+static_assert(offsetof(WsHeader, seg_fault) == offsetof(WsHeader, seg_tag) + 8, "SegState mirrors the header's tail");
+
 inline a2sgd_status_t dev(hipError_t err) { return err == hipSuccess ? A2SGD_OK : A2SGD_ERR_DEVICE; }
 
 // Validation shared by the calls that take g and e.  In retained-error mode e is required.
@@ -263,6 +368,13 @@ a2sgd_status_t check_g_e(const a2sgd_plan_t *plan, const float *const *g, const 
     if (st != A2SGD_OK)
         return st;
     return check_table(e, plan->P, plan->mode == A2SGD_MODE_RETAINED_ERROR, has_e);
+}
+
+// True if a2sgd_step may take the single launch now: the plan has a grid and a cell for it, and the current device
+// holds the whole grid at once.
+bool single_launch_now(const a2sgd_plan_t *plan)
+{
+    return plan->fused_grid != 0 && plan->barrier_cell >= 0 && plan->fused_grid <= current_device_compute_units();
 }
 
 // The aliasing rule for a call that reads g, updates e (if given) and w (one vector, or one per worker) in place
@@ -297,7 +409,7 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
         return A2SGD_ERR_INVALID_ARG;
     if (cfg->num_segments == 0 && (cfg->pooled_means != 0 || cfg->seg_offset != nullptr))
         return A2SGD_ERR_INVALID_ARG;
-    if (cfg->pooled_means > 1 || cfg->reserved != 0)
+    if (cfg->pooled_means > 1 || cfg->device < -1)
         return A2SGD_ERR_INVALID_ARG;
     if (cfg->num_segments >= 1) {
         if (cfg->seg_length == nullptr)
@@ -323,19 +435,25 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
     pl->apply.up = pl->P >= 8 ? 8 : pl->P >= 4 ? 4 : pl->P >= 2 ? 2 : 1;
     pl->apply.lds_bytes = pl->streaming ? apply_lds_bytes(pl->P) : 0;
     pl->apply.dense_lds_bytes = pl->streaming ? dense_lds_bytes(pl->P) : 0;
-    // Single-launch step while everything fits the caches: one workgroup of kFusedBlock threads per 4096
-    // elements, at most one per two CUs, all resident at once (the kernel's grid-wide barrier relies on that).
-    pl->barrier_slot = g_next_slot.fetch_add(1) % kBarrierSlots;
+    pl->device = cfg->device;
+    // Single-launch step while everything fits the caches: one workgroup of kFusedBlock threads per 2048 elements,
+    // at most kFusedGridMax of them.  It needs a grid-barrier cell of its own; without one the plan runs the three
+    // passes.
+    pl->barrier_cell = -1;
     pl->last_token = 0;
     pl->fused_grid = 0;
-    if (!pl->streaming) {
+    if (!pl->streaming && cfg->num_segments == 0 && (pl->barrier_cell = g_cells.take()) >= 0) {
         const uint64_t want = (pl->n + 4 * kFusedBlock - 1) / (4 * kFusedBlock);
         pl->fused_grid = static_cast<uint32_t>(want < kFusedGridMax ? want : kFusedGridMax);
     }
-    const uint32_t rows = pl->B > pl->fused_grid ? pl->B : pl->fused_grid;
+    // the records have room for the single launch's grid whether or not this plan got a cell, so that the size of
+    // the workspace does not depend on how many other plans are alive
+    const uint64_t fused_rows = pl->streaming ? 0 : std::min<uint64_t>((pl->n + 4 * kFusedBlock - 1) / (4 * kFusedBlock), kFusedGridMax);
+    const uint32_t rows = pl->B > fused_rows ? pl->B : static_cast<uint32_t>(fused_rows);
     const size_t partials = 5ull * 8ull * pl->P * rows;
     const size_t drift = 2ull * 8ull * pl->P * (kDriftBlocks + 1);  // the drift diagnostic reuses the same region
     pl->workspace_bytes = kHeaderBytes + (partials > drift ? partials : drift);
+    pl->eager_bytes = pl->workspace_bytes;
     pl->lazy_blocks = pl->lazy_folded = 0;
     pl->lazy_offset = pl->lazy_sign_offset = 0;
     if (cfg->num_segments == 0) {
@@ -351,12 +469,13 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
     if (cfg->num_segments >= 1) {
         try {
             build_segments(*pl, cfg->num_segments, cfg->seg_length, cfg->seg_offset, cfg->pooled_means != 0);
+            pl->seg.tag = tables_tag(*pl);
         } catch (const std::bad_alloc &) {
+            g_cells.give(pl->barrier_cell);
             delete pl;
             return A2SGD_ERR_NOMEM;
         }
-        pl->fused_grid = 0;  // the single-launch step knows whole-model means only
-        pl->workspace_bytes = pl->seg.end;
+        pl->workspace_bytes = pl->seg.end;  // the single-launch step knows whole-model means only: no grid, no cell
     }
     *out_plan = pl;
     return A2SGD_OK;
@@ -364,13 +483,30 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
 
 a2sgd_status_t a2sgd_plan_destroy(a2sgd_plan_t *plan)
 {
+    if (plan != nullptr)
+        g_cells.give(plan->barrier_cell);
     delete plan;
     return A2SGD_OK;
 }
 
 size_t a2sgd_workspace_bytes(const a2sgd_plan_t *plan) { return plan ? plan->workspace_bytes : 0; }
 
+a2sgd_status_t a2sgd_workspace_check(const a2sgd_plan_t *plan, const void *workspace, size_t bytes)
+{
+    if (plan == nullptr)
+        return A2SGD_ERR_INVALID_ARG;
+    a2sgd_status_t st = check_buffer(workspace);
+    if (st != A2SGD_OK)
+        return st;
+    return bytes >= plan->workspace_bytes ? A2SGD_OK : A2SGD_ERR_WORKSPACE_TOO_SMALL;
+}
+
 uint32_t a2sgd_plan_blocks_per_worker(const a2sgd_plan_t *plan) { return plan ? plan->B : 0; }
+
+int32_t a2sgd_plan_single_launch_cell(const a2sgd_plan_t *plan)
+{
+    return plan != nullptr && plan->fused_grid != 0 ? plan->barrier_cell : -1;
+}
 
 a2sgd_status_t a2sgd_local_averages(const a2sgd_plan_t *plan, const float *const *g, const float *const *e,
                                     void *workspace, a2sgd_stream_t stream)
@@ -387,6 +523,8 @@ a2sgd_status_t a2sgd_local_averages(const a2sgd_plan_t *plan, const float *const
     rg.add(workspace, plan->workspace_bytes, true);
     if (!rg.disjoint())
         return A2SGD_ERR_INVALID_ARG;
+    if ((st = check_device(plan)) != A2SGD_OK)
+        return st;
     PtrTable tab;
     fill_table(tab, plan->P, g, has_e ? e : nullptr);
     plan->last_token = 0;
@@ -408,6 +546,8 @@ a2sgd_status_t a2sgd_global_average(const a2sgd_plan_t *plan, void *workspace, a
     a2sgd_status_t st = check_buffer(workspace);
     if (st != A2SGD_OK)
         return st;
+    if ((st = check_device(plan)) != A2SGD_OK)
+        return st;
     if (segmented(plan))
         return dev(launch_seg_global(*plan, workspace, static_cast<hipStream_t>(stream)));
     return dev(launch_global_average(*plan, workspace, static_cast<hipStream_t>(stream)));
@@ -420,6 +560,8 @@ a2sgd_status_t a2sgd_export_local_means(const a2sgd_plan_t *plan, const void *wo
         return A2SGD_ERR_INVALID_ARG;
     if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(out) & 3u) != 0)
         return A2SGD_ERR_ALIGNMENT;
+    if (check_device(plan) != A2SGD_OK)
+        return A2SGD_ERR_DEVICE;
     return dev(launch_export_local_means(*plan, workspace, out, static_cast<hipStream_t>(stream)));
 }
 
@@ -430,6 +572,8 @@ a2sgd_status_t a2sgd_import_global_means(const a2sgd_plan_t *plan, void *workspa
         return A2SGD_ERR_INVALID_ARG;
     if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(gmu) & 3u) != 0)
         return A2SGD_ERR_ALIGNMENT;
+    if (check_device(plan) != A2SGD_OK)
+        return A2SGD_ERR_DEVICE;
     plan->last_token = 0;
     return dev(launch_import_global_means(*plan, workspace, gmu, static_cast<hipStream_t>(stream)));
 }
@@ -446,6 +590,8 @@ a2sgd_status_t a2sgd_apply_and_update_error(const a2sgd_plan_t *plan, const floa
     if ((st = check_buffer(workspace)) != A2SGD_OK)
         return st;
     if ((st = check_step_ranges(plan, g, has_e ? e : nullptr, w, nullptr, workspace)) != A2SGD_OK)
+        return st;
+    if ((st = check_device(plan)) != A2SGD_OK)
         return st;
     PtrTable tab;
     fill_table(tab, plan->P, g, has_e ? e : nullptr);
@@ -468,7 +614,9 @@ a2sgd_status_t a2sgd_step(const a2sgd_plan_t *plan, const float *const *g, float
         return st;
     if ((st = check_step_ranges(plan, g, has_e ? e : nullptr, w, nullptr, workspace)) != A2SGD_OK)
         return st;
-    if (plan->fused_grid != 0) {
+    if ((st = check_device(plan)) != A2SGD_OK)
+        return st;
+    if (single_launch_now(plan)) {
         PtrTable tab;
         fill_table(tab, plan->P, g, has_e ? e : nullptr);
         uint32_t token = g_next_token.fetch_add(1);
@@ -495,6 +643,9 @@ a2sgd_status_t a2sgd_read_stats(const a2sgd_plan_t *plan, const void *workspace,
         const SegPlan &sp = plan->seg;
         const char *b = static_cast<const char *>(workspace);
         float gmu[2] = {0.0f, 0.0f};
+        SegState state = {};
+        if (hipMemcpyAsync(&state, b + offsetof(WsHeader, seg_tag), sizeof(state), hipMemcpyDeviceToHost, s) != hipSuccess)
+            return A2SGD_ERR_DEVICE;
         for (uint32_t p = 0; out_workers && p < plan->P; ++p)
             if (hipMemcpyAsync(out_workers + p, b + sp.off_stats + sizeof(a2sgd_worker_stats_t) * p * sp.S,
                                sizeof(a2sgd_worker_stats_t), hipMemcpyDeviceToHost, s) != hipSuccess)
@@ -503,6 +654,8 @@ a2sgd_status_t a2sgd_read_stats(const a2sgd_plan_t *plan, const void *workspace,
             return A2SGD_ERR_DEVICE;
         if (hipStreamSynchronize(s) != hipSuccess)
             return A2SGD_ERR_DEVICE;
+        if (state.tag != sp.tag || state.fault != 0)
+            return A2SGD_ERR_WORKSPACE_STATE;
         if (out_global) {
             out_global->gmu_pos = gmu[0];
             out_global->gmu_neg = -gmu[1];  // the table keeps the negated value for the apply pass
@@ -514,8 +667,15 @@ a2sgd_status_t a2sgd_read_stats(const a2sgd_plan_t *plan, const void *workspace,
         return A2SGD_ERR_DEVICE;
     if (hipStreamSynchronize(s) != hipSuccess)
         return A2SGD_ERR_DEVICE;
-    if (plan->last_token != 0 && hdr.failed_token == plan->last_token)
-        return A2SGD_ERR_DEVICE;  // the last single-launch step gave up at its grid barrier; outputs are invalid
+    if (plan->last_token != 0 && hdr.failed_token == plan->last_token) {
+        // The last single-launch step gave up at its grid barrier; its outputs are invalid.  Its grid has drained
+        // (the stream was synchronised above), so the cell can be put back into its initial state for whoever owns
+        // it next; this plan runs the three passes from now on.
+        plan->fused_grid = 0;
+        plan->last_token = 0;
+        (void)launch_barrier_reset(static_cast<uint32_t>(plan->barrier_cell), s);
+        return A2SGD_ERR_DEVICE;
+    }
     if (out_workers)
         for (uint32_t p = 0; p < plan->P; ++p)
             out_workers[p] = hdr.workers[p];
@@ -545,6 +705,8 @@ a2sgd_status_t a2sgd_export_mask(const a2sgd_plan_t *plan, const float *const *g
     rg.add(mask, 8ull * plan->P * ((plan->n + 63) / 64), true);
     if (!rg.disjoint())
         return A2SGD_ERR_INVALID_ARG;
+    if ((st = check_device(plan)) != A2SGD_OK)
+        return st;
     PtrTable tab;
     fill_table(tab, plan->P, g, has_e ? e : nullptr);
     return dev(launch_export_mask(*plan, tab, has_e, mask, static_cast<hipStream_t>(stream)));
@@ -562,6 +724,8 @@ a2sgd_status_t a2sgd_dense_step(const a2sgd_plan_t *plan, const float *const *g,
     if ((st = check_buffer(w)) != A2SGD_OK)
         return st;
     if ((st = check_step_ranges(plan, g, nullptr, w, nullptr, nullptr)) != A2SGD_OK)
+        return st;
+    if ((st = check_device(plan)) != A2SGD_OK)
         return st;
     PtrTable tab;
     fill_table(tab, plan->P, g, nullptr);
@@ -583,6 +747,8 @@ a2sgd_status_t a2sgd_apply_and_update_error_replicas(const a2sgd_plan_t *plan, c
     if ((st = check_buffer(workspace)) != A2SGD_OK)
         return st;
     if ((st = check_step_ranges(plan, g, has_e ? e : nullptr, nullptr, w, workspace)) != A2SGD_OK)
+        return st;
+    if ((st = check_device(plan)) != A2SGD_OK)
         return st;
     PtrTable tab;
     ReplicaTable wt;
@@ -628,6 +794,8 @@ a2sgd_status_t a2sgd_dense_step_replicas(const a2sgd_plan_t *plan, const float *
         return st;
     if ((st = check_step_ranges(plan, g, nullptr, nullptr, w, nullptr)) != A2SGD_OK)
         return st;
+    if ((st = check_device(plan)) != A2SGD_OK)
+        return st;
     PtrTable tab;
     ReplicaTable wt;
     fill_table(tab, plan->P, g, nullptr);
@@ -645,6 +813,8 @@ a2sgd_status_t a2sgd_replica_drift(const a2sgd_plan_t *plan, const float *const 
     if (st != A2SGD_OK)
         return st;
     if ((st = check_buffer(workspace)) != A2SGD_OK)
+        return st;
+    if ((st = check_device(plan)) != A2SGD_OK)
         return st;
     ReplicaTable wt;
     fill_replicas(wt, plan->P, const_cast<float *const *>(w));
@@ -673,6 +843,8 @@ a2sgd_status_t a2sgd_lazy_reset(const a2sgd_plan_t *plan, void *workspace, a2sgd
     a2sgd_status_t st = check_buffer(workspace);
     if (st != A2SGD_OK)
         return st;
+    if ((st = check_device(plan)) != A2SGD_OK)
+        return st;
     return dev(launch_lazy_reset(*plan, workspace, static_cast<hipStream_t>(stream)));
 }
 
@@ -690,6 +862,8 @@ a2sgd_status_t a2sgd_lazy_local_averages(const a2sgd_plan_t *plan, const float *
     if ((st = check_buffer(workspace)) != A2SGD_OK)
         return st;
     if ((st = check_step_ranges(plan, g, s, nullptr, nullptr, workspace)) != A2SGD_OK)
+        return st;
+    if ((st = check_device(plan)) != A2SGD_OK)
         return st;
     PtrTable tab;
     fill_table(tab, plan->P, g, s);
@@ -716,6 +890,8 @@ a2sgd_status_t a2sgd_lazy_apply(const a2sgd_plan_t *plan, const float *const *s,
     rg.add(workspace, plan->workspace_bytes, true);
     if (!rg.disjoint())
         return A2SGD_ERR_INVALID_ARG;
+    if ((st = check_device(plan)) != A2SGD_OK)
+        return st;
     PtrTable tab;
     fill_table(tab, plan->P, s, s);  // the pass reads the state buffers only
     return dev(launch_lazy_apply(*plan, tab, w, eta, workspace, static_cast<hipStream_t>(stream)));
@@ -757,19 +933,21 @@ a2sgd_status_t a2sgd_lazy_materialize(const a2sgd_plan_t *plan, float *const *s,
         return st;
     if ((st = check_buffer(workspace)) != A2SGD_OK)
         return st;
+    if ((st = check_device(plan)) != A2SGD_OK)
+        return st;
     PtrTable tab;
     fill_table(tab, plan->P, s, s);
     return dev(launch_lazy_materialize(*plan, tab, workspace, static_cast<hipStream_t>(stream)));
 }
 
-a2sgd_status_t a2sgd_selftest_barrier(void *scratch, a2sgd_stream_t stream)
+a2sgd_status_t a2sgd_selftest_barrier(void *buffer, a2sgd_stream_t stream)
 {
-    a2sgd_status_t st = check_buffer(scratch);
+    a2sgd_status_t st = check_buffer(buffer);
     if (st != A2SGD_OK)
         return st;
     constexpr uint32_t kGrid = 128;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    uint32_t *passed = static_cast<uint32_t *>(scratch);
+    uint32_t *passed = static_cast<uint32_t *>(buffer);
     uint32_t *cell_failed = passed + kGrid;
     uint32_t host[kGrid + 1];
     for (int round = 0; round < 2; ++round) {
@@ -777,7 +955,7 @@ a2sgd_status_t a2sgd_selftest_barrier(void *scratch, a2sgd_stream_t stream)
         if (launch_barrier_selftest(kGrid, starve ? kGrid + 1 : kGrid, starve ? 64u : (1u << 21), passed, cell_failed,
                                     s) != hipSuccess)
             return A2SGD_ERR_DEVICE;
-        if (hipMemcpyAsync(host, scratch, sizeof(host), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        if (hipMemcpyAsync(host, buffer, sizeof(host), hipMemcpyDeviceToHost, s) != hipSuccess ||
             hipStreamSynchronize(s) != hipSuccess)
             return A2SGD_ERR_DEVICE;
         for (uint32_t b = 0; b < kGrid; ++b)
@@ -798,6 +976,8 @@ a2sgd_status_t a2sgd_workspace_init(const a2sgd_plan_t *plan, void *workspace, a
         return st;
     if (!segmented(plan))
         return A2SGD_OK;
+    if ((st = check_device(plan)) != A2SGD_OK)
+        return st;
     const SegPlan &sp = plan->seg;
     char *b = static_cast<char *>(workspace);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -815,7 +995,8 @@ a2sgd_status_t a2sgd_workspace_init(const a2sgd_plan_t *plan, void *workspace, a
     for (const auto &part : parts)
         if (hipMemcpyAsync(b + part.off, part.src, part.bytes, hipMemcpyHostToDevice, s) != hipSuccess)
             return A2SGD_ERR_DEVICE;
-    return A2SGD_OK;
+    // last, in stream order: the tag that tells the kernels whose tables these are
+    return dev(launch_seg_mark(*plan, workspace, s));
 }
 
 a2sgd_status_t a2sgd_read_segment_stats(const a2sgd_plan_t *plan, const void *workspace, a2sgd_stream_t stream,
@@ -832,6 +1013,9 @@ a2sgd_status_t a2sgd_read_segment_stats(const a2sgd_plan_t *plan, const void *wo
     } catch (const std::bad_alloc &) {
         return A2SGD_ERR_NOMEM;
     }
+    SegState state = {};
+    if (hipMemcpyAsync(&state, b + offsetof(WsHeader, seg_tag), sizeof(state), hipMemcpyDeviceToHost, s) != hipSuccess)
+        return A2SGD_ERR_DEVICE;
     if (out_workers && hipMemcpyAsync(out_workers, b + sp.off_stats, sizeof(a2sgd_worker_stats_t) * plan->P * sp.S,
                                       hipMemcpyDeviceToHost, s) != hipSuccess)
         return A2SGD_ERR_DEVICE;
@@ -840,6 +1024,8 @@ a2sgd_status_t a2sgd_read_segment_stats(const a2sgd_plan_t *plan, const void *wo
         return A2SGD_ERR_DEVICE;
     if (hipStreamSynchronize(s) != hipSuccess)
         return A2SGD_ERR_DEVICE;
+    if (state.tag != sp.tag || state.fault != 0)
+        return A2SGD_ERR_WORKSPACE_STATE;
     if (out_global)
         for (uint32_t k = 0; k < sp.S; ++k) {
             out_global[k].gmu_pos = gmu[2 * k];
@@ -873,6 +1059,8 @@ const char *a2sgd_status_string(a2sgd_status_t status)
     case A2SGD_ERR_ALIGNMENT: return "device pointer not 16-byte aligned";
     case A2SGD_ERR_DEVICE: return "HIP call or kernel launch failed";
     case A2SGD_ERR_NOMEM: return "out of host memory";
+    case A2SGD_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than a2sgd_workspace_bytes";
+    case A2SGD_ERR_WORKSPACE_STATE: return "workspace not initialised for this plan (a2sgd_workspace_init)";
     }
     return "unknown status";
 }

@@ -17,7 +17,7 @@ constexpr int kBlock = 256;           // threads per workgroup: 4 wavefronts of 
 constexpr int kReduceUnroll = 4;      // float4 loads per array per thread per tile in the reduction
 constexpr uint32_t kMaxBlocksPerWorker = 65536;
 constexpr int kFusedBlock = 512;       // threads per workgroup of the single-launch step
-constexpr uint32_t kBarrierSlots = 64;  // grid-barrier cells of the single-launch step, one per plan (mod 64)
+constexpr uint32_t kBarrierSlots = 64;  // grid-barrier cells of the single-launch step: a live plan owns at most one
 constexpr int kLazyItems = 8;           // float4 groups per array per thread in the lazy state's reduction pass
 constexpr uint32_t kFoldSpan = 4096;    // records that one workgroup of k_fold_partials adds up
 
@@ -36,6 +36,12 @@ struct WsHeader {
     a2sgd_worker_stats_t workers[kMaxWorkers];  // Algorithm 1 line 3, per worker
     float neg_mu_pos[kMaxWorkers];  // -mu_pos and mu_neg of every worker again, packed for the apply pass
     float mu_neg[kMaxWorkers];
+    // Plans with tensors: a2sgd_workspace_init leaves the tag of the tables it uploaded here.  A kernel that is about
+    // to index through those tables compares it with its plan's tag first and, on a mismatch (workspace never
+    // initialised, or initialised for another plan), sets seg_fault and exits without touching the tables.
+    uint64_t seg_tag;
+    uint32_t seg_fault;
+    uint32_t reserved;
 };
 constexpr size_t kHeaderBytes = 4096;
 static_assert(sizeof(WsHeader) <= kHeaderBytes, "header must fit its slot");
@@ -104,6 +110,8 @@ struct SegItem {  // one work item: a run of elements inside one segment
 struct SegView {
     uint32_t S;
     uint32_t num_items;
+    WsHeader *hdr;  // holds the tag of the tables that a2sgd_workspace_init uploaded
+    uint64_t tag;   // the tag of this plan's tables
     const uint64_t *seg_start;  // [S + 1] first element of every segment; entry S is a sentinel (2^64 - 1)
     const uint64_t *seg_end;    // [S + 1] exclusive end of every segment; entry S is a sentinel (2^64 - 1)
     const SegItem *item;       // [num_items], ascending start
@@ -128,6 +136,7 @@ struct SegPlan {
     std::vector<uint32_t> item_lo, coarse;
     uint32_t blocks = 0;  // workgroups per worker of the reduction
     std::vector<uint32_t> sched_lo, sched_item;
+    uint64_t tag = 0;  // checksum of the tables above and of the sizes that fix their layout; never 0
     // byte offsets into the workspace
     size_t off_seg_start = 0, off_seg_end = 0, off_item = 0, off_item_lo = 0, off_coarse = 0, off_sched_lo = 0, off_sched_item = 0,
            off_stats = 0, off_nmp = 0, off_mn = 0, off_gmu = 0, off_records = 0, end = 0;
@@ -142,14 +151,19 @@ struct a2sgd_plan {
     uint32_t B;           // blocks per worker in the first-level reduction
     bool streaming;       // footprint exceeds the on-chip caches: use non-temporal loads and stores
     a2sgd::ApplyGeom apply;
-    uint32_t fused_grid;  // workgroups of the single-launch step; 0 = a2sgd_step runs the three passes
-    uint32_t barrier_slot;
+    int32_t device;       // HIP device the calls must find current, or -1: whichever is current
+    // The three fields below change after the plan is made (a single-launch step notes its token; a step that gave
+    // up at its barrier switches the plan to the three passes), which is why a plan is not safe to share between
+    // host threads without the caller's own lock.
+    mutable uint32_t fused_grid;  // workgroups of the single-launch step; 0 = a2sgd_step runs the three passes
+    int32_t barrier_cell;         // the grid-barrier cell this plan owns until it is destroyed; -1 = none
     mutable uint32_t last_token;  // token of the last single-launch step enqueued with this plan; 0 = none
     a2sgd::SegPlan seg;
     uint32_t lazy_blocks;  // workgroups per worker of the lazy state's reduction pass (one record each)
     uint32_t lazy_folded;  // records per worker after k_fold_partials
     size_t lazy_offset;    // byte offset of those records in the workspace; 0 = the plan has no lazy state
     size_t lazy_sign_offset;  // byte offset of the sign words
+    size_t eager_bytes;       // header + partial records: all that the three eager passes of a whole-model plan touch
     size_t workspace_bytes;
 };
 
@@ -180,6 +194,10 @@ hipError_t launch_lazy_materialize(const a2sgd_plan_t &pl, const PtrTable &tab, 
 // *cell_failed (device memory) receive the outcome; the spare cell is cleared afterwards.
 hipError_t launch_barrier_selftest(uint32_t grid, uint32_t expected, uint32_t spin_limit, uint32_t *passed,
                                    uint32_t *cell_failed, hipStream_t s);
+// Puts a grid-barrier cell back into its initial state.  Only for a cell whose grid has drained.
+hipError_t launch_barrier_reset(uint32_t cell, hipStream_t s);
+// Writes the tag of the uploaded tables into the workspace header and clears its fault flag.
+hipError_t launch_seg_mark(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
 // Per-tensor means (a2sgd_segments.hip).
 SegView seg_view(const a2sgd_plan_t &pl, void *ws);
 hipError_t launch_seg_partials(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, void *ws, hipStream_t s);

@@ -328,13 +328,14 @@ __global__ __launch_bounds__(BLOCK) void k_apply(const PtrTable tab, float *__re
 // Single-launch step for models whose g, e and w fit the on-chip caches (Algorithm 1 lines 3-7 in one kernel)
 // ---------------------------------------------------------------------------------------------------------
 
-// Grid-wide barrier for the single-launch step.  The cells live in device memory that the loader zeroes, one
-// per plan slot, so neither the caller nor the plan has to allocate or initialise anything.  It is a
-// sense-reversing barrier: the last workgroup to arrive clears the arrival count and advances the generation,
-// which leaves the cell ready for the next launch.  It is only used with grids that are resident all at once
-// (at most 2 workgroups of 256 threads per compute unit), so every arrival is certain; the wait is bounded all
-// the same, and a wait that runs out marks the cell as failed for good: later launches on it exit at once and
-// report through the workspace header instead of computing on a cell whose count can no longer be trusted.
+// Grid-wide barrier for the single-launch step.  The cells live in device memory that the loader zeroes, so
+// neither the caller nor the plan has to allocate or initialise anything; the host hands each cell to at most one
+// live plan.  It is a sense-reversing barrier: the last workgroup to arrive clears the arrival count and advances
+// the generation, which leaves the cell ready for the next launch.  It is only used with grids that are resident
+// all at once (no more workgroups of kFusedBlock threads than the device has compute units, checked at launch), so
+// every arrival is certain; the wait is bounded all the same, and a wait that runs out marks the cell as failed:
+// later launches on it exit at once and report through the workspace header instead of computing on a cell whose
+// count can no longer be trusted, until the host, having seen the report, resets the cell.
 struct GridBarrier {
     uint32_t arrive, generation, failed, pad;
 };
@@ -408,11 +409,13 @@ __global__ __launch_bounds__(kBlock) void k_barrier_selftest(const uint32_t expe
         passed[blockIdx.x] = ok ? 1u : 0u;
 }
 
-__global__ void k_barrier_selftest_reset(uint32_t *__restrict__ cell_failed_out)
+// Puts a cell back into its initial state; cell_failed_out (may be null) receives its failed flag first.
+__global__ void k_barrier_reset(const uint32_t cell, uint32_t *__restrict__ cell_failed_out)
 {
-    GridBarrier *bar = &g_barriers[kBarrierSlots];
+    GridBarrier *bar = &g_barriers[cell];
     if (threadIdx.x == 0 && blockIdx.x == 0) {
-        *cell_failed_out = load_device(&bar->failed);
+        if (cell_failed_out != nullptr)
+            *cell_failed_out = load_device(&bar->failed);
         store_device(&bar->arrive, 0u);
         store_device(&bar->generation, 0u);
         store_device(&bar->failed, 0u);
@@ -1284,13 +1287,7 @@ template <int MODE, bool HAS_E, bool NT, int UP, int ITEMS, int SEQ, int BLOCK>
 hipError_t launch_apply_geom(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eop, const WsHeader *hdr,
                              uint32_t lds_bytes, hipStream_t s)
 {
-    auto kern = k_apply<MODE, HAS_E, NT, UP, ITEMS, SEQ, BLOCK>;
-    if (lds_bytes > 64 * 1024) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
-        if (err != hipSuccess)
-            return err;
-    }
+    auto kern = k_apply<MODE, HAS_E, NT, UP, ITEMS, SEQ, BLOCK>;  // lds_bytes <= 48 KiB: no attribute to raise
     const uint64_t nvec = (pl.n + 3) >> 2;  // the scalar tail rides in the last workgroup even when n < 4
     const uint64_t per = static_cast<uint64_t>(BLOCK) * ITEMS * SEQ;
     const dim3 grid(static_cast<uint32_t>((nvec + per - 1) / per)), block(BLOCK);
@@ -1345,10 +1342,10 @@ static hipError_t launch_fused_inst(const a2sgd_plan_t &pl, const PtrTable &tab,
     const Partials part = partials_of(ws, pl.P, pl.fused_grid);
     WsHeader *hdr = static_cast<WsHeader *>(ws);
     switch (pl.apply.up) {
-    case 8: k_fused_step<MODE, HAS_E, 8><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, pl.barrier_slot, token); break;
-    case 4: k_fused_step<MODE, HAS_E, 4><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, pl.barrier_slot, token); break;
-    case 2: k_fused_step<MODE, HAS_E, 2><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, pl.barrier_slot, token); break;
-    default: k_fused_step<MODE, HAS_E, 1><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, pl.barrier_slot, token); break;
+    case 8: k_fused_step<MODE, HAS_E, 8><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, static_cast<uint32_t>(pl.barrier_cell), token); break;
+    case 4: k_fused_step<MODE, HAS_E, 4><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, static_cast<uint32_t>(pl.barrier_cell), token); break;
+    case 2: k_fused_step<MODE, HAS_E, 2><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, static_cast<uint32_t>(pl.barrier_cell), token); break;
+    default: k_fused_step<MODE, HAS_E, 1><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, static_cast<uint32_t>(pl.barrier_cell), token); break;
     }
     return hipGetLastError();
 }
@@ -1550,7 +1547,15 @@ hipError_t launch_barrier_selftest(uint32_t grid, uint32_t expected, uint32_t sp
     hipError_t err = hipGetLastError();
     if (err != hipSuccess)
         return err;
-    k_barrier_selftest_reset<<<dim3(1), dim3(64), 0, s>>>(cell_failed);
+    k_barrier_reset<<<dim3(1), dim3(64), 0, s>>>(kBarrierSlots, cell_failed);
+    return hipGetLastError();
+}
+
+hipError_t launch_barrier_reset(uint32_t cell, hipStream_t s)
+{
+    if (cell >= kBarrierSlots)
+        return hipErrorInvalidValue;
+    k_barrier_reset<<<dim3(1), dim3(64), 0, s>>>(cell, nullptr);
     return hipGetLastError();
 }
 

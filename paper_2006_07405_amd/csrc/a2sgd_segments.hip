@@ -20,6 +20,8 @@ SegView seg_view(const a2sgd_plan_t &pl, void *ws)
     SegView v;
     v.S = sp.S;
     v.num_items = static_cast<uint32_t>(sp.item.size());
+    v.hdr = reinterpret_cast<WsHeader *>(b);
+    v.tag = sp.tag;
     v.seg_start = reinterpret_cast<const uint64_t *>(b + sp.off_seg_start);
     v.seg_end = reinterpret_cast<const uint64_t *>(b + sp.off_seg_end);
     v.item = reinterpret_cast<const SegItem *>(b + sp.off_item);
@@ -39,6 +41,27 @@ SegView seg_view(const a2sgd_plan_t &pl, void *ws)
     return v;
 }
 
+// The kernels below index through tables that a2sgd_workspace_init uploads.  Before its first such access every
+// workgroup compares the tag in the workspace header with the tag of its plan's tables; on a mismatch (the
+// workspace was never initialised, or for another plan) it raises the header's fault flag and the caller returns
+// without reading a table entry or writing any output.  The answer is the same for every thread of the grid.
+__device__ __forceinline__ bool seg_tables_ok(const SegView &sv)
+{
+    if (sv.hdr->seg_tag == sv.tag)
+        return true;
+    if (threadIdx.x == 0)
+        sv.hdr->seg_fault = 1u;  // every writer stores the same value
+    return false;
+}
+
+__global__ void k_seg_mark(WsHeader *__restrict__ hdr, const uint64_t tag)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        hdr->seg_tag = tag;
+        hdr->seg_fault = 0u;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // Reduction, first level (Algorithm 1 line 3 per tensor).  grid = (B, P); block b of worker p takes the items
 // that the plan's schedule gives it (about equal work per block).  An item starts and ends anywhere: elements up to the first 16-byte boundary and after the
@@ -56,6 +79,8 @@ __global__ __launch_bounds__(kBlock) void k_seg_partials(const PtrTable tab, con
     __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
     __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
 
+    if (!seg_tables_ok(sv))
+        return;
     const uint32_t k_end = sv.sched_lo[blockIdx.x + 1];
     for (uint32_t k = sv.sched_lo[blockIdx.x]; k < k_end; ++k) {
         const uint32_t it = sv.sched_item[k];
@@ -129,6 +154,8 @@ __global__ __launch_bounds__(kBlock) void k_seg_partials(const PtrTable tab, con
 __global__ __launch_bounds__(64) void k_seg_finalize(const SegView sv)
 {
     const uint32_t s = blockIdx.x, p = blockIdx.y, lane = threadIdx.x;
+    if (!seg_tables_ok(sv))
+        return;
     const uint32_t lo = sv.item_lo[s], hi = sv.item_lo[s + 1];
     const size_t row = static_cast<size_t>(p) * sv.num_items;
     double sp = 0.0, sn = 0.0;
@@ -276,27 +303,30 @@ __global__ __launch_bounds__(BLOCK) void k_seg_apply(const PtrTable tab, float *
     const uint64_t nvec = n >> 2;
     const uint64_t first = static_cast<uint64_t>(blockIdx.x) * BLOCK;  // first float4 group of the workgroup
     const uint64_t i = first + tid;
-    if (first < nvec) {
-        const bool live = i < nvec;
-        vf4 *w4 = reinterpret_cast<vf4 *>(w) + i;
-        vf4 wv, v[UP], ev[UP];
-        if (live) {
-            wv = ld4<NT>(w4);
+    const bool live = i < nvec;
+    vf4 *w4 = reinterpret_cast<vf4 *>(w) + i;
+    vf4 wv, v[UP], ev[UP];
+    if (live) {  // these loads need no table
+        wv = ld4<NT>(w4);
+#pragma unroll
+        for (int u = 0; u < UP; ++u)
+            if (static_cast<uint32_t>(u) < P)
+                v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[u]) + i);
+        if (HAS_E) {
 #pragma unroll
             for (int u = 0; u < UP; ++u)
                 if (static_cast<uint32_t>(u) < P)
-                    v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[u]) + i);
-            if (HAS_E) {
-#pragma unroll
-                for (int u = 0; u < UP; ++u)
-                    if (static_cast<uint32_t>(u) < P)
-                        ev[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[u]) + i);
-            }
+                    ev[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[u]) + i);
         }
-        __builtin_amdgcn_sched_barrier(0);
-        // the table has exactly one entry per workgroup: the segment of its first element
-        static_assert(BLOCK * 4 == (1 << kSegCoarseShift), "one lookup entry per apply workgroup");
-        const uint32_t entry = sv.coarse[blockIdx.x];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // the table has exactly one entry per workgroup, the segment of its first element; the entry's address does not
+    // depend on what the tables hold, so it is read together with the tag that says whether they may be trusted
+    static_assert(BLOCK * 4 == (1 << kSegCoarseShift), "one lookup entry per apply workgroup");
+    const uint32_t entry = sv.coarse[blockIdx.x];
+    if (!seg_tables_ok(sv))
+        return;
+    if (first < nvec) {
         const uint32_t s0 = entry & ~kSegInsideBit;  // the first segment that ends after the workgroup's first element
         if (entry & kSegInsideBit) {
             // the whole workgroup lies in segment s0
@@ -406,6 +436,12 @@ hipError_t launch_seg_partials(const a2sgd_plan_t &pl, const PtrTable &tab, bool
         else
             k_seg_partials<false, false><<<grid, block, 0, s>>>(tab, sv);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_seg_mark(const a2sgd_plan_t &pl, void *ws, hipStream_t s)
+{
+    k_seg_mark<<<dim3(1), dim3(64), 0, s>>>(static_cast<WsHeader *>(ws), pl.seg.tag);
     return hipGetLastError();
 }
 

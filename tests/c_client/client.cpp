@@ -51,6 +51,7 @@ int main(int argc, char **argv)
     cfg.n = n;
     cfg.num_workers = P;
     cfg.mode = mode;
+    cfg.device = 0;  // this program runs on HIP device 0
     a2sgd_plan_t *plan = nullptr;
     CHECK_A2SGD(a2sgd_plan(&cfg, &plan));
 

@@ -110,7 +110,7 @@ def test_segmented_plan_validation_and_workspace(A):
     for cfg in (B.a2sgd_config_t(10, 2, 0, 0, 0, None, None, 1, 0),
                 B.a2sgd_config_t(10, 2, 0, 0, 0, None, (C.c_uint64 * 1)(0), 0, 0),
                 B.a2sgd_config_t(10, 2, 0, 0, 1, (C.c_uint64 * 1)(10), None, 2, 0),
-                B.a2sgd_config_t(10, 2, 0, 0, 1, (C.c_uint64 * 1)(10), None, 0, 7)):
+                B.a2sgd_config_t(10, 2, 0, 0, 1, (C.c_uint64 * 1)(10), None, 0, -2)):
         assert A.raw.a2sgd_plan(C.byref(cfg), C.byref(h)) == A.A2SGD_ERR_INVALID_ARG
     pooled = A.a2sgd_plan(100, 2, 0, 0, seg_lengths=[10, 20], seg_offsets=[4, 50], pooled_means=True)
     assert A.raw.a2sgd_read_stats(pooled.handle, None, None, None, None) == A.A2SGD_ERR_INVALID_ARG  # NULL workspace
@@ -119,6 +119,67 @@ def test_segmented_plan_validation_and_workspace(A):
     assert R.a2sgd_read_segment_stats(whole.handle, 0x30000, None, None, None) == A.A2SGD_ERR_INVALID_ARG
     assert R.a2sgd_lazy_reset(seg.handle, 0x30000, None) == A.A2SGD_ERR_INVALID_ARG
     assert R.a2sgd_workspace_init(whole.handle, 0x30000, None) == A.A2SGD_OK  # nothing to upload
+
+
+def test_grid_barrier_cells_are_owned_by_live_plans(A):
+    """A plan whose model fits the caches owns one of the 64 grid-barrier cells from a2sgd_plan to
+    a2sgd_plan_destroy: live plans never share a cell, a plan made while all are taken runs the three passes, and
+    destroying a plan frees its cell for the next one."""
+    import gc
+    gc.collect()  # plans of earlier tests give their cells back when they are collected
+    plans, cells = [], []
+    for _ in range(70):
+        p = A.a2sgd_plan(5000, 2)
+        c = A.a2sgd_plan_single_launch_cell(p)
+        if c < 0:
+            spare = p
+            break
+        plans.append(p)
+        cells.append(c)
+    else:
+        raise AssertionError("more than 64 plans got a cell")
+    assert 1 <= len(cells) <= 64 and len(set(cells)) == len(cells) and all(0 <= c < 64 for c in cells)
+    assert A.a2sgd_plan_single_launch_cell(spare) == -1
+    # the workspace does not depend on whether the plan got a cell
+    assert A.a2sgd_workspace_bytes(spare) == A.a2sgd_workspace_bytes(plans[0])
+    # models too large for the caches and plans with tensors never take one
+    assert A.a2sgd_plan_single_launch_cell(A.a2sgd_plan(1 << 28, 4)) == -1
+    victim = plans.pop(len(plans) // 2)
+    freed = A.a2sgd_plan_single_launch_cell(victim)
+    assert A.raw.a2sgd_plan_destroy(victim.handle) == A.A2SGD_OK
+    victim.handle = None
+    again = A.a2sgd_plan(5000, 2)
+    assert A.a2sgd_plan_single_launch_cell(again) == freed
+    assert A.a2sgd_plan_single_launch_cell(A.a2sgd_plan(5000, 2)) == -1  # all taken once more
+    assert A.raw.a2sgd_plan_single_launch_cell(None) == -1
+    del plans, again, spare
+    gc.collect()
+    assert A.a2sgd_plan_single_launch_cell(A.a2sgd_plan(5000, 2, seg_lengths=[5000])) == -1
+    assert A.a2sgd_plan_single_launch_cell(A.a2sgd_plan(5000, 2)) >= 0
+
+
+def test_workspace_check_and_new_status_codes(A):
+    plan = A.a2sgd_plan(1000, 2)
+    need = A.a2sgd_workspace_bytes(plan)
+    R, h = A.raw, plan.handle
+    assert R.a2sgd_workspace_check(h, 0x30000, need) == A.A2SGD_OK
+    assert R.a2sgd_workspace_check(h, 0x30000, need + 1) == A.A2SGD_OK
+    assert R.a2sgd_workspace_check(h, 0x30000, need - 1) == A.A2SGD_ERR_WORKSPACE_TOO_SMALL
+    assert R.a2sgd_workspace_check(h, 0x30000, 0) == A.A2SGD_ERR_WORKSPACE_TOO_SMALL
+    assert R.a2sgd_workspace_check(h, None, need) == A.A2SGD_ERR_INVALID_ARG
+    assert R.a2sgd_workspace_check(None, 0x30000, need) == A.A2SGD_ERR_INVALID_ARG
+    assert R.a2sgd_workspace_check(h, 0x30008, need) == A.A2SGD_ERR_ALIGNMENT
+    assert A.A2SGD_ERR_WORKSPACE_TOO_SMALL == 5 and A.A2SGD_ERR_WORKSPACE_STATE == 6
+    assert b"workspace" in R.a2sgd_status_string(5) and b"a2sgd_workspace_init" in R.a2sgd_status_string(6)
+    assert R.a2sgd_status_string(99) == b"unknown status"
+
+
+def test_plan_for_a_device(A):
+    """The device index is part of the plan; -1 means no check.  (What a mismatch does is a GPU test.)"""
+    assert A.a2sgd_plan(1000, 2, device=0).handle and A.a2sgd_plan(1000, 2, device=3).handle
+    with pytest.raises(A.A2sgdError) as ei:
+        A.a2sgd_plan(1000, 2, device=-2)
+    assert ei.value.status == A.A2SGD_ERR_INVALID_ARG
 
 
 def _tab(vals):

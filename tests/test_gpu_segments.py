@@ -185,11 +185,14 @@ def test_streaming_size_with_padding(A):
     run_padded_case(A, 12, n, 7, 0, seg, off, pooled=True)
 
 
-@pytest.mark.parametrize("P,mode", [(7, 0), (12, 1)])
+@pytest.mark.parametrize("P,mode", [(7, 0), (12, 1), (16, 0), (33, 1)])
 def test_streaming_size_with_a_short_group_of_workers(A, P, mode):
     """A footprint above the cache limit (streaming kernels) with tensor boundaries of every alignment and a worker
-    count that is not a multiple of the group size."""
+    count that is not a multiple of the group size; 16 and 33 workers take the widest groups of the apply pass, two
+    and five of them, with streaming stores."""
     seg = [1_000_003, 5, 777_777, 64, 1_300_001, 131_072, 2, 291_079]
+    if P >= 16:
+        seg = [600_003, 5, 477_777, 64, 500_001, 131_072, 2, 91_079]
     n = sum(seg)
     assert (2 * P + 1) * 4 * n > 192 << 20
     g, e, w = make_case(n + P, n, P, scales_for(seg, P))
