@@ -29,6 +29,21 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+STREAMS_LIB = os.path.join(HERE, "libhbm_streams.so")
+STREAMS_SRC = os.path.join(HERE, "csrc", "hbm_streams.hip")
+
+
+def build_streams() -> str:
+    """The plain streaming kernels that bench.py times for its measured bandwidth ceilings (csrc/hbm_streams.hip)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Xclang", "-target-feature",
+           "-Xclang", "-packed-fp32-ops", "-Wall", "-Wextra", "-x", "hip", STREAMS_SRC, "-o", STREAMS_LIB]
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed on the streaming kernels:\n" + proc.stdout)
+    return STREAMS_LIB
+
+
 CLIENT_SRC = os.path.join(ROOT, "tests", "c_client", "client.cpp")
 CLIENT = os.path.join(ROOT, "tests", "c_client", "client")
 
