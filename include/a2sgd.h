@@ -53,8 +53,9 @@ typedef enum {
     A2SGD_ERR_DEVICE = 3,      /* a HIP call or kernel launch failed */
     A2SGD_ERR_NOMEM = 4,       /* host allocation of the plan failed */
     A2SGD_ERR_WORKSPACE_TOO_SMALL = 5, /* a2sgd_workspace_check: fewer bytes than a2sgd_workspace_bytes */
-    A2SGD_ERR_WORKSPACE_STATE = 6      /* a plan with tensors found a workspace that a2sgd_workspace_init has not
+    A2SGD_ERR_WORKSPACE_STATE = 6,     /* a plan with tensors found a workspace that a2sgd_workspace_init has not
                                           prepared for it; the calls since then have computed nothing */
+    A2SGD_ERR_SCRATCH_LIMIT = 7        /* a2sgd_step_static: the plan needs more than A2SGD_STATIC_SCRATCH_BYTES */
 } a2sgd_status_t;
 
 typedef enum {
@@ -153,6 +154,23 @@ a2sgd_status_t a2sgd_apply_and_update_error(const a2sgd_plan_t *plan, const floa
  * it once with A2SGD_ERR_DEVICE; from then on the plan runs the three passes. */
 a2sgd_status_t a2sgd_step(const a2sgd_plan_t *plan, const float *const *g, float *const *e, float *w, float eta,
                           void *workspace, a2sgd_stream_t stream);
+
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): a2sgd_step's three passes (never the single launch) with the header and
+ * the block partial records in a fixed array inside the library's own device memory instead of a workspace.  The
+ * array has A2SGD_STATIC_SCRATCH_BYTES on every GPU the library runs on, for the life of the process; a whole-model
+ * plan fits if 4096 + 40 * P * a2sgd_plan_blocks_per_worker(plan) is no more than that (every plan made with
+ * blocks_per_worker = 0 does), otherwise A2SGD_ERR_SCRATCH_LIMIT and nothing is enqueued; plans with tensors get
+ * A2SGD_ERR_INVALID_ARG.  The call allocates and frees nothing, copies nothing and does not synchronise: it only
+ * enqueues the same kernels as a2sgd_local_averages, a2sgd_global_average and a2sgd_apply_and_update_error, so e and
+ * w come out bit-identical to those three calls.  Every pass rewrites what it reads from the array, so nothing in it
+ * has to start at zero and what an earlier call left does not matter.  All calls on one GPU share the array: two
+ * calls that may run at the same time on that GPU (two streams, two host threads) race and give wrong results;
+ * calls ordered by one stream are safe.  The statistics are not readable after this call (a2sgd_read_stats needs
+ * a workspace). */
+#define A2SGD_STATIC_SCRATCH_BYTES (256u * 1024u)
+a2sgd_status_t a2sgd_step_static(const a2sgd_plan_t *plan, const float *const *g, float *const *e, float *w, float eta,
+                                 a2sgd_stream_t stream);
 
 /* Copies the per-worker and global results of the last completed reduction out of the workspace into host
  * memory: out_workers[P] and *out_global (either may be NULL).  Synchronises `stream`.  For tests and logging. */

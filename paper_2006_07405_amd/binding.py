@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_HERE, "liba2sgd.so")
 
 A2SGD_MAX_WORKERS = 64
 (A2SGD_OK, A2SGD_ERR_INVALID_ARG, A2SGD_ERR_ALIGNMENT, A2SGD_ERR_DEVICE, A2SGD_ERR_NOMEM, A2SGD_ERR_WORKSPACE_TOO_SMALL,
- A2SGD_ERR_WORKSPACE_STATE) = range(7)
+ A2SGD_ERR_WORKSPACE_STATE, A2SGD_ERR_SCRATCH_LIMIT) = range(8)
+A2SGD_STATIC_SCRATCH_BYTES = 256 * 1024
 A2SGD_MODE_RETAINED_ERROR, A2SGD_MODE_ALG1_LITERAL = 0, 1
 
 
@@ -65,6 +66,8 @@ def _load():
     L.a2sgd_global_average.argtypes = [vp, vp, vp]
     L.a2sgd_apply_and_update_error.argtypes = [vp, tab, tab, vp, C.c_float, vp, vp]
     L.a2sgd_step.argtypes = [vp, tab, tab, vp, C.c_float, vp, vp]
+    L.a2sgd_step_static.argtypes = [vp, tab, tab, vp, C.c_float, vp]
+    L.a2sgd_step_static.restype = C.c_int
     L.a2sgd_read_stats.argtypes = [vp, vp, vp, C.POINTER(a2sgd_worker_stats_t), C.POINTER(a2sgd_global_stats_t)]
     L.a2sgd_export_mask.argtypes = [vp, tab, tab, vp, vp]
     L.a2sgd_dense_step.argtypes = [vp, tab, vp, C.c_float, vp]
@@ -258,6 +261,13 @@ def a2sgd_step(plan: Plan, g, e, w: torch.Tensor, eta: float, workspace: torch.T
     _check(raw.a2sgd_step(plan.handle, _table(plan, g, "g"), _table(plan, e, "e"),
                           _dev_ptr(w, plan.n, torch.float32, "w"), C.c_float(eta), _workspace(plan, workspace),
                           _stream(stream)), "a2sgd_step")
+
+
+def a2sgd_step_static(plan: Plan, g, e, w: torch.Tensor, eta: float, stream=None) -> None:
+    """The three passes of one step on the library's built-in scratch array: no workspace, no allocation."""
+    _check(raw.a2sgd_step_static(plan.handle, _table(plan, g, "g"), _table(plan, e, "e"),
+                                 _dev_ptr(w, plan.n, torch.float32, "w"), C.c_float(eta), _stream(stream)),
+           "a2sgd_step_static")
 
 
 @dataclass

@@ -13,6 +13,12 @@
 
 using namespace a2sgd;
 
+// Scratch memory for a2sgd_step_static, whose callers cannot allocate: the workspace of the three eager passes
+// (header and block partial records) in a fixed array that every GPU the library runs on holds until the process
+// ends.  In host code the array's name is only a handle for the runtime, not a device address.
+constexpr size_t kStaticScratchBytes = A2SGD_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 // One workgroup of the apply-type passes covers as little as 64 float4 groups and a grid holds fewer than 2^31
@@ -244,6 +250,27 @@ uint32_t current_device_compute_units()
         cached[device].store(cu, std::memory_order_relaxed);
     }
     return cu;
+}
+
+// The device address of `scratch` on the current device: asked for once per device, with that device current, and
+// kept; every later use of the array's memory in host code goes through this address, never through the name.
+a2sgd_status_t static_scratch(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mutex;
+    static void *address[kMaxDevices];  // zero-initialised: not asked yet
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices)
+        return A2SGD_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(mutex);
+    if (address[device] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr)
+            return A2SGD_ERR_DEVICE;
+        address[device] = ptr;
+    }
+    *out = address[device];
+    return A2SGD_OK;
 }
 
 // A plan made for one device refuses to launch while another one is current.
@@ -630,6 +657,40 @@ a2sgd_status_t a2sgd_step(const a2sgd_plan_t *plan, const float *const *g, float
     if ((st = a2sgd_global_average(plan, workspace, stream)) != A2SGD_OK)
         return st;
     return a2sgd_apply_and_update_error(plan, g, e, w, eta, workspace, stream);
+}
+
+a2sgd_status_t a2sgd_step_static(const a2sgd_plan_t *plan, const float *const *g, float *const *e, float *w, float eta,
+                                 a2sgd_stream_t stream)
+{
+    bool has_e = false;
+    a2sgd_status_t st = check_g_e(plan, g, e, &has_e);
+    if (st != A2SGD_OK)
+        return st;
+    if (segmented(plan))
+        return A2SGD_ERR_INVALID_ARG;
+    if ((st = check_buffer(w)) != A2SGD_OK)
+        return st;
+    // the built-in array lies in the library's own device memory: no buffer of the caller can overlap it
+    if ((st = check_step_ranges(plan, g, has_e ? e : nullptr, w, nullptr, nullptr)) != A2SGD_OK)
+        return st;
+    // the three passes touch the header and P * B partial records, nothing else
+    if (kHeaderBytes + 5ull * 8ull * plan->P * plan->B > kStaticScratchBytes)
+        return A2SGD_ERR_SCRATCH_LIMIT;
+    if ((st = check_device(plan)) != A2SGD_OK)
+        return st;
+    void *ws = nullptr;
+    if ((st = static_scratch(&ws)) != A2SGD_OK)
+        return st;
+    PtrTable tab;
+    fill_table(tab, plan->P, g, has_e ? e : nullptr);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if ((st = dev(launch_local_partials(*plan, tab, has_e, ws, s))) != A2SGD_OK)
+        return st;
+    if ((st = dev(launch_local_finalize(*plan, ws, s))) != A2SGD_OK)
+        return st;
+    if ((st = dev(launch_global_average(*plan, ws, s))) != A2SGD_OK)
+        return st;
+    return dev(launch_apply(*plan, tab, has_e, w, eta, ws, s));
 }
 
 a2sgd_status_t a2sgd_read_stats(const a2sgd_plan_t *plan, const void *workspace, a2sgd_stream_t stream,
@@ -1061,6 +1122,7 @@ const char *a2sgd_status_string(a2sgd_status_t status)
     case A2SGD_ERR_NOMEM: return "out of host memory";
     case A2SGD_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than a2sgd_workspace_bytes";
     case A2SGD_ERR_WORKSPACE_STATE: return "workspace not initialised for this plan (a2sgd_workspace_init)";
+    case A2SGD_ERR_SCRATCH_LIMIT: return "plan needs more scratch than the library's built-in array holds";
     }
     return "unknown status";
 }

@@ -232,6 +232,31 @@ def test_step_calls_validate_before_launch(A):
     assert R.a2sgd_status_string(ALN) == b"device pointer not 16-byte aligned"
 
 
+def test_step_static_validates_before_it_touches_the_device(A):
+    """The entry point for callers that cannot allocate rejects bad arguments, plans with tensors and plans whose
+    records do not fit its built-in array, all before the first HIP call."""
+    R = A.raw
+    INV, ALN = A.A2SGD_ERR_INVALID_ARG, A.A2SGD_ERR_ALIGNMENT
+    plan = A.a2sgd_plan(1000, 2)
+    good, other = _tab([0x10000, 0x20000]), _tab([0x50000, 0x60000])
+    w = 0x40000
+    assert R.a2sgd_step_static(None, good, other, w, 0.1, None) == INV
+    assert R.a2sgd_step_static(plan.handle, good, None, w, 0.1, None) == INV
+    assert R.a2sgd_step_static(plan.handle, good, other, None, 0.1, None) == INV
+    assert R.a2sgd_step_static(plan.handle, good, other, w + 8, 0.1, None) == ALN
+    assert R.a2sgd_step_static(plan.handle, good, good, w, 0.1, None) == INV  # e^p is g^p
+    tensors = A.a2sgd_plan(1000, 2, seg_lengths=[400, 600])
+    assert R.a2sgd_step_static(tensors.handle, good, other, w, 0.1, None) == INV
+    # 4096 + 40 * P * B bytes must fit the array
+    limit = (A.A2SGD_STATIC_SCRATCH_BYTES - 4096) // (40 * 2)
+    big = A.a2sgd_plan(1000, 2, blocks_per_worker=limit + 1)
+    assert R.a2sgd_step_static(big.handle, good, other, w, 0.1, None) == A.A2SGD_ERR_SCRATCH_LIMIT
+    assert A.A2SGD_ERR_SCRATCH_LIMIT == 7 and b"built-in" in R.a2sgd_status_string(7)
+    # every plan that lets the library choose the grid fits
+    for n, P in ((1 << 38, 64), (1_500_000_000, 4), (5, 1), (138_357_544, 16)):
+        assert 4096 + 40 * P * A.a2sgd_plan_blocks_per_worker(A.a2sgd_plan(n, P)) <= A.A2SGD_STATIC_SCRATCH_BYTES
+
+
 def test_binding_checks_shapes_without_touching_the_gpu(A):
     import torch
     plan = A.a2sgd_plan(100, 2)
