@@ -61,6 +61,7 @@ uint32_t dense_lds_bytes(uint32_t P)
 constexpr uint64_t kStreamingBytes = 192ull << 20;
 
 constexpr uint32_t kMaxSegments = 1u << 20;
+constexpr uint32_t kTwoKernelWorkers = 8;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -462,6 +463,10 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
     pl->apply.up = pl->P >= 8 ? 8 : pl->P >= 4 ? 4 : pl->P >= 2 ? 2 : 1;
     pl->apply.lds_bytes = pl->streaming ? apply_lds_bytes(pl->P) : 0;
     pl->apply.dense_lds_bytes = pl->streaming ? dense_lds_bytes(pl->P) : 0;
+    // From kTwoKernelWorkers workers on, a workgroup of the one-kernel apply pass has so many buffers open (2P + 1)
+    // that address translation costs it more than the sign words cost the two-kernel form (nP/4 extra bytes).
+    pl->apply.two_kernels = pl->streaming && cfg->num_segments == 0 && pl->mode == A2SGD_MODE_RETAINED_ERROR &&
+                            pl->P >= kTwoKernelWorkers;
     pl->device = cfg->device;
     // Single-launch step while everything fits the caches: one workgroup of kFusedBlock threads per 2048 elements,
     // at most kFusedGridMax of them.  It needs a grid-barrier cell of its own; without one the plan runs the three
@@ -624,7 +629,7 @@ a2sgd_status_t a2sgd_apply_and_update_error(const a2sgd_plan_t *plan, const floa
     fill_table(tab, plan->P, g, has_e ? e : nullptr);
     if (segmented(plan))
         return dev(launch_seg_apply(*plan, tab, has_e, w, eta, workspace, static_cast<hipStream_t>(stream)));
-    return dev(launch_apply(*plan, tab, has_e, w, eta, workspace, static_cast<hipStream_t>(stream)));
+    return dev(launch_apply(*plan, tab, has_e, w, eta, workspace, false, static_cast<hipStream_t>(stream)));
 }
 
 a2sgd_status_t a2sgd_step(const a2sgd_plan_t *plan, const float *const *g, float *const *e, float *w, float eta,
@@ -690,7 +695,7 @@ a2sgd_status_t a2sgd_step_static(const a2sgd_plan_t *plan, const float *const *g
         return st;
     if ((st = dev(launch_global_average(*plan, ws, s))) != A2SGD_OK)
         return st;
-    return dev(launch_apply(*plan, tab, has_e, w, eta, ws, s));
+    return dev(launch_apply(*plan, tab, has_e, w, eta, ws, true, s));  // the array has no room for sign words
 }
 
 a2sgd_status_t a2sgd_read_stats(const a2sgd_plan_t *plan, const void *workspace, a2sgd_stream_t stream,
@@ -815,7 +820,7 @@ a2sgd_status_t a2sgd_apply_and_update_error_replicas(const a2sgd_plan_t *plan, c
     ReplicaTable wt;
     fill_table(tab, plan->P, g, has_e ? e : nullptr);
     if (plan->P == 1)  // one worker: its own replica is the shared vector, and that pass is the tuned one
-        return dev(launch_apply(*plan, tab, has_e, w[0], eta, workspace, static_cast<hipStream_t>(stream)));
+        return dev(launch_apply(*plan, tab, has_e, w[0], eta, workspace, false, static_cast<hipStream_t>(stream)));
     fill_replicas(wt, plan->P, w);
     return dev(launch_apply_replicas(*plan, tab, wt, has_e, eta, workspace, static_cast<hipStream_t>(stream)));
 }

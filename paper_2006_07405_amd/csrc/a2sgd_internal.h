@@ -28,7 +28,7 @@ constexpr uint32_t kFoldSpan = 4096;    // records that one workgroup of k_fold_
 //   uint64_t n_pos [P][B], n_neg [P][B], n_zero [P][B]
 //   whole-model plans only, at plan.lazy_offset: the same five arrays as [P][lazy_blocks] (one record per
 //   workgroup of the lazy state's reduction pass), then as [P][lazy_folded]; at plan.lazy_sign_offset:
-//   uint16_t sign [P][lazy_blocks][2][64], one bit per element: pos(v) of Eq. 2
+//   uint16_t sign [lazy_blocks][2][P][64], one bit per element: pos(v) of Eq. 2
 struct WsHeader {
     float gmu_pos, gmu_neg;  // Algorithm 1 line 5
     uint32_t failed_token;   // set to the launch's token by a single-launch step that could not complete
@@ -90,6 +90,7 @@ struct ApplyGeom {
     int up;
     uint32_t lds_bytes;
     uint32_t dense_lds_bytes;  // the same for the dense step
+    bool two_kernels;          // retained-error mode: error write-back and weight update as two kernels (many workers)
 };
 }  // namespace a2sgd
 
@@ -175,8 +176,9 @@ hipError_t launch_local_finalize(const a2sgd_plan_t &pl, void *ws, hipStream_t s
 hipError_t launch_global_average(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
 hipError_t launch_export_local_means(const a2sgd_plan_t &pl, const void *ws, float *out, hipStream_t s);
 hipError_t launch_import_global_means(const a2sgd_plan_t &pl, void *ws, const float *gmu, hipStream_t s);
+// one_kernel: never the two-kernel form (whose sign words need the whole workspace)
 hipError_t launch_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
-                        hipStream_t s);
+                        bool one_kernel, hipStream_t s);
 hipError_t launch_fused_step(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
                              uint32_t token, hipStream_t s);
 hipError_t launch_apply_replicas(const a2sgd_plan_t &pl, const PtrTable &tab, const ReplicaTable &wt, bool has_e,

@@ -865,6 +865,14 @@ __device__ __forceinline__ vf4 pending_error4(vf4 s, float neg_mu_pos, float mu_
 // groups per thread, all loads issued before the first store (a loop would wait for its own older stores before
 // it could use newer loads, since both are counted together).  Every workgroup writes one record; the records
 // of a worker are combined in index order by k_fold_partials and k_local_finalize.
+// Where the sign words of worker p for half h of the 2048-element block b start: uint16_t sign[blocks][2][P][64].
+// A workgroup of the pass that reads them covers one (b, h) and finds every worker's 128 bytes side by side.
+__device__ __forceinline__ uint16_t *sign_row(uint16_t *sign, const uint32_t P, const uint64_t b, const uint32_t h,
+                                              const uint32_t p)
+{
+    return sign + ((b * 2 + h) * P + p) * 64;
+}
+
 // Shifts pos(v) of the four components into the low end of `bits`, x first.
 __device__ __forceinline__ uint32_t push_signs(uint32_t bits, vf4 v)
 {
@@ -877,8 +885,9 @@ __device__ __forceinline__ uint32_t push_signs(uint32_t bits, vf4 v)
 
 // With SIGNS the pass also leaves pos(v) of Eq. 2 as one bit per element for the apply pass: thread `tid` of
 // workgroup b collects 32 bits, bit 31 - (4 * u + c) for component c of its float4 group u (0 where the group lies
-// past the end), and writes them as two 16-bit halves, sign[p][b][h][tid] (h = 0: groups 0-3), so that a
-// workgroup of the apply pass, which covers half of the groups, reads 128 contiguous bytes per worker.
+// past the end), and writes them as two 16-bit halves, sign[b][h][p][tid] (h = 0: groups 0-3), so that a
+// workgroup of the apply pass, which covers half of the groups, reads 128 contiguous bytes per worker, and all
+// workers' bytes next to each other.
 template <bool NT, bool SIGNS>
 __global__ __launch_bounds__(64) void k_lazy_partials(const PtrTable tab, const uint64_t n, const uint32_t blocks,
                                                       const WsHeader *__restrict__ hdr, Partials out,
@@ -932,9 +941,8 @@ __global__ __launch_bounds__(64) void k_lazy_partials(const PtrTable tab, const 
         }
     }
     if (SIGNS) {
-        uint16_t *row = sign + (static_cast<size_t>(p) * blocks + b) * 128 + tid;
-        row[0] = static_cast<uint16_t>(bits >> 16);
-        row[64] = static_cast<uint16_t>(bits & 0xffffu);
+        sign_row(sign, gridDim.y, b, 0, p)[tid] = static_cast<uint16_t>(bits >> 16);
+        sign_row(sign, gridDim.y, b, 1, p)[tid] = static_cast<uint16_t>(bits & 0xffffu);
     }
     if (b == 0 && tid < (n & 3)) {
         const uint64_t i = (nvec << 2) + tid;
@@ -952,6 +960,68 @@ __global__ __launch_bounds__(64) void k_lazy_partials(const PtrTable tab, const 
         out.n_pos[slot] = acc.c_pos;
         out.n_neg[slot] = acc.c_neg;
         out.n_zero[slot] = acc.c_zero;
+    }
+}
+
+// First half of the apply pass in its two-kernel form (retained-error mode, many workers).  In that mode the update
+// of parameter i depends only on how many workers have i in the positive group, so the pass over g and e need not
+// touch w at all: workgroup (x, p) rewrites 1024 elements of worker p's error (Algorithm 1 line 4, Eq. 2) and leaves
+// pos(v) in the sign words, in k_lazy_partials' layout (one half of a row per workgroup); k_apply_signs then updates
+// w from the sign words alone.  A workgroup has 3 buffers open instead of 2P + 1, and all workgroups that run at one
+// time are on the same worker or two: what the single kernel loses to address translation as P grows is not lost
+// here.  Single wavefronts launched once, ITEMS float4 groups of g and of e per thread, all loads ahead of the first
+// store.  The last n % 4 elements are left to k_apply_signs.
+template <bool NT, int ITEMS>
+__global__ __launch_bounds__(64) void k_error_signs(const PtrTable tab, const uint64_t n,
+                                                    const WsHeader *__restrict__ hdr, uint16_t *__restrict__ sign)
+{
+    static_assert(ITEMS == kLazyItems || 2 * ITEMS == kLazyItems, "a workgroup fills both halves of a sign row or one");
+    constexpr uint32_t kParts = kLazyItems / ITEMS;
+    const uint32_t p = blockIdx.y, tid = threadIdx.x;
+    const uint32_t b = blockIdx.x / kParts, h = blockIdx.x % kParts;  // sign row, and which half of it
+    const uint32_t lz = opaque_zero();
+    const float nmp = hdr->neg_mu_pos[p + lz], mn = hdr->mu_neg[p + lz];
+    const vf4 *__restrict__ g4 = reinterpret_cast<const vf4 *>(tab.g[p]);
+    vf4 *e4 = reinterpret_cast<vf4 *>(tab.e[p]);
+    const uint64_t nvec = n >> 2;
+    constexpr uint64_t kPer = 64ull * ITEMS;
+    const uint64_t base = static_cast<uint64_t>(blockIdx.x) * kPer + tid;
+    uint32_t bits = 0;
+    if ((static_cast<uint64_t>(blockIdx.x) + 1) * kPer <= nvec) {
+        vf4 gv[ITEMS], ev[ITEMS];
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u)
+            gv[u] = ld4<NT>(g4 + base + u * 64);
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u)
+            ev[u] = ld4<NT>(e4 + base + u * 64);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u) {
+            const vf4 v = gv[u] + ev[u];
+            bits = push_signs(bits, v);
+            const vf4 err = pending_error4(v, nmp, mn);  // v - enc(v)
+            st4<NT>(e4 + base + u * 64, err);
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u) {
+            const uint64_t i = base + static_cast<uint64_t>(u) * 64;
+            if (i < nvec) {
+                const vf4 v = ld4<NT>(g4 + i) + ld4<NT>(e4 + i);
+                bits = push_signs(bits, v);
+                const vf4 err = pending_error4(v, nmp, mn);
+                st4<NT>(e4 + i, err);
+            } else {
+                bits <<= 4;
+            }
+        }
+    }
+    if (kParts == 1) {
+        sign_row(sign, gridDim.y, b, 0, p)[tid] = static_cast<uint16_t>(bits >> 16);
+        sign_row(sign, gridDim.y, b, 1, p)[tid] = static_cast<uint16_t>(bits & 0xffffu);
+    } else {
+        sign_row(sign, gridDim.y, b, h, p)[tid] = static_cast<uint16_t>(bits);  // 4 groups of 4 bits
     }
 }
 
@@ -1067,19 +1137,23 @@ __global__ __launch_bounds__(BLOCK) void k_lazy_apply(const PtrTable tab, float 
     }
 }
 
+constexpr int kErrorItems = 4;  // float4 groups per array per thread in k_error_signs: half a sign row per workgroup
 constexpr uint32_t kLazySignLds = 8 * 1024;  // its dynamic-LDS request when streaming (20 workgroups per CU)
 
-// Apply pass on the lazy state in retained-error mode, from the sign words: there the update of an element is
+// Weight update in retained-error mode from the sign words: there the update of an element is
 // (k * gmu_pos - (P - k) * gmu_neg) / P with k = the number of workers whose v is >= 0 (Algorithm 1 line 6 summed
 // over the workers as in Eq. 1), so the pass reads one bit per element-worker instead of v.  A workgroup is one
-// wavefront; it covers one half (4) of the float4 groups that each thread of one workgroup of the reduction pass
-// owned, so a thread finds its 16 bits in that thread's half-word of every worker.  A NaN has no sign: if the
-// reduction counted any, the pass reads v as k_lazy_apply does (a branch that is uniform over the grid).
-template <bool NT, int UP>
-__global__ __launch_bounds__(64) void k_lazy_apply_signs(const PtrTable tab, const uint16_t *__restrict__ sign,
-                                                         const uint64_t row_halves, float *__restrict__ w,
-                                                         const uint64_t n, const uint32_t P, const float eta_over_P,
-                                                         const WsHeader *__restrict__ hdr)
+// wavefront; it covers one half (4) of the float4 groups that each thread of one workgroup of the pass that wrote
+// the sign words owned, so a thread finds its 16 bits in that thread's half-word of every worker.
+// LAZY: the apply pass of the lazy state; tab.e holds v.  A NaN has no sign: if the reduction counted any, the pass
+// reads v as k_lazy_apply does (a branch that is uniform over the grid), and the scalar tail reads v too.
+// !LAZY: second half of the two-kernel apply pass; tab.e holds the new errors that k_error_signs wrote, which are
+// NaN exactly where v was, so with NaNs about the pass reads them next to the sign bits; the last n % 4 elements,
+// which k_error_signs left alone, get the whole of lines 4, 6 and 7 here.
+template <bool NT, int UP, bool LAZY>
+__global__ __launch_bounds__(64) void k_apply_signs(const PtrTable tab, const uint16_t *__restrict__ sign,
+                                                    float *__restrict__ w, const uint64_t n, const uint32_t P,
+                                                    const float eta_over_P, const WsHeader *__restrict__ hdr)
 {
     constexpr int ITEMS = 4;
     constexpr uint32_t kParts = kLazyItems / ITEMS;
@@ -1100,7 +1174,7 @@ __global__ __launch_bounds__(64) void k_lazy_apply_signs(const PtrTable tab, con
             wv[t] = ld4<NT>(w4 + first + t * 64);
     vf4 acc[ITEMS];
     if (any_nan == 0) {
-        const uint16_t *half = sign + b * 128 + (blockIdx.x % kParts) * 64 + lane;
+        const uint16_t *half = sign + static_cast<uint64_t>(blockIdx.x) * P * 64 + lane;  // sign[b][h][.][lane]
         uint32_t k[ITEMS][4];
 #pragma unroll
         for (int t = 0; t < ITEMS; ++t)
@@ -1110,7 +1184,7 @@ __global__ __launch_bounds__(64) void k_lazy_apply_signs(const PtrTable tab, con
             uint32_t d[UP];
 #pragma unroll
             for (int q = 0; q < UP; ++q)
-                d[q] = half[(p0 + q) * row_halves];
+                d[q] = half[(p0 + q) * 64];
 #pragma unroll
             for (int q = 0; q < UP; ++q)
 #pragma unroll
@@ -1120,7 +1194,7 @@ __global__ __launch_bounds__(64) void k_lazy_apply_signs(const PtrTable tab, con
                         k[t][c] += (d[q] >> (15u - (4u * t + c))) & 1u;
         }
         for (; p0 < P; ++p0) {
-            const uint32_t d = half[p0 * row_halves];
+            const uint32_t d = half[p0 * 64];
 #pragma unroll
             for (int t = 0; t < ITEMS; ++t)
 #pragma unroll
@@ -1132,7 +1206,7 @@ __global__ __launch_bounds__(64) void k_lazy_apply_signs(const PtrTable tab, con
         for (int t = 0; t < ITEMS; ++t)
             acc[t] = vf4{static_cast<float>(k[t][0]) * gsum - base, static_cast<float>(k[t][1]) * gsum - base,
                          static_cast<float>(k[t][2]) * gsum - base, static_cast<float>(k[t][3]) * gsum - base};
-    } else {
+    } else if (LAZY) {
         const float neg_gmu_neg = -gmu_neg;
 #pragma unroll
         for (int t = 0; t < ITEMS; ++t)
@@ -1146,6 +1220,28 @@ __global__ __launch_bounds__(64) void k_lazy_apply_signs(const PtrTable tab, con
                     (void)apply4<A2SGD_MODE_RETAINED_ERROR>(ld4<NT>(v4 + first + t * 64), acc[t], nmp, mn, gmu_pos,
                                                             neg_gmu_neg);
         }
+    } else {
+        const uint16_t *half = sign + static_cast<uint64_t>(blockIdx.x) * P * 64 + lane;  // sign[b][h][.][lane]
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t)
+            acc[t] = vf4{0.0f, 0.0f, 0.0f, 0.0f};
+        for (uint32_t p = 0; p < P; ++p) {
+            const vf4 *e4 = reinterpret_cast<const vf4 *>(tab.e[p]);
+            const uint32_t d = half[p * 64];
+#pragma unroll
+            for (int t = 0; t < ITEMS; ++t)
+                if (first + t * 64 < nvec) {
+                    const vf4 err = ld4<NT>(e4 + first + t * 64);
+                    const float x[4] = {err.x, err.y, err.z, err.w};
+                    float u[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        u[c] = ((d >> (15u - (4u * t + c))) & 1u) ? gmu_pos : -gmu_neg;
+                        u[c] = (x[c] != x[c]) ? x[c] : u[c];  // the error is NaN exactly where v was
+                    }
+                    acc[t] += vf4{u[0], u[1], u[2], u[3]};
+                }
+        }
     }
 #pragma unroll
     for (int t = 0; t < ITEMS; ++t)
@@ -1157,8 +1253,10 @@ __global__ __launch_bounds__(64) void k_lazy_apply_signs(const PtrTable tab, con
         const uint64_t i = (nvec << 2) + lane;
         float a = 0.0f;
         for (uint32_t p = 0; p < P; ++p) {
-            float v = tab.e[p][i];
+            float v = LAZY ? tab.e[p][i] : tab.g[p][i] + tab.e[p][i];
             a += apply1<A2SGD_MODE_RETAINED_ERROR>(v, hdr->neg_mu_pos[p], hdr->mu_neg[p], gmu_pos, -gmu_neg);
+            if (!LAZY)
+                tab.e[p][i] = v;  // apply1 has turned v into the new error
         }
         w[i] -= eta_over_P * a;
     }
@@ -1312,12 +1410,38 @@ static hipError_t launch_apply_shape(const a2sgd_plan_t &pl, const PtrTable &tab
     return hipErrorInvalidValue;
 }
 
+// The apply pass as two kernels (k_error_signs, then k_apply_signs on the sign words it left): streaming plans in
+// retained-error mode with many workers.  The sign words live where the lazy calls keep theirs.
+static hipError_t launch_apply_two_kernels(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eop, void *ws,
+                                           hipStream_t s)
+{
+    const WsHeader *hdr = static_cast<const WsHeader *>(ws);
+    uint16_t *sign = reinterpret_cast<uint16_t *>(static_cast<char *>(ws) + pl.lazy_sign_offset);
+    // 4 float4 groups of g and of e per thread and 8 workgroups per compute unit (64 KiB of loads in flight per CU):
+    // measured at 16 workers against 8 groups per thread with 6 workgroups per CU, 4.26 ms against 4.65 ms
+    k_error_signs<true, kErrorItems><<<dim3(pl.lazy_blocks * (kLazyItems / kErrorItems), pl.P), dim3(64), 18 * 1024, s>>>(
+        tab, pl.n, hdr, sign);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess)
+        return err;
+    const dim3 grid(pl.lazy_blocks * 2), block(64);
+    if (pl.P >= 16)  // the sign words of 16, 8 or 4 workers are loaded together
+        k_apply_signs<true, 16, false><<<grid, block, kLazySignLds, s>>>(tab, sign, w, pl.n, pl.P, eop, hdr);
+    else if (pl.P >= 8)
+        k_apply_signs<true, 8, false><<<grid, block, kLazySignLds, s>>>(tab, sign, w, pl.n, pl.P, eop, hdr);
+    else
+        k_apply_signs<true, 4, false><<<grid, block, kLazySignLds, s>>>(tab, sign, w, pl.n, pl.P, eop, hdr);
+    return hipGetLastError();
+}
+
 hipError_t launch_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
-                        hipStream_t s)
+                        bool one_kernel, hipStream_t s)
 {
     const float eop = static_cast<float>(static_cast<double>(eta) / static_cast<double>(pl.P));
     const WsHeader *hdr = static_cast<const WsHeader *>(ws);
     const bool lit = pl.mode == A2SGD_MODE_ALG1_LITERAL;
+    if (pl.apply.two_kernels && !one_kernel && !lit && has_e)
+        return launch_apply_two_kernels(pl, tab, w, eop, ws, s);
 #define A2SGD_APPLY_CASE(L, E, N)                                                                              \
     if (lit == L && has_e == E && pl.streaming == N)                                                           \
         return launch_apply_shape<L ? A2SGD_MODE_ALG1_LITERAL : A2SGD_MODE_RETAINED_ERROR, E, N>(pl, tab, w, eop, \
@@ -1509,18 +1633,17 @@ hipError_t launch_lazy_apply(const a2sgd_plan_t &pl, const PtrTable &tab, float 
     // retained-error mode: from the sign bits that the reduction pass left, two workgroups per workgroup of that
     // pass (one per half of its float4 groups)
     const uint16_t *sign = reinterpret_cast<const uint16_t *>(static_cast<const char *>(ws) + pl.lazy_sign_offset);
-    const uint64_t row_halves = 128ull * pl.lazy_blocks;
     const dim3 grid(pl.lazy_blocks * 2), block(64);
     if (pl.streaming) {
         if (pl.P >= 4)
-            k_lazy_apply_signs<true, 4><<<grid, block, kLazySignLds, s>>>(tab, sign, row_halves, w, pl.n, pl.P, eop, hdr);
+            k_apply_signs<true, 4, true><<<grid, block, kLazySignLds, s>>>(tab, sign, w, pl.n, pl.P, eop, hdr);
         else
-            k_lazy_apply_signs<true, 1><<<grid, block, kLazySignLds, s>>>(tab, sign, row_halves, w, pl.n, pl.P, eop, hdr);
+            k_apply_signs<true, 1, true><<<grid, block, kLazySignLds, s>>>(tab, sign, w, pl.n, pl.P, eop, hdr);
     } else {
         if (pl.P >= 4)
-            k_lazy_apply_signs<false, 4><<<grid, block, 0, s>>>(tab, sign, row_halves, w, pl.n, pl.P, eop, hdr);
+            k_apply_signs<false, 4, true><<<grid, block, 0, s>>>(tab, sign, w, pl.n, pl.P, eop, hdr);
         else
-            k_lazy_apply_signs<false, 1><<<grid, block, 0, s>>>(tab, sign, row_halves, w, pl.n, pl.P, eop, hdr);
+            k_apply_signs<false, 1, true><<<grid, block, 0, s>>>(tab, sign, w, pl.n, pl.P, eop, hdr);
     }
     return hipGetLastError();
 }

@@ -313,6 +313,40 @@ def test_streaming_path_with_worker_counts_that_leave_a_short_group(A, n, P):
         assert_array_close(s[p].cpu().numpy(), ref1.e_new[p], f"lazy e[{p}]")
 
 
+@pytest.mark.parametrize("n,P", [(3_200_003, 8), (3_145_728, 8), (1_600_002, 16), (1_574_913, 17), (420_001, 64)])
+def test_two_kernel_apply_pass(A, n, P):
+    """From 8 workers on, streaming plans in retained-error mode write the errors back and update the weights in two
+    kernels, the second working from stored sign bits.  Against the oracle on sizes with every kind of tail (n % 4,
+    part of a 2048-element workgroup, a whole number of them), with exact zeros in g and e so that v = 0 occurs; then with a
+    few NaNs in g, which have no sign bit and take the pass's other branch; over two steps on carried state."""
+    assert (2 * P + 1) * 4 * n > 192 << 20
+    g, e, w = make_case(n * 7 + P, n, P)
+    plan = A.a2sgd_plan(n, P, 0)
+    ws = A.alloc_workspace(plan)
+    for with_nan in (False, True):
+        print(f"case n={n} P={P} nan={with_nan}", flush=True)
+        if with_nan:
+            rng = np.random.default_rng(n)
+            for p in (0, P - 1):
+                g[p][rng.integers(0, n, 5)] = np.nan
+            g[1][n - 1] = np.nan  # in the scalar tail when n % 4 != 0
+        gd, ed, wd = [dev(x) for x in g], [dev(x) for x in e], dev(w)
+        e_o, w_o = e, w
+        for t in range(2):
+            A.a2sgd_local_averages(plan, gd, ed, ws)
+            A.a2sgd_global_average(plan, ws)
+            A.a2sgd_apply_and_update_error(plan, gd, ed, wd, 0.1, ws)
+            stats, gmu = A.a2sgd_read_stats(plan, ws)
+            ref = O.step(g, e_o, w_o, 0.1, 0)
+            compare_stats(stats, gmu, ref)
+            e_o, w_o = ref.e_new, ref.w_new
+            for p in range(P):
+                assert_array_close(ed[p].cpu().numpy(), e_o[p], f"step {t} e[{p}]")
+            assert_array_close(wd.cpu().numpy(), w_o, f"step {t} w")
+        for p in range(P):
+            assert np.array_equal(gd[p].cpu().numpy().view(np.uint32), g[p].view(np.uint32))  # g is read-only
+
+
 def test_runs_on_a_side_stream_and_respects_stream_order(A):
     g, e, w = make_case(4242, 1_000_003, 4)
     ref = O.step(g, e, w, 0.1, 0)

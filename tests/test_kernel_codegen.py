@@ -64,8 +64,9 @@ def test_every_hand_written_store_has_its_wait_states(asm):
                 seen += 1
                 assert lines[k + 1].startswith("s_nop 1"), f"{name}: store without its wait states"
     assert seen > 100
-    for pat in (r"_ZN5a2sgd15k_lazy_partialsILb1E", r"_ZN5a2sgd18k_lazy_materializeILb1E", r"_ZN5a2sgd18k_lazy_apply_signsILb1E",
-                r"_ZN5a2sgd12k_dense_stepILb1E", r"_ZN5a2sgd11k_seg_applyILi[01]ELb[01]ELb1E"):
+    for pat in (r"_ZN5a2sgd15k_lazy_partialsILb1E", r"_ZN5a2sgd18k_lazy_materializeILb1E", r"_ZN5a2sgd13k_apply_signsILb1E",
+                r"_ZN5a2sgd13k_error_signsILb1E", r"_ZN5a2sgd12k_dense_stepILb1E",
+                r"_ZN5a2sgd11k_seg_applyILi[01]ELb[01]ELb1E"):
         names = [k for k in kernels if re.match(pat, k)]
         assert names, pat
         for name in names:
