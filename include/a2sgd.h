@@ -195,9 +195,11 @@ a2sgd_status_t a2sgd_dense_step(const a2sgd_plan_t *plan, const float *const *g,
  * has one pair of means over all its tensors together, as in the paper, and the tensors only say which elements of
  * the buffers belong to the model.  Elements outside every tensor (possible with seg_offset) are left alone by every
  * call except a2sgd_dense_step and a2sgd_export_mask, which do not depend on the segments.
- * a2sgd_local_averages, a2sgd_global_average, a2sgd_apply_and_update_error and a2sgd_step work as described above.
- * Not available on such a plan (A2SGD_ERR_INVALID_ARG): the replica calls and the lazy calls, and a2sgd_read_stats
- * unless the means are pooled.  The workspace of such a plan holds static lookup tables: */
+ * a2sgd_local_averages, a2sgd_global_average, a2sgd_apply_and_update_error and a2sgd_step work as described above,
+ * and so do the replica calls and the lazy calls further down, each element with the means of its tensor (the lazy
+ * state carries one pair of means per worker and tensor; its apply pass reads v in both modes, 16nP + 8n bytes per
+ * step).  Not available on such a plan (A2SGD_ERR_INVALID_ARG): a2sgd_step_static, the export/import pair, and
+ * a2sgd_read_stats unless the means are pooled.  The workspace of such a plan holds static lookup tables: */
 
 /* Uploads the plan's segment tables into the workspace, and last a tag that identifies them.  Required once per
  * workspace, before its first use, when the plan has num_segments >= 1; a no-op otherwise.  Asynchronous on

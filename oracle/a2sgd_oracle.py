@@ -306,3 +306,36 @@ def step_segmented(g: Sequence[np.ndarray], e: Optional[Sequence[Optional[np.nda
         w_new[lo:hi] = r.w_new
         per_seg.append(r)
     return per_seg, e_new, w_new
+
+
+def step_replicas_segmented(g: Sequence[np.ndarray], e: Optional[Sequence[Optional[np.ndarray]]], w: Sequence[np.ndarray],
+                            eta: float, mode: int, seg_lengths: Sequence[int],
+                            seg_offsets: Optional[Sequence[int]] = None, pooled: bool = False):
+    """step_replicas on buffers that consist of tensors: one weight vector per worker, each tensor with its own means
+    (pooled: one pair per worker over the tensors laid end to end).  The same slicing as step_segmented; elements
+    outside every tensor come back unchanged.  Returns (e_new list, w_new list)."""
+    P = len(g)
+    n = int(np.asarray(w[0]).shape[0])
+    lengths = [int(x) for x in seg_lengths]
+    offsets = [int(x) for x in (seg_offsets if seg_offsets is not None else np.concatenate([[0], np.cumsum(lengths)[:-1]]))]
+    ranges = [(o, o + l) for o, l in zip(offsets, lengths)]
+    e_new = [np.array(x, dtype=np.float32, copy=True) for x in e] if e is not None else [np.zeros(n, np.float32) for _ in range(P)]
+    w_new = [np.array(x, dtype=np.float32, copy=True) for x in w]
+    if pooled:
+        cat = lambda x: np.concatenate([x[lo:hi] for lo, hi in ranges])
+        _, _, en, wn = step_replicas([cat(x) for x in g], [cat(x) for x in e] if e is not None else None,
+                                     [cat(x) for x in w], eta, mode)
+        pos = 0
+        for lo, hi in ranges:
+            for p in range(P):
+                e_new[p][lo:hi] = en[p][pos:pos + hi - lo]
+                w_new[p][lo:hi] = wn[p][pos:pos + hi - lo]
+            pos += hi - lo
+        return e_new, w_new
+    for lo, hi in ranges:
+        _, _, en, wn = step_replicas([x[lo:hi] for x in g], [x[lo:hi] for x in e] if e is not None else None,
+                                     [x[lo:hi] for x in w], eta, mode)
+        for p in range(P):
+            e_new[p][lo:hi] = en[p]
+            w_new[p][lo:hi] = wn[p]
+    return e_new, w_new

@@ -806,8 +806,6 @@ a2sgd_status_t a2sgd_apply_and_update_error_replicas(const a2sgd_plan_t *plan, c
     a2sgd_status_t st = check_g_e(plan, g, e, &has_e);
     if (st != A2SGD_OK)
         return st;
-    if (segmented(plan))
-        return A2SGD_ERR_INVALID_ARG;
     if ((st = check_table(w, plan->P, true, &has_w)) != A2SGD_OK)
         return st;
     if ((st = check_buffer(workspace)) != A2SGD_OK)
@@ -819,6 +817,10 @@ a2sgd_status_t a2sgd_apply_and_update_error_replicas(const a2sgd_plan_t *plan, c
     PtrTable tab;
     ReplicaTable wt;
     fill_table(tab, plan->P, g, has_e ? e : nullptr);
+    if (segmented(plan)) {
+        fill_replicas(wt, plan->P, w);
+        return dev(launch_seg_apply_replicas(*plan, tab, wt, has_e, eta, workspace, static_cast<hipStream_t>(stream)));
+    }
     if (plan->P == 1)  // one worker: its own replica is the shared vector, and that pass is the tuned one
         return dev(launch_apply(*plan, tab, has_e, w[0], eta, workspace, false, static_cast<hipStream_t>(stream)));
     fill_replicas(wt, plan->P, w);
@@ -832,8 +834,6 @@ a2sgd_status_t a2sgd_step_replicas(const a2sgd_plan_t *plan, const float *const 
     a2sgd_status_t st = check_g_e(plan, g, e, &has_e);
     if (st != A2SGD_OK)
         return st;
-    if (segmented(plan))
-        return A2SGD_ERR_INVALID_ARG;
     if ((st = check_table(w, plan->P, true, &has_w)) != A2SGD_OK)
         return st;
     if ((st = check_buffer(workspace)) != A2SGD_OK)
@@ -904,20 +904,22 @@ a2sgd_status_t a2sgd_replica_drift(const a2sgd_plan_t *plan, const float *const 
 
 a2sgd_status_t a2sgd_lazy_reset(const a2sgd_plan_t *plan, void *workspace, a2sgd_stream_t stream)
 {
-    if (plan == nullptr || segmented(plan))
+    if (plan == nullptr)
         return A2SGD_ERR_INVALID_ARG;
     a2sgd_status_t st = check_buffer(workspace);
     if (st != A2SGD_OK)
         return st;
     if ((st = check_device(plan)) != A2SGD_OK)
         return st;
+    if (segmented(plan))
+        return dev(launch_seg_lazy_reset(*plan, workspace, static_cast<hipStream_t>(stream)));
     return dev(launch_lazy_reset(*plan, workspace, static_cast<hipStream_t>(stream)));
 }
 
 a2sgd_status_t a2sgd_lazy_local_averages(const a2sgd_plan_t *plan, const float *const *g, float *const *s,
                                          void *workspace, a2sgd_stream_t stream)
 {
-    if (plan == nullptr || segmented(plan))
+    if (plan == nullptr)
         return A2SGD_ERR_INVALID_ARG;
     bool has_g = false, has_s = false;
     a2sgd_status_t st = check_table(g, plan->P, true, &has_g);
@@ -934,13 +936,19 @@ a2sgd_status_t a2sgd_lazy_local_averages(const a2sgd_plan_t *plan, const float *
     PtrTable tab;
     fill_table(tab, plan->P, g, s);
     plan->last_token = 0;
+    if (segmented(plan)) {
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        if ((st = dev(launch_seg_lazy_partials(*plan, tab, workspace, s))) != A2SGD_OK)
+            return st;
+        return dev(launch_seg_finalize(*plan, workspace, s));
+    }
     return dev(launch_lazy_partials(*plan, tab, workspace, static_cast<hipStream_t>(stream)));
 }
 
 a2sgd_status_t a2sgd_lazy_apply(const a2sgd_plan_t *plan, const float *const *s, float *w, float eta, void *workspace,
                                 a2sgd_stream_t stream)
 {
-    if (plan == nullptr || segmented(plan))
+    if (plan == nullptr)
         return A2SGD_ERR_INVALID_ARG;
     bool has_s = false;
     a2sgd_status_t st = check_table(s, plan->P, true, &has_s);
@@ -959,6 +967,12 @@ a2sgd_status_t a2sgd_lazy_apply(const a2sgd_plan_t *plan, const float *const *s,
     if ((st = check_device(plan)) != A2SGD_OK)
         return st;
     PtrTable tab;
+    if (segmented(plan)) {
+        // the per-tensor apply pass with the stored v in the place of the gradient and no error buffer: it reads v,
+        // forms the update from its sign group (literal mode: and its error) and writes w only
+        fill_table(tab, plan->P, s, nullptr);
+        return dev(launch_seg_apply(*plan, tab, false, w, eta, workspace, static_cast<hipStream_t>(stream)));
+    }
     fill_table(tab, plan->P, s, s);  // the pass reads the state buffers only
     return dev(launch_lazy_apply(*plan, tab, w, eta, workspace, static_cast<hipStream_t>(stream)));
 }
@@ -967,7 +981,7 @@ a2sgd_status_t a2sgd_lazy_step(const a2sgd_plan_t *plan, const float *const *g, 
                                void *workspace, a2sgd_stream_t stream)
 {
     // validate everything first so that a failed step has enqueued nothing
-    if (plan == nullptr || segmented(plan))
+    if (plan == nullptr)
         return A2SGD_ERR_INVALID_ARG;
     bool has_g = false, has_s = false;
     a2sgd_status_t st = check_table(g, plan->P, true, &has_g);
@@ -991,7 +1005,7 @@ a2sgd_status_t a2sgd_lazy_step(const a2sgd_plan_t *plan, const float *const *g, 
 a2sgd_status_t a2sgd_lazy_materialize(const a2sgd_plan_t *plan, float *const *s, void *workspace,
                                       a2sgd_stream_t stream)
 {
-    if (plan == nullptr || segmented(plan))
+    if (plan == nullptr)
         return A2SGD_ERR_INVALID_ARG;
     bool has_s = false;
     a2sgd_status_t st = check_table(s, plan->P, true, &has_s);
@@ -1003,6 +1017,8 @@ a2sgd_status_t a2sgd_lazy_materialize(const a2sgd_plan_t *plan, float *const *s,
         return st;
     PtrTable tab;
     fill_table(tab, plan->P, s, s);
+    if (segmented(plan))
+        return dev(launch_seg_materialize(*plan, tab, workspace, static_cast<hipStream_t>(stream)));
     return dev(launch_lazy_materialize(*plan, tab, workspace, static_cast<hipStream_t>(stream)));
 }
 

@@ -117,6 +117,19 @@ __device__ __forceinline__ vf4 apply4(vf4 v, vf4 &acc, float neg_mu_pos, float m
     return vf4{x, y, z, t};
 }
 
+// The pending error of one stored element of the lazy state: s - enc(s) with the carried means (Eq. 2, Algorithm 1
+// line 4).  A NaN stays a NaN.
+__device__ __forceinline__ float pending_error(float s, float neg_mu_pos, float mu_neg)
+{
+    return s + (s >= 0.0f ? neg_mu_pos : mu_neg);
+}
+
+__device__ __forceinline__ vf4 pending_error4(vf4 s, float neg_mu_pos, float mu_neg)
+{
+    return vf4{pending_error(s.x, neg_mu_pos, mu_neg), pending_error(s.y, neg_mu_pos, mu_neg),
+               pending_error(s.z, neg_mu_pos, mu_neg), pending_error(s.w, neg_mu_pos, mu_neg)};
+}
+
 // A zero the compiler cannot see through, in a vector register.  Added to an index it turns a load with a
 // wavefront-uniform address into an ordinary vector load.  The apply pass wants that for the handful of means
 // it reads from the workspace: vector loads return in issue order and are counted apart from the scalar loads

@@ -207,6 +207,12 @@ hipError_t launch_seg_finalize(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
 hipError_t launch_seg_global(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
 hipError_t launch_seg_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
                             hipStream_t s);
+// Replica calls and the lazy state on plans with tensors.
+hipError_t launch_seg_apply_replicas(const a2sgd_plan_t &pl, const PtrTable &tab, const ReplicaTable &wt, bool has_e,
+                                     float eta, void *ws, hipStream_t s);
+hipError_t launch_seg_lazy_partials(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s);
+hipError_t launch_seg_lazy_reset(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
+hipError_t launch_seg_materialize(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s);
 hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, uint64_t *mask, hipStream_t s);
 hipError_t launch_dense_step(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eta, hipStream_t s);
 

@@ -846,18 +846,6 @@ __global__ void k_replica_drift_finalize(const uint64_t n, const uint32_t P, con
 // means, and e = v - enc(v) (Eq. 2, Algorithm 1 line 4) is formed when the buffer is next read
 // ---------------------------------------------------------------------------------------------------------
 
-// The pending error of one stored element: s - enc(s) with the carried means.  A NaN stays a NaN.
-__device__ __forceinline__ float pending_error(float s, float neg_mu_pos, float mu_neg)
-{
-    return s + (s >= 0.0f ? neg_mu_pos : mu_neg);
-}
-
-__device__ __forceinline__ vf4 pending_error4(vf4 s, float neg_mu_pos, float mu_neg)
-{
-    return vf4{pending_error(s.x, neg_mu_pos, mu_neg), pending_error(s.y, neg_mu_pos, mu_neg),
-               pending_error(s.z, neg_mu_pos, mu_neg), pending_error(s.w, neg_mu_pos, mu_neg)};
-}
-
 // Reduction pass on the lazy state: each element is e = pending error of the stored value, v = fl32(g + e); v is
 // written back in place of the stored value and enters the sums and counts.  tab.e holds the state buffers.
 // 8 bytes read and 4 written per element-worker.  Because it stores, it has the shape of the apply pass and not of

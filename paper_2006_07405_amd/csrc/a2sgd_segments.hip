@@ -69,13 +69,19 @@ __global__ void k_seg_mark(WsHeader *__restrict__ hdr, const uint64_t tag)
 // ---------------------------------------------------------------------------------------------------------
 constexpr int kSegUnroll = 4;
 
-template <bool HAS_E, bool NT>
+// LAZY: the reduction on the lazy error state.  tab.e holds the state buffers, which keep the folded vector of the
+// last step; an element's error is its pending error with the carried means of its tensor (the tables the last
+// step's global pass filled), v = fl32(g + that error) is written back in place of the stored value and enters the
+// sums and counts.
+template <bool HAS_E, bool NT, bool LAZY>
 __global__ __launch_bounds__(kBlock) void k_seg_partials(const PtrTable tab, const SegView sv)
 {
-    const uint32_t p = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    static_assert(HAS_E || !LAZY, "the lazy state is the e table");
+    const uint32_t p = blockIdx.y, P = gridDim.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *__restrict__ g = tab.g[p];
-    const float *__restrict__ e = HAS_E ? tab.e[p] : nullptr;
-    const vf4 *g4 = reinterpret_cast<const vf4 *>(g), *e4 = reinterpret_cast<const vf4 *>(e);
+    float *e = HAS_E ? tab.e[p] : nullptr;
+    const vf4 *g4 = reinterpret_cast<const vf4 *>(g);
+    vf4 *e4 = reinterpret_cast<vf4 *>(e);
     __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
     __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
 
@@ -90,10 +96,22 @@ __global__ __launch_bounds__(kBlock) void k_seg_partials(const PtrTable tab, con
         if (a > hi)
             a = hi;
         const uint64_t z = a + ((hi - a) & ~static_cast<uint64_t>(3));  // end of the float4 groups
+        float nmp = 0.0f, mn = 0.0f;  // the carried means of this item's tensor
+        if (LAZY) {
+            nmp = sv.neg_mu_pos[static_cast<size_t>(item.seg) * P + p];
+            mn = sv.mu_neg[static_cast<size_t>(item.seg) * P + p];
+        }
+        auto scalar = [&](const uint64_t i) {  // one element outside the float4 groups
+            float v = g[i];
+            if (HAS_E)
+                v += LAZY ? pending_error(e[i], nmp, mn) : e[i];
+            if (LAZY)
+                e[i] = v;
+            return v;
+        };
         LaneAcc acc;
         if (tid < a - lo) {  // head, at most 3 elements
-            const uint64_t i = lo + tid;
-            acc.add(HAS_E ? g[i] + e[i] : g[i]);
+            acc.add(scalar(lo + tid));
             acc.flush();
         }
         const uint64_t v_lo = a >> 2, v_hi = z >> 2;
@@ -108,13 +126,16 @@ __global__ __launch_bounds__(kBlock) void k_seg_partials(const PtrTable tab, con
                 }
 #pragma unroll
             for (int u = 0; u < kSegUnroll; ++u)
-                if (i0 + u * kBlock < v_hi)
-                    acc.add4(HAS_E ? gv[u] + ev[u] : gv[u]);
+                if (i0 + u * kBlock < v_hi) {
+                    const vf4 v = !HAS_E ? gv[u] : LAZY ? gv[u] + pending_error4(ev[u], nmp, mn) : gv[u] + ev[u];
+                    if (LAZY)
+                        st4<NT>(e4 + i0 + u * kBlock, v);
+                    acc.add4(v);
+                }
             acc.flush();
         }
         if (tid < hi - z) {  // tail, at most 3 elements
-            const uint64_t i = z + tid;
-            acc.add(HAS_E ? g[i] + e[i] : g[i]);
+            acc.add(scalar(z + tid));
             acc.flush();
         }
         // block reduction of this item (the counts are wavefront totals, valid in lane 0: indices grow with the lane)
@@ -417,6 +438,137 @@ __global__ __launch_bounds__(BLOCK) void k_seg_apply(const PtrTable tab, float *
     }
 }
 
+// One weight vector per worker on a plan with tensors (Algorithm 1 line 7 as each worker runs it, per tensor):
+// w^p <- w^p - eta * u^p with the means of the element's tensor.  Same lookup as k_seg_apply; workers in groups of
+// UP whose g, e and w^p loads are issued together.
+template <int MODE, bool HAS_E>
+__device__ __forceinline__ void seg_apply_element_replicas(const PtrTable &tab, const ReplicaTable &wt, const uint64_t idx,
+                                                           const uint32_t s, const uint32_t P, const float eta,
+                                                           const SegView &sv)
+{
+    const float gmu_pos = sv.gmu[2 * s], neg_gmu_neg = sv.gmu[2 * s + 1];
+    for (uint32_t p = 0; p < P; ++p) {
+        float v = tab.g[p][idx];
+        if (HAS_E)
+            v += tab.e[p][idx];
+        const float u = apply1<MODE>(v, sv.neg_mu_pos[static_cast<size_t>(s) * P + p],
+                                     sv.mu_neg[static_cast<size_t>(s) * P + p], gmu_pos, neg_gmu_neg);
+        if (HAS_E)
+            tab.e[p][idx] = v;
+        wt.w[p][idx] -= eta * u;
+    }
+}
+
+template <int MODE, bool HAS_E, bool NT, int UP, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_seg_apply_replicas(const PtrTable tab, const ReplicaTable wt, const uint64_t n,
+                                                              const uint32_t P, const float eta, const SegView sv)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint64_t nvec = n >> 2;
+    const uint64_t first = static_cast<uint64_t>(blockIdx.x) * BLOCK;
+    const uint64_t i = first + tid;
+    static_assert(BLOCK * 4 == (1 << kSegCoarseShift), "one lookup entry per apply workgroup");
+    const uint32_t entry = sv.coarse[blockIdx.x];
+    if (!seg_tables_ok(sv))
+        return;
+    if (i < nvec) {
+        const uint32_t s0 = entry & ~kSegInsideBit;
+        if (entry & kSegInsideBit) {
+            const float *nmp = sv.neg_mu_pos + static_cast<size_t>(s0) * P;
+            const float *mn = sv.mu_neg + static_cast<size_t>(s0) * P;
+            const float gmu_pos = sv.gmu[2 * s0], neg_gmu_neg = sv.gmu[2 * s0 + 1];
+            for (uint32_t p0 = 0; p0 < P; p0 += UP) {
+                vf4 v[UP], ev[UP], wv[UP];
+#pragma unroll
+                for (int u = 0; u < UP; ++u)
+                    if (p0 + u < P) {
+                        v[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.g[p0 + u]) + i);
+                        if (HAS_E)
+                            ev[u] = ld4<NT>(reinterpret_cast<const vf4 *>(tab.e[p0 + u]) + i);
+                        wv[u] = ld4<NT>(reinterpret_cast<const vf4 *>(wt.w[p0 + u]) + i);
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < UP; ++u)
+                    if (p0 + u < P) {
+                        const vf4 vv = HAS_E ? v[u] + ev[u] : v[u];
+                        vf4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
+                        const vf4 err = apply4<MODE>(vv, upd, nmp[p0 + u], mn[p0 + u], gmu_pos, neg_gmu_neg);
+                        if (HAS_E)
+                            st4<NT>(reinterpret_cast<vf4 *>(tab.e[p0 + u]) + i, err);
+                        const vf4 wn = wv[u] - eta * upd;
+                        st4<NT>(reinterpret_cast<vf4 *>(wt.w[p0 + u]) + i, wn);
+                    }
+            }
+        } else {
+            // a boundary or padding inside the workgroup: element by element, padding is not touched
+            uint32_t sx = s0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                sx = seg_of(sv, sx, (i << 2) + c);
+                if (sv.seg_start[sx] <= (i << 2) + c)
+                    seg_apply_element_replicas<MODE, HAS_E>(tab, wt, (i << 2) + c, sx, P, eta, sv);
+            }
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
+        const uint64_t idx = (nvec << 2) + tid;
+        const uint32_t s = seg_of(sv, sv.coarse[idx >> kSegCoarseShift] & ~kSegInsideBit, idx);
+        if (sv.seg_start[s] <= idx)
+            seg_apply_element_replicas<MODE, HAS_E>(tab, wt, idx, s, P, eta, sv);
+    }
+}
+
+// Lazy state on a plan with tensors, back to true errors: s <- pending error of s with the carried means of the
+// element's tensor.  grid = (workgroups of 64 float4 groups, P).
+template <bool NT>
+__global__ __launch_bounds__(64) void k_seg_materialize(const PtrTable tab, const uint64_t n, const SegView sv)
+{
+    const uint32_t p = blockIdx.y, P = gridDim.y, tid = threadIdx.x;
+    const uint64_t nvec = n >> 2;
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * 64 + tid;
+    const uint32_t entry = sv.coarse[blockIdx.x];
+    if (!seg_tables_ok(sv))
+        return;
+    float *s = tab.e[p];
+    if (i < nvec) {
+        const uint32_t s0 = entry & ~kSegInsideBit;
+        vf4 *s4 = reinterpret_cast<vf4 *>(s) + i;
+        if (entry & kSegInsideBit) {
+            const vf4 err = pending_error4(ld4<NT>(s4), sv.neg_mu_pos[static_cast<size_t>(s0) * P + p],
+                                           sv.mu_neg[static_cast<size_t>(s0) * P + p]);
+            st4<NT>(s4, err);
+        } else {
+            uint32_t sx = s0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint64_t idx = (i << 2) + c;
+                sx = seg_of(sv, sx, idx);
+                if (sv.seg_start[sx] <= idx)
+                    s[idx] = pending_error(s[idx], sv.neg_mu_pos[static_cast<size_t>(sx) * P + p],
+                                           sv.mu_neg[static_cast<size_t>(sx) * P + p]);
+            }
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
+        const uint64_t idx = (nvec << 2) + tid;
+        const uint32_t sx = seg_of(sv, sv.coarse[idx >> kSegCoarseShift] & ~kSegInsideBit, idx);
+        if (sv.seg_start[sx] <= idx)
+            s[idx] = pending_error(s[idx], sv.neg_mu_pos[static_cast<size_t>(sx) * P + p],
+                                   sv.mu_neg[static_cast<size_t>(sx) * P + p]);
+    }
+}
+
+// Clears the carried means of every tensor and worker: from here on the state buffers are read as true errors.
+__global__ __launch_bounds__(256) void k_seg_lazy_reset(const uint64_t entries, const SegView sv)
+{
+    const uint64_t k = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (k < entries) {
+        sv.neg_mu_pos[k] = 0.0f;
+        sv.mu_neg[k] = 0.0f;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------------------------------------
@@ -427,15 +579,26 @@ hipError_t launch_seg_partials(const a2sgd_plan_t &pl, const PtrTable &tab, bool
     const dim3 grid(pl.seg.blocks, pl.P), block(kBlock);
     if (has_e) {
         if (pl.streaming)
-            k_seg_partials<true, true><<<grid, block, 0, s>>>(tab, sv);
+            k_seg_partials<true, true, false><<<grid, block, 0, s>>>(tab, sv);
         else
-            k_seg_partials<true, false><<<grid, block, 0, s>>>(tab, sv);
+            k_seg_partials<true, false, false><<<grid, block, 0, s>>>(tab, sv);
     } else {
         if (pl.streaming)
-            k_seg_partials<false, true><<<grid, block, 0, s>>>(tab, sv);
+            k_seg_partials<false, true, false><<<grid, block, 0, s>>>(tab, sv);
         else
-            k_seg_partials<false, false><<<grid, block, 0, s>>>(tab, sv);
+            k_seg_partials<false, false, false><<<grid, block, 0, s>>>(tab, sv);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_seg_lazy_partials(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s)
+{
+    const SegView sv = seg_view(pl, ws);
+    const dim3 grid(pl.seg.blocks, pl.P), block(kBlock);
+    if (pl.streaming)
+        k_seg_partials<true, true, true><<<grid, block, 0, s>>>(tab, sv);
+    else
+        k_seg_partials<true, false, true><<<grid, block, 0, s>>>(tab, sv);
     return hipGetLastError();
 }
 
@@ -502,6 +665,65 @@ hipError_t launch_seg_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool ha
     A2SGD_SEG_CASE(true, false, false)
 #undef A2SGD_SEG_CASE
     return hipErrorInvalidValue;
+}
+
+template <int MODE, bool HAS_E, bool NT>
+static hipError_t launch_seg_apply_replicas_shape(const a2sgd_plan_t &pl, const PtrTable &tab, const ReplicaTable &wt,
+                                                  float eta, const SegView &sv, hipStream_t s)
+{
+    constexpr int kThreads = 64;
+    const uint64_t nvec = (pl.n + 3) >> 2;
+    const dim3 grid(static_cast<uint32_t>((nvec + kThreads - 1) / kThreads)), block(kThreads);
+    const uint32_t lds = pl.streaming ? 14 * 1024 : 0;  // 11 workgroups per CU, as the shared-weight pass at P = 4
+    if (pl.P >= 4)
+        k_seg_apply_replicas<MODE, HAS_E, NT, 4, kThreads><<<grid, block, lds, s>>>(tab, wt, pl.n, pl.P, eta, sv);
+    else
+        k_seg_apply_replicas<MODE, HAS_E, NT, 2, kThreads><<<grid, block, lds, s>>>(tab, wt, pl.n, pl.P, eta, sv);
+    return hipGetLastError();
+}
+
+hipError_t launch_seg_apply_replicas(const a2sgd_plan_t &pl, const PtrTable &tab, const ReplicaTable &wt, bool has_e,
+                                     float eta, void *ws, hipStream_t s)
+{
+    const SegView sv = seg_view(pl, ws);
+    const bool lit = pl.mode == A2SGD_MODE_ALG1_LITERAL;
+#define A2SGD_SEG_REPL_CASE(L, E, N)                                                                                  \
+    if (lit == L && has_e == E && pl.streaming == N)                                                                  \
+        return launch_seg_apply_replicas_shape<L ? A2SGD_MODE_ALG1_LITERAL : A2SGD_MODE_RETAINED_ERROR, E, N>(pl, tab, wt, \
+                                                                                                              eta, sv, s);
+    A2SGD_SEG_REPL_CASE(false, true, true)
+    A2SGD_SEG_REPL_CASE(false, true, false)
+    A2SGD_SEG_REPL_CASE(false, false, true)
+    A2SGD_SEG_REPL_CASE(false, false, false)
+    A2SGD_SEG_REPL_CASE(true, true, true)
+    A2SGD_SEG_REPL_CASE(true, true, false)
+    A2SGD_SEG_REPL_CASE(true, false, true)
+    A2SGD_SEG_REPL_CASE(true, false, false)
+#undef A2SGD_SEG_REPL_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_seg_lazy_reset(const a2sgd_plan_t &pl, void *ws, hipStream_t s)
+{
+    const SegView sv = seg_view(pl, ws);
+    const uint64_t entries = static_cast<uint64_t>(sv.S) * pl.P;
+    k_seg_lazy_reset<<<dim3(static_cast<uint32_t>((entries + 255) / 256)), dim3(256), 0, s>>>(entries, sv);
+    return hipGetLastError();
+}
+
+hipError_t launch_seg_materialize(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s)
+{
+    const SegView sv = seg_view(pl, ws);
+    const uint64_t nvec = (pl.n + 3) >> 2;
+    const dim3 grid(static_cast<uint32_t>((nvec + 63) / 64), pl.P), block(64);
+    if (pl.streaming)
+        k_seg_materialize<true><<<grid, block, 12 * 1024, s>>>(tab, pl.n, sv);
+    else
+        k_seg_materialize<false><<<grid, block, 0, s>>>(tab, pl.n, sv);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess)
+        return err;
+    return launch_seg_lazy_reset(pl, ws, s);
 }
 
 }  // namespace a2sgd

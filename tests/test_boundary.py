@@ -117,7 +117,6 @@ def test_segmented_plan_validation_and_workspace(A):
     R = A.raw
     assert R.a2sgd_read_stats(seg.handle, 0x30000, None, None, None) == A.A2SGD_ERR_INVALID_ARG
     assert R.a2sgd_read_segment_stats(whole.handle, 0x30000, None, None, None) == A.A2SGD_ERR_INVALID_ARG
-    assert R.a2sgd_lazy_reset(seg.handle, 0x30000, None) == A.A2SGD_ERR_INVALID_ARG
     assert R.a2sgd_workspace_init(whole.handle, 0x30000, None) == A.A2SGD_OK  # nothing to upload
 
 

@@ -257,3 +257,177 @@ def test_config2_full_size_per_tensor(A):
         for p in range(P):
             assert_array_close(e[p][lo:hi].cpu().numpy(), e_ref[p][lo:hi], f"e[{p}] tensor {s}")
         assert_array_close(w[lo:hi].cpu().numpy(), w_ref[lo:hi], f"w tensor {s}")
+
+
+# ---- one weight vector per worker, and the lazy error state, on plans with tensors ----------------------------------
+
+def run_replica_case(A, seed, n, P, mode, lengths, offsets=None, pooled=False):
+    """a2sgd_step_replicas and a2sgd_dense_step_replicas on a plan with tensors against the oracle's per-replica step
+    applied tensor by tensor; padding (NaN in every buffer) must come back untouched."""
+    rng = np.random.default_rng(seed)
+    offs = offsets if offsets is not None else list(np.concatenate([[0], np.cumsum(lengths)[:-1]]))
+    member = np.zeros(n, bool)
+    scale = np.ones(n, f32)
+    for o, l in zip(offs, lengths):
+        member[o:o + l] = True
+        scale[o:o + l] = 10.0 ** rng.uniform(-5, -2)
+    g = [(rng.standard_normal(n).astype(f32) * scale) for _ in range(P)]
+    e = [(rng.standard_normal(n).astype(f32) * scale * f32(0.5)) for _ in range(P)]
+    w = [(rng.standard_normal(n) * 0.02).astype(f32) for _ in range(P)]
+    for x in g + e + w:
+        x[~member] = np.nan
+    plan = A.a2sgd_plan(n, P, mode, 0, seg_lengths=lengths, seg_offsets=offsets, pooled_means=pooled)
+    ws = A.alloc_workspace(plan)
+    gd, ed, wd = [dev(x) for x in g], [dev(x) for x in e], [dev(x) for x in w]
+    A.a2sgd_step_replicas(plan, gd, ed, wd, 0.1, ws)
+    e_ref, w_ref = O.step_replicas_segmented(g, e, w, 0.1, mode, lengths, offsets, pooled)
+    for p in range(P):
+        e_got, w_got = ed[p].cpu().numpy(), wd[p].cpu().numpy()
+        assert np.isnan(e_got[~member]).all() and np.isnan(w_got[~member]).all(), "padding was written"
+        for o, l in zip(offs, lengths):
+            assert_array_close(e_got[o:o + l], e_ref[p][o:o + l], f"e[{p}] tensor at {o}")
+            assert_array_close(w_got[o:o + l], w_ref[p][o:o + l], f"w[{p}] tensor at {o}")
+
+
+@pytest.mark.parametrize("seg", LAYOUTS, ids=[f"layout{i}" for i in range(len(LAYOUTS))])
+def test_replicas_on_tensor_plans(A, seg):
+    n = sum(seg)
+    for P, mode in ((1, 0), (3, 1), (4, 0), (9, 1)):
+        print(f"case S={len(seg)} n={n} P={P} mode={mode}", flush=True)
+        run_replica_case(A, n + P, n, P, mode, seg)
+
+
+@pytest.mark.parametrize("case", PADDED, ids=[f"padded{i}" for i in range(len(PADDED))])
+def test_replicas_on_tensor_plans_with_padding(A, case):
+    n, lengths, offsets = case
+    for P, mode, pooled in ((2, 0, False), (3, 1, True), (5, 0, True)):
+        print(f"case n={n} S={len(lengths)} P={P} mode={mode} pooled={pooled}", flush=True)
+        run_replica_case(A, n + P, n, P, mode, lengths, offsets, pooled)
+
+
+def test_replicas_on_a_tensor_plan_streaming(A):
+    seg = [1_000_003, 5, 777_777, 64, 1_300_001, 131_072, 2, 291_079]
+    assert (2 * 7 + 1) * 4 * sum(seg) > 192 << 20
+    run_replica_case(A, 77, sum(seg), 7, 0, seg)
+
+
+def run_lazy_case(A, seed, n, P, mode, lengths, offsets=None, pooled=False, steps=4):
+    """Steps on the lazy state of a plan with tensors (the buffers hold v, every tensor's pending error is formed with
+    that tensor's carried means) against eager steps of the per-tensor oracle: same statistics and w at every step,
+    same errors once materialised; padding untouched."""
+    rng = np.random.default_rng(seed)
+    offs = offsets if offsets is not None else list(np.concatenate([[0], np.cumsum(lengths)[:-1]]))
+    member = np.zeros(n, bool)
+    scale = np.ones(n, f32)
+    for o, l in zip(offs, lengths):
+        member[o:o + l] = True
+        scale[o:o + l] = 10.0 ** rng.uniform(-5, -2)
+    e0 = [(rng.standard_normal(n).astype(f32) * scale * f32(0.5)) for _ in range(P)]
+    w0 = (rng.standard_normal(n) * 0.02).astype(f32)
+    for x in e0 + [w0]:
+        x[~member] = np.nan
+    plan = A.a2sgd_plan(n, P, mode, 0, seg_lengths=lengths, seg_offsets=offsets, pooled_means=pooled)
+    ws = A.alloc_workspace(plan)
+    s, wd = [dev(x) for x in e0], dev(w0)
+    e_o, w_o = [x.copy() for x in e0], w0.copy()
+    A.a2sgd_lazy_reset(plan, ws)
+    for t in range(steps):
+        g = [(rng.standard_normal(n).astype(f32) * scale) for _ in range(P)]
+        for x in g:
+            x[~member] = np.nan
+        gd = [dev(x) for x in g]
+        res, e_o, w_o = O.step_segmented(g, e_o, w_o, 0.1, mode, lengths, offsets, pooled)
+        A.a2sgd_lazy_step(plan, gd, s, wd, 0.1, ws)
+        stats, gmu = A.a2sgd_read_segment_stats(plan, ws)
+        for k in range(len(lengths)):
+            r = res[0] if pooled else res[k]
+            for p in range(P):
+                a, b = stats[p][k], r.workers[p]
+                assert (a.n_pos, a.n_neg, a.n_zero, a.n_nan) == (b.n_pos, b.n_neg, b.n_zero, b.n_nan), f"step {t} tensor {k} worker {p}"
+                close(a.mu_pos, b.mu_pos, f"step {t} tensor {k} worker {p} mu_pos")
+                close(a.mu_neg, b.mu_neg, f"step {t} tensor {k} worker {p} mu_neg")
+            close(gmu[k][0], r.gmu_pos, f"step {t} tensor {k} gmu_pos")
+            close(gmu[k][1], r.gmu_neg, f"step {t} tensor {k} gmu_neg")
+        w_got = wd.cpu().numpy()
+        assert np.isnan(w_got[~member]).all(), "padding of w was written"
+        for o, l in zip(offs, lengths):
+            assert_array_close(w_got[o:o + l], w_o[o:o + l], f"step {t} w tensor at {o}")
+    A.a2sgd_lazy_materialize(plan, s, ws)
+    for p in range(P):
+        e_got = s[p].cpu().numpy()
+        assert np.isnan(e_got[~member]).all(), "padding of the state was written"
+        for o, l in zip(offs, lengths):
+            assert_array_close(e_got[o:o + l], e_o[p][o:o + l], f"materialised e[{p}] tensor at {o}")
+    # the buffers are true errors again: an eager step goes on from them
+    g = [(rng.standard_normal(n).astype(f32) * scale) for _ in range(P)]
+    for x in g:
+        x[~member] = np.nan
+    A.a2sgd_step(plan, [dev(x) for x in g], s, wd, 0.1, ws)
+    _, e_o, w_o = O.step_segmented(g, e_o, w_o, 0.1, mode, lengths, offsets, pooled)
+    for o, l in zip(offs, lengths):
+        assert_array_close(wd.cpu().numpy()[o:o + l], w_o[o:o + l], f"eager step after materialise, w tensor at {o}")
+
+
+@pytest.mark.parametrize("seg", LAYOUTS, ids=[f"layout{i}" for i in range(len(LAYOUTS))])
+def test_lazy_state_on_tensor_plans(A, seg):
+    n = sum(seg)
+    for P, mode in ((1, 0), (3, 1), (4, 0), (9, 0)):
+        print(f"case S={len(seg)} n={n} P={P} mode={mode}", flush=True)
+        run_lazy_case(A, n + P, n, P, mode, seg)
+
+
+@pytest.mark.parametrize("case", PADDED, ids=[f"padded{i}" for i in range(len(PADDED))])
+def test_lazy_state_on_tensor_plans_with_padding(A, case):
+    n, lengths, offsets = case
+    for P, mode, pooled in ((2, 0, False), (3, 1, True), (5, 0, True)):
+        print(f"case n={n} S={len(lengths)} P={P} mode={mode} pooled={pooled}", flush=True)
+        run_lazy_case(A, n + P, n, P, mode, lengths, offsets, pooled, steps=3)
+
+
+def test_lazy_state_on_a_tensor_plan_streaming(A):
+    seg = [1_000_003, 5, 777_777, 64, 1_300_001, 131_072, 2, 291_079]
+    assert (2 * 7 + 1) * 4 * sum(seg) > 192 << 20
+    run_lazy_case(A, 78, sum(seg), 7, 0, seg, steps=2)
+    run_lazy_case(A, 79, sum(seg), 7, 1, seg, steps=2)
+
+
+def test_config2_full_size_replicas_and_lazy_state_per_tensor(A):
+    """ResNet-50 shape at full size (161 tensors, 8 workers, inputs generated on the device): one per-replica step and
+    one lazy step with per-tensor means, every element against the oracle."""
+    wl = workloads.config2()
+    n, P = wl.n, wl.num_workers
+    seg = [numel for _, numel in wl.tensors]
+    plan = A.a2sgd_plan(n, P, 0, 0, seg_lengths=seg)
+    ws = A.alloc_workspace(plan)
+    g = [wl.gradient(p, 0, device="cuda") for p in range(P)]
+    gh = [x.cpu().numpy() for x in g]
+    eh = [wl.synthetic_error(p).numpy() for p in range(P)]
+    wh = wl.weights().numpy()
+    # replicas: all start from the same weights
+    ed, wr = [dev(x) for x in eh], [dev(wh) for _ in range(P)]
+    A.a2sgd_step_replicas(plan, g, ed, wr, wl.eta, ws)
+    e_ref, w_ref = O.step_replicas_segmented(gh, eh, [wh] * P, wl.eta, 0, seg)
+    offs = np.concatenate([[0], np.cumsum(seg)])
+    for p in range(P):
+        e_got, w_got = ed[p].cpu().numpy(), wr[p].cpu().numpy()
+        for k in range(len(seg)):
+            lo, hi = int(offs[k]), int(offs[k + 1])
+            assert_array_close(e_got[lo:hi], e_ref[p][lo:hi], f"replica e[{p}] tensor {k}")
+            assert_array_close(w_got[lo:hi], w_ref[p][lo:hi], f"replica w[{p}] tensor {k}")
+    del wr
+    # lazy state: one step from true errors, then materialise
+    s, wd = [dev(x) for x in eh], dev(wh)
+    A.a2sgd_lazy_reset(plan, ws)
+    A.a2sgd_lazy_step(plan, g, s, wd, wl.eta, ws)
+    A.a2sgd_lazy_materialize(plan, s, ws)
+    _, e_ref, w_ref = O.step_segmented(gh, eh, wh, wl.eta, 0, seg)
+    w_got = wd.cpu().numpy()
+    for k in range(len(seg)):
+        lo, hi = int(offs[k]), int(offs[k + 1])
+        assert_array_close(w_got[lo:hi], w_ref[lo:hi], f"lazy w tensor {k}")
+    for p in range(P):
+        e_got = s[p].cpu().numpy()
+        for k in range(len(seg)):
+            lo, hi = int(offs[k]), int(offs[k + 1])
+            assert_array_close(e_got[lo:hi], e_ref[p][lo:hi], f"lazy e[{p}] tensor {k}")
+

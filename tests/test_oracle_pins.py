@@ -225,6 +225,49 @@ def test_tensors_with_padding_and_pooled_means():
                         assert w_new[sl].tolist() == [float(x) for x in wn]
 
 
+def test_per_tensor_replicas():
+    """One weight vector per worker on buffers that consist of tensors.  Pinned by the hand-worked per-tensor case
+    (each worker's rebuilt update is +gmu_pos or -gmu_neg of the element's tensor) and, on random dyadic cases with
+    padding, per tensor and pooled, by two identities: the errors are those of the shared-weight form, and the mean
+    of the replicas, all started from the same w, is the shared form's new w (Eq. 1 with rebuilt gradients)."""
+    gA, gB = arr([1, -2, 3, 0, -4, 2]), arr([-1, -3, 2, -2, 4, 0])
+    zero = arr([0] * 6)
+    e_new, w_new = O.step_replicas_segmented([gA, gB], [zero, zero], [zero, zero], 0.5, O.RETAINED_ERROR, [3, 3])
+    # tensor 0: global means (2, 2); tensor 1: (1.5, 3); w^p = -0.5 * (+gmu_pos or -gmu_neg by the sign of g^p)
+    assert w_new[0].tolist() == [-1, 1, -1, -0.75, 1.5, -0.75]
+    assert w_new[1].tolist() == [1, 1, -1, 1.5, -0.75, -0.75]
+    assert e_new[0].tolist() == [-1, 0, 1, -1, 0, 1] and e_new[1].tolist() == [1, -1, 0, 0, 2, -2]
+    rng = np.random.default_rng(79)
+    for _ in range(25):
+        P, S = int(rng.choice([1, 2, 4])), int(rng.integers(1, 5))
+        lengths = [int(x) for x in rng.integers(1, 6, S)]
+        gaps = [int(x) for x in rng.integers(0, 4, S + 1)]
+        offsets, pos = [], gaps[0]
+        for k in range(S):
+            offsets.append(pos)
+            pos += lengths[k] + gaps[k + 1]
+        n = max(pos, 1)
+        member = np.zeros(n, bool)
+        for o, l in zip(offsets, lengths):
+            member[o:o + l] = True
+        g = [arr(rng.integers(-32, 33, n) / 8.0) for _ in range(P)]
+        e = [arr(rng.integers(-16, 17, n) / 8.0) for _ in range(P)]
+        w = arr(rng.integers(-64, 65, n) / 16.0)
+        for x in g + e + [w]:
+            x[~member] = np.nan
+        for mode in (O.RETAINED_ERROR, O.ALG1_LITERAL):
+            for pooled in (False, True):
+                _, e_ref, w_ref = O.step_segmented(g, e, w, 0.25, mode, lengths, offsets, pooled)
+                e_new, w_new = O.step_replicas_segmented(g, e, [w.copy() for _ in range(P)], 0.25, mode, lengths,
+                                                         offsets, pooled)
+                for p in range(P):
+                    assert np.array_equal(e_new[p], e_ref[p], equal_nan=True)
+                    assert np.isnan(w_new[p][~member]).all() and not np.isnan(w_new[p][member]).any()
+                # each replica and the shared w are rounded to fp32 once: the identity holds to a few ulp
+                mean = np.mean(np.stack(w_new).astype(np.float64), axis=0)
+                assert np.allclose(mean[member], w_ref[member].astype(np.float64), rtol=4e-7, atol=1e-7)
+
+
 # ---------------------------------------------------------------------------------------------------------
 # exactly rounded means: math.fsum is an exact sum, so fl32(fsum/n) is the definition's value
 # ---------------------------------------------------------------------------------------------------------
