@@ -166,6 +166,9 @@ def main() -> int:
     ap.add_argument("--blocks-per-worker", type=int, default=0)
     ap.add_argument("--n", type=int, default=0, help="override n (config 1 only: one flat tensor)")
     ap.add_argument("--workers", type=int, default=0, help="override P (config 1 only)")
+    ap.add_argument("--table1", choices=["fnn3", "resnet20", "vgg16_cifar"], default=None,
+                    help="instead of a benchmark configuration: one of the paper's own small models (Table 1) as "
+                         "per-layer tensors; combine with --per-tensor and --single-call, --workers sets P (default 4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short runs of the other four workloads (they are part of the default run only)")
@@ -197,7 +200,9 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     wl = workloads.FULL[args.config]()
-    if args.n or args.workers:
+    if args.table1:
+        wl = workloads.table1(args.table1, num_workers=args.workers or 4)
+    elif args.n or args.workers:
         assert args.config == 1, "--n and --workers apply to the flat workload of config 1"
         wl = workloads.config1(n=args.n or wl.n, num_workers=args.workers or wl.num_workers)
     n, P = wl.n, wl.num_workers
@@ -230,7 +235,7 @@ def main() -> int:
         stats, gmu = [row[0] for row in seg_stats], seg_gmu[0]
     else:
         stats, gmu = A.a2sgd_read_stats(plan, ws)
-    traffic, traffic_source = (None, None) if (no_events or plan.num_segments or args.n or args.workers) else \
+    traffic, traffic_source = (None, None) if (no_events or plan.num_segments or args.n or args.workers or args.table1) else \
         MEASURED_TRAFFIC.get(f"config{args.config}", (None, None))
 
     out = {
@@ -246,7 +251,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"config{args.config}:{wl.name}", "n": n, "num_workers": P, "seed": wl.seed,
+        "config": {"workload": wl.name if args.table1 else f"config{args.config}:{wl.name}", "n": n, "num_workers": P, "seed": wl.seed,
                    "recipe": wl.recipe, "mode": "retained_error", "eta": wl.eta, "per_tensor_means": plan.num_segments, "pooled_means": bool(seg) and args.pooled,
                    "blocks_per_worker": A.a2sgd_plan_blocks_per_worker(plan),
                    "launch": ("one_call" if args.single_call else "three_calls") + ("+hip_graph_replay" if args.hip_graph else "")},
@@ -333,7 +338,8 @@ def main() -> int:
     if copy_gbps:
         out["step_frac_of_plain_copy"] = out["step_hbm_gbps"] / copy_gbps
 
-    default_run = args.config == 5 and not (args.n or args.workers or args.per_tensor or args.single_call or args.hip_graph)
+    default_run = args.config == 5 and not (args.n or args.workers or args.per_tensor or args.single_call or args.hip_graph
+                                            or args.table1)
     if default_run and not args.no_other_configs:
         del g, e, w, ws
         torch.cuda.empty_cache()

@@ -195,7 +195,9 @@ a2sgd_status_t a2sgd_dense_step(const a2sgd_plan_t *plan, const float *const *g,
  * has one pair of means over all its tensors together, as in the paper, and the tensors only say which elements of
  * the buffers belong to the model.  Elements outside every tensor (possible with seg_offset) are left alone by every
  * call except a2sgd_dense_step and a2sgd_export_mask, which do not depend on the segments.
- * a2sgd_local_averages, a2sgd_global_average, a2sgd_apply_and_update_error and a2sgd_step work as described above,
+ * a2sgd_local_averages, a2sgd_global_average, a2sgd_apply_and_update_error and a2sgd_step work as described above
+ * (a2sgd_step is one kernel launch for such a plan too, when the model stays in the caches, has at most about 4 M
+ * elements and its means are not pooled: the paper's own FNN-3 and ResNet-20 with a pair of means per layer),
  * and so do the replica calls and the lazy calls further down, each element with the means of its tensor (the lazy
  * state carries one pair of means per worker and tensor; its apply pass reads v in both modes, 16nP + 8n bytes per
  * step).  Not available on such a plan (A2SGD_ERR_INVALID_ARG): a2sgd_step_static, the export/import pair, and
@@ -307,8 +309,8 @@ a2sgd_status_t a2sgd_selftest_barrier(void *buffer, a2sgd_stream_t stream);
 uint32_t a2sgd_plan_blocks_per_worker(const a2sgd_plan_t *plan);
 
 /* The grid-barrier cell (0..63) that a2sgd_step's single launch uses with this plan, or -1 if the plan runs the
- * three passes (model too large for the caches, a plan with tensors, no free cell when it was made, or a step
- * that gave up at its barrier).  Host call. */
+ * three passes (model too large for the caches, tensors with pooled means or more than about 4 M elements, no free
+ * cell when it was made, or a step that gave up at its barrier).  Host call. */
 int32_t a2sgd_plan_single_launch_cell(const a2sgd_plan_t *plan);
 
 /* What the current HIP device reports about itself, for benchmark reports: compute units, memory clock (kHz) and

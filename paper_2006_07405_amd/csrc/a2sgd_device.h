@@ -130,6 +130,19 @@ __device__ __forceinline__ vf4 pending_error4(vf4 s, float neg_mu_pos, float mu_
                pending_error(s.z, neg_mu_pos, mu_neg), pending_error(s.w, neg_mu_pos, mu_neg)};
 }
 
+// The kernels of plans with tensors index through tables that a2sgd_workspace_init uploads.  Before its first such access every
+// workgroup compares the tag in the workspace header with the tag of its plan's tables; on a mismatch (the
+// workspace was never initialised, or for another plan) it raises the header's fault flag and the caller returns
+// without reading a table entry or writing any output.  The answer is the same for every thread of the grid.
+__device__ __forceinline__ bool seg_tables_ok(const SegView &sv)
+{
+    if (sv.hdr->seg_tag == sv.tag)
+        return true;
+    if (threadIdx.x == 0)
+        sv.hdr->seg_fault = 1u;  // every writer stores the same value
+    return false;
+}
+
 // A zero the compiler cannot see through, in a vector register.  Added to an index it turns a load with a
 // wavefront-uniform address into an ordinary vector load.  The apply pass wants that for the handful of means
 // it reads from the workspace: vector loads return in issue order and are counted apart from the scalar loads

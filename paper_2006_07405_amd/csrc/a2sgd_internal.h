@@ -128,6 +128,17 @@ struct SegView {
     uint64_t *r_npos, *r_nneg, *r_nzero;
 };
 
+// The single-launch step on a plan with tensors works on finer items (at most kFusedItemElems elements inside one
+// tensor, so that a small model still spreads over many workgroups): one partial record per (worker, item).
+constexpr uint32_t kFusedItemElems = 4096;  // 2 float4 groups per thread of a kFusedBlock workgroup
+struct FusedSegView {
+    uint32_t num_items;
+    const SegItem *item;      // [num_items], ascending start
+    const uint32_t *item_lo;  // [S + 1]: items of segment s
+    double *r_spos, *r_sneg;  // [P][num_items]
+    uint64_t *r_npos, *r_nneg, *r_nzero;
+};
+
 struct SegPlan {
     uint32_t S = 0;  // 0 = the plan has no segments: whole-model means over [0, n)
     bool pooled = false;  // one pair of means per worker over all segments together
@@ -137,6 +148,9 @@ struct SegPlan {
     std::vector<uint32_t> item_lo, coarse;
     uint32_t blocks = 0;  // workgroups per worker of the reduction
     std::vector<uint32_t> sched_lo, sched_item;
+    std::vector<SegItem> fitem;       // items of the single-launch step; empty if the plan cannot take it
+    std::vector<uint32_t> fitem_lo;
+    size_t off_fitem = 0, off_fitem_lo = 0, off_frecords = 0;
     uint64_t tag = 0;  // checksum of the tables above and of the sizes that fix their layout; never 0
     // byte offsets into the workspace
     size_t off_seg_start = 0, off_seg_end = 0, off_item = 0, off_item_lo = 0, off_coarse = 0, off_sched_lo = 0, off_sched_item = 0,
@@ -207,6 +221,10 @@ hipError_t launch_seg_finalize(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
 hipError_t launch_seg_global(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
 hipError_t launch_seg_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
                             hipStream_t s);
+// Single-launch step on a plan with tensors (a2sgd_kernels.hip, next to the grid barrier it uses).
+FusedSegView fused_seg_view(const a2sgd_plan_t &pl, void *ws);
+hipError_t launch_seg_fused_step(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
+                                 uint32_t token, hipStream_t s);
 // Replica calls and the lazy state on plans with tensors.
 hipError_t launch_seg_apply_replicas(const a2sgd_plan_t &pl, const PtrTable &tab, const ReplicaTable &wt, bool has_e,
                                      float eta, void *ws, hipStream_t s);

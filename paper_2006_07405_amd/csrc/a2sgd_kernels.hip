@@ -587,6 +587,196 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused_step(const PtrTable tab, 
     }
 }
 
+// The single-launch step on a plan with tensors (one pair of means per worker and tensor): Algorithm 1 lines 3-7 in
+// one kernel for models that stay in the caches, such as the paper's own FNN-3, ResNet-20 and VGG-16 (Table 1) with a
+// per-layer hook.  The unit of work is an item of at most kFusedItemElems elements inside one tensor; workgroup b owns
+// a contiguous run of items in all phases, so what it read for the sums it re-reads for the update from its own
+// XCD's L2.  Phase 1: one partial record per (worker, item).  Barrier.  Phase 2: the tensors are dealt out to the
+// wavefronts of the whole grid; a wavefront combines, worker by worker, the records of its tensor's items in a fixed
+// order, rounds the two local means, and averages them over the workers (line 5); means and global means go to the
+// tables of the three-pass form, the statistics to where a2sgd_read_segment_stats reads them.  Barrier.  Phase 3:
+// the apply body on every item with the means of its tensor; an item starts and ends anywhere, so the elements
+// before its first and after its last 16-byte boundary go one per thread.  Everything that crosses a barrier is
+// written and read with device-scope accesses, as in k_fused_step.
+template <int MODE, bool HAS_E, int UP>
+__global__ __launch_bounds__(kFusedBlock) void k_seg_fused_step(const PtrTable tab, float *__restrict__ w, const uint32_t P,
+                                                                const float eta_over_P, const SegView sv,
+                                                                const FusedSegView fv, const uint32_t slot,
+                                                                const uint32_t token)
+{
+    GridBarrier *bar = &g_barriers[slot];
+    WsHeader *hdr = sv.hdr;
+    __shared__ uint32_t s_stop;
+    if (threadIdx.x == 0) {
+        const uint32_t cell_failed = __hip_atomic_load(&bar->failed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (cell_failed != 0)
+            hdr->failed_token = token;
+        s_stop = cell_failed;
+    }
+    __syncthreads();
+    // both tests give the same answer in every workgroup of the grid, so either all go on to the barrier or none
+    if (s_stop != 0 || !seg_tables_ok(sv))
+        return;
+    __shared__ double sh_pos[kMaxWorkers][kFusedBlock / 64], sh_neg[kMaxWorkers][kFusedBlock / 64];
+    __shared__ uint64_t sh_cp[kMaxWorkers][kFusedBlock / 64], sh_cn[kMaxWorkers][kFusedBlock / 64],
+        sh_cz[kMaxWorkers][kFusedBlock / 64];
+    __shared__ float s_neg_mu_pos[kMaxWorkers], s_mu_neg[kMaxWorkers], s_gmu[2];
+
+    const uint32_t G = gridDim.x, b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t q = fv.num_items / G, r = fv.num_items % G;
+    const uint32_t it_lo = b * q + (b < r ? b : r), it_hi = it_lo + q + (b < r ? 1 : 0);
+
+    // ---- phase 1
+    for (uint32_t it = it_lo; it < it_hi; ++it) {
+        const SegItem item = fv.item[it];
+        const uint64_t lo = item.start, hi = item.start + item.count;
+        uint64_t a = (lo + 3) & ~static_cast<uint64_t>(3);
+        if (a > hi)
+            a = hi;
+        const uint64_t z = a + ((hi - a) & ~static_cast<uint64_t>(3));
+        const uint64_t v_lo = a >> 2, v_hi = z >> 2;
+        for (uint32_t p = 0; p < P; ++p) {
+            const float *__restrict__ g = tab.g[p];
+            const float *__restrict__ e = HAS_E ? tab.e[p] : nullptr;
+            const vf4 *g4 = reinterpret_cast<const vf4 *>(g), *e4 = reinterpret_cast<const vf4 *>(e);
+            LaneAcc acc;
+            if (tid < a - lo) {
+                acc.add(HAS_E ? g[lo + tid] + e[lo + tid] : g[lo + tid]);
+                acc.flush();
+            }
+            for (uint64_t i = v_lo + tid; i < v_hi; i += kFusedBlock) {
+                acc.add4(HAS_E ? g4[i] + e4[i] : g4[i]);
+                acc.flush();
+            }
+            if (tid < hi - z) {
+                acc.add(HAS_E ? g[z + tid] + e[z + tid] : g[z + tid]);
+                acc.flush();
+            }
+            const double wp = wave_sum(acc.s_pos), wn = wave_sum(acc.s_neg);
+            if (lane == 0) {
+                sh_pos[p][wave] = wp;
+                sh_neg[p][wave] = wn;
+                sh_cp[p][wave] = acc.c_pos;
+                sh_cn[p][wave] = acc.c_neg;
+                sh_cz[p][wave] = acc.c_zero;
+            }
+        }
+        __syncthreads();
+        if (tid < P) {
+            double sp = 0.0, sn = 0.0;
+            uint64_t cp = 0, cn = 0, cz = 0;
+#pragma unroll
+            for (int k = 0; k < kFusedBlock / 64; ++k) {
+                sp += sh_pos[tid][k];
+                sn += sh_neg[tid][k];
+                cp += sh_cp[tid][k];
+                cn += sh_cn[tid][k];
+                cz += sh_cz[tid][k];
+            }
+            const size_t rec = static_cast<size_t>(tid) * fv.num_items + it;
+            store_device(fv.r_spos + rec, sp);
+            store_device(fv.r_sneg + rec, sn);
+            store_device(fv.r_npos + rec, cp);
+            store_device(fv.r_nneg + rec, cn);
+            store_device(fv.r_nzero + rec, cz);
+        }
+        __syncthreads();  // the LDS slots are free again for the next item
+    }
+    if (!grid_barrier(bar, G, kBarrierSpinLimit)) {
+        if (tid == 0)
+            hdr->failed_token = token;
+        return;
+    }
+
+    // ---- phase 2: one wavefront per tensor
+    for (uint32_t s = b * (kFusedBlock / 64) + wave; s < sv.S; s += G * (kFusedBlock / 64)) {
+        const uint32_t lo = fv.item_lo[s], hi = fv.item_lo[s + 1];
+        const uint64_t len = sv.seg_end[s] - sv.seg_start[s];
+        double gp = 0.0, gn = 0.0;  // sums of the workers' means, lane 0
+        for (uint32_t p = 0; p < P; ++p) {
+            const size_t row = static_cast<size_t>(p) * fv.num_items;
+            double sp = 0.0, sn = 0.0;
+            uint64_t cp = 0, cn = 0, cz = 0;
+            for (uint32_t j = lo + lane; j < hi; j += 64) {
+                sp += load_device(fv.r_spos + row + j);
+                sn += load_device(fv.r_sneg + row + j);
+                cp += load_device(fv.r_npos + row + j);
+                cn += load_device(fv.r_nneg + row + j);
+                cz += load_device(fv.r_nzero + row + j);
+            }
+            sp = wave_sum(sp);
+            sn = wave_sum(sn);
+            cp = wave_sum(cp);
+            cn = wave_sum(cn);
+            cz = wave_sum(cz);
+            if (lane == 0) {
+                a2sgd_worker_stats_t st;
+                st.mu_pos = cp ? static_cast<float>(sp / static_cast<double>(cp)) : 0.0f;
+                st.mu_neg = cn ? static_cast<float>(sn / static_cast<double>(cn)) : 0.0f;
+                st.n_pos = cp;
+                st.n_neg = cn;
+                st.n_zero = cz;
+                st.n_nan = len - cp - cn;
+                sv.stats[static_cast<size_t>(p) * sv.S + s] = st;
+                store_device(sv.neg_mu_pos + static_cast<size_t>(s) * P + p, -st.mu_pos);
+                store_device(sv.mu_neg + static_cast<size_t>(s) * P + p, st.mu_neg);
+                gp += static_cast<double>(st.mu_pos);
+                gn += static_cast<double>(st.mu_neg);
+            }
+        }
+        if (lane == 0) {  // Algorithm 1 line 5 for this tensor
+            store_device(sv.gmu + 2 * s, static_cast<float>(gp / static_cast<double>(P)));
+            store_device(sv.gmu + 2 * s + 1, -static_cast<float>(gn / static_cast<double>(P)));
+        }
+    }
+    if (!grid_barrier(bar, G, kBarrierSpinLimit)) {
+        if (tid == 0)
+            hdr->failed_token = token;
+        return;
+    }
+
+    // ---- phase 3
+    for (uint32_t it = it_lo; it < it_hi; ++it) {
+        const SegItem item = fv.item[it];
+        const uint32_t s = item.seg;
+        if (tid < P) {
+            s_neg_mu_pos[tid] = load_device(sv.neg_mu_pos + static_cast<size_t>(s) * P + tid);
+            s_mu_neg[tid] = load_device(sv.mu_neg + static_cast<size_t>(s) * P + tid);
+        }
+        if (tid < 2)
+            s_gmu[tid] = load_device(sv.gmu + 2 * s + tid);
+        __syncthreads();
+        const float gmu_pos = s_gmu[0], neg_gmu_neg = s_gmu[1];
+        const uint64_t lo = item.start, hi = item.start + item.count;
+        uint64_t a = (lo + 3) & ~static_cast<uint64_t>(3);
+        if (a > hi)
+            a = hi;
+        const uint64_t z = a + ((hi - a) & ~static_cast<uint64_t>(3));
+        auto scalar = [&](const uint64_t k) {  // lines 4, 6, 7 on one element outside the float4 groups
+            float acc = 0.0f;
+            for (uint32_t p = 0; p < P; ++p) {
+                float v = tab.g[p][k];
+                if (HAS_E)
+                    v += tab.e[p][k];
+                acc += apply1<MODE>(v, s_neg_mu_pos[p], s_mu_neg[p], gmu_pos, neg_gmu_neg);
+                if (HAS_E)
+                    tab.e[p][k] = v;
+            }
+            w[k] -= eta_over_P * acc;
+        };
+        if (tid < a - lo)
+            scalar(lo + tid);
+        // an item has at most kFusedItemElems / 4 float4 groups: two per thread
+        static_assert(kFusedItemElems == 2 * 4 * kFusedBlock, "apply_body covers an item with ITEMS = 2");
+        if ((a >> 2) + tid < (z >> 2))
+            apply_body<MODE, HAS_E, false, UP, 2, kFusedBlock, false>(tab, w, z >> 2, (a >> 2) + tid, P, eta_over_P,
+                                                                     s_neg_mu_pos, s_mu_neg, gmu_pos, neg_gmu_neg);
+        if (tid < hi - z)
+            scalar(z + tid);
+        __syncthreads();  // the means in LDS may be replaced
+    }
+}
+
 // Eq. 1 / Algorithm 1 lines 9-10: w <- w - eta * mean_p g^p.  Same shape as the apply pass: single-wavefront
 // workgroups launched once each, thread t owning ITEMS float4 groups of w and of every worker, the loads of UP
 // workers issued together, residency capped by the launcher's dynamic-LDS request.
@@ -1471,6 +1661,51 @@ hipError_t launch_fused_step(const a2sgd_plan_t &pl, const PtrTable &tab, bool h
                      : launch_fused_inst<A2SGD_MODE_ALG1_LITERAL, false>(pl, tab, w, eop, ws, token, s);
     return has_e ? launch_fused_inst<A2SGD_MODE_RETAINED_ERROR, true>(pl, tab, w, eop, ws, token, s)
                  : launch_fused_inst<A2SGD_MODE_RETAINED_ERROR, false>(pl, tab, w, eop, ws, token, s);
+}
+
+FusedSegView fused_seg_view(const a2sgd_plan_t &pl, void *ws)
+{
+    char *b = static_cast<char *>(ws);
+    const SegPlan &sp = pl.seg;
+    const size_t stride = 8ull * pl.P * sp.fitem.size();
+    FusedSegView v;
+    v.num_items = static_cast<uint32_t>(sp.fitem.size());
+    v.item = reinterpret_cast<const SegItem *>(b + sp.off_fitem);
+    v.item_lo = reinterpret_cast<const uint32_t *>(b + sp.off_fitem_lo);
+    v.r_spos = reinterpret_cast<double *>(b + sp.off_frecords);
+    v.r_sneg = reinterpret_cast<double *>(b + sp.off_frecords + stride);
+    v.r_npos = reinterpret_cast<uint64_t *>(b + sp.off_frecords + 2 * stride);
+    v.r_nneg = reinterpret_cast<uint64_t *>(b + sp.off_frecords + 3 * stride);
+    v.r_nzero = reinterpret_cast<uint64_t *>(b + sp.off_frecords + 4 * stride);
+    return v;
+}
+
+template <int MODE, bool HAS_E>
+static hipError_t launch_seg_fused_inst(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eop, void *ws,
+                                        uint32_t token, hipStream_t s)
+{
+    const dim3 grid(pl.fused_grid), block(kFusedBlock);
+    const SegView sv = seg_view(pl, ws);
+    const FusedSegView fv = fused_seg_view(pl, ws);
+    const uint32_t cell = static_cast<uint32_t>(pl.barrier_cell);
+    switch (pl.apply.up) {
+    case 8: k_seg_fused_step<MODE, HAS_E, 8><<<grid, block, 0, s>>>(tab, w, pl.P, eop, sv, fv, cell, token); break;
+    case 4: k_seg_fused_step<MODE, HAS_E, 4><<<grid, block, 0, s>>>(tab, w, pl.P, eop, sv, fv, cell, token); break;
+    case 2: k_seg_fused_step<MODE, HAS_E, 2><<<grid, block, 0, s>>>(tab, w, pl.P, eop, sv, fv, cell, token); break;
+    default: k_seg_fused_step<MODE, HAS_E, 1><<<grid, block, 0, s>>>(tab, w, pl.P, eop, sv, fv, cell, token); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_seg_fused_step(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
+                                 uint32_t token, hipStream_t s)
+{
+    const float eop = static_cast<float>(static_cast<double>(eta) / static_cast<double>(pl.P));
+    if (pl.mode == A2SGD_MODE_ALG1_LITERAL)
+        return has_e ? launch_seg_fused_inst<A2SGD_MODE_ALG1_LITERAL, true>(pl, tab, w, eop, ws, token, s)
+                     : launch_seg_fused_inst<A2SGD_MODE_ALG1_LITERAL, false>(pl, tab, w, eop, ws, token, s);
+    return has_e ? launch_seg_fused_inst<A2SGD_MODE_RETAINED_ERROR, true>(pl, tab, w, eop, ws, token, s)
+                 : launch_seg_fused_inst<A2SGD_MODE_RETAINED_ERROR, false>(pl, tab, w, eop, ws, token, s);
 }
 
 template <int MODE, bool HAS_E, bool NT>

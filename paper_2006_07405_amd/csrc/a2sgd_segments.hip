@@ -41,19 +41,6 @@ SegView seg_view(const a2sgd_plan_t &pl, void *ws)
     return v;
 }
 
-// The kernels below index through tables that a2sgd_workspace_init uploads.  Before its first such access every
-// workgroup compares the tag in the workspace header with the tag of its plan's tables; on a mismatch (the
-// workspace was never initialised, or for another plan) it raises the header's fault flag and the caller returns
-// without reading a table entry or writing any output.  The answer is the same for every thread of the grid.
-__device__ __forceinline__ bool seg_tables_ok(const SegView &sv)
-{
-    if (sv.hdr->seg_tag == sv.tag)
-        return true;
-    if (threadIdx.x == 0)
-        sv.hdr->seg_fault = 1u;  // every writer stores the same value
-    return false;
-}
-
 __global__ void k_seg_mark(WsHeader *__restrict__ hdr, const uint64_t tag)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {

@@ -141,7 +141,7 @@ def test_grid_barrier_cells_are_owned_by_live_plans(A):
     assert A.a2sgd_plan_single_launch_cell(spare) == -1
     # the workspace does not depend on whether the plan got a cell
     assert A.a2sgd_workspace_bytes(spare) == A.a2sgd_workspace_bytes(plans[0])
-    # models too large for the caches and plans with tensors never take one
+    # models too large for the caches never take one
     assert A.a2sgd_plan_single_launch_cell(A.a2sgd_plan(1 << 28, 4)) == -1
     victim = plans.pop(len(plans) // 2)
     freed = A.a2sgd_plan_single_launch_cell(victim)
@@ -153,7 +153,9 @@ def test_grid_barrier_cells_are_owned_by_live_plans(A):
     assert A.raw.a2sgd_plan_single_launch_cell(None) == -1
     del plans, again, spare
     gc.collect()
-    assert A.a2sgd_plan_single_launch_cell(A.a2sgd_plan(5000, 2, seg_lengths=[5000])) == -1
+    # plans with tensors take one too, unless their means are pooled
+    assert A.a2sgd_plan_single_launch_cell(A.a2sgd_plan(5000, 2, seg_lengths=[5000], pooled_means=True)) == -1
+    assert A.a2sgd_plan_single_launch_cell(A.a2sgd_plan(5000, 2, seg_lengths=[3000, 2000])) >= 0
     assert A.a2sgd_plan_single_launch_cell(A.a2sgd_plan(5000, 2)) >= 0
 
 

@@ -431,3 +431,89 @@ def test_config2_full_size_replicas_and_lazy_state_per_tensor(A):
             lo, hi = int(offs[k]), int(offs[k + 1])
             assert_array_close(e_got[lo:hi], e_ref[p][lo:hi], f"lazy e[{p}] tensor {k}")
 
+
+# ---- the single-launch step on plans with tensors -------------------------------------------------------------------
+
+@pytest.mark.parametrize("model,P", [("fnn3", 4), ("fnn3", 16), ("resnet20", 4), ("resnet20", 8), ("vgg16_cifar", 1)])
+def test_single_launch_step_on_the_papers_own_models(A, model, P):
+    """Table 1's models as per-layer tensors, small enough to stay in the caches: a2sgd_step is one kernel launch
+    with per-tensor means.  Three steps on carried state in both modes, every tensor's statistics and every element
+    of e and w against the per-tensor oracle; then the same plan's three calls give the same result."""
+    wl = workloads.table1(model, num_workers=P)
+    n = wl.n
+    seg = [numel for _, numel in wl.tensors]
+    offs = np.concatenate([[0], np.cumsum(seg)])
+    for mode in (0, 1):
+        plan = A.a2sgd_plan(n, P, mode, 0, seg_lengths=seg)
+        # one launch up to about 4 M elements; the 14.7 M-parameter VGG-16 runs the three passes, which are faster there
+        assert (A.a2sgd_plan_single_launch_cell(plan) >= 0) == (model != "vgg16_cifar")
+        ws = A.alloc_workspace(plan)
+        e_o = [wl.synthetic_error(p).numpy() for p in range(P)]
+        w_o = wl.weights().numpy()
+        ed, wd = [dev(x) for x in e_o], dev(w_o)
+        for t in range(3):
+            g = [wl.gradient(p, t).numpy() for p in range(P)]
+            gd = [dev(x) for x in g]
+            if t == 2:  # last step through the three calls, from the same state: the same kernels' tables, other route
+                e3, w3 = [x.clone() for x in ed], wd.clone()
+                A.a2sgd_local_averages(plan, gd, e3, ws)
+                A.a2sgd_global_average(plan, ws)
+                A.a2sgd_apply_and_update_error(plan, gd, e3, w3, wl.eta, ws)
+            A.a2sgd_step(plan, gd, ed, wd, wl.eta, ws)
+            stats, gmu = A.a2sgd_read_segment_stats(plan, ws)
+            res, e_o, w_o = O.step_segmented(g, e_o, w_o, wl.eta, mode, seg)
+            for k, r in enumerate(res):
+                for p in range(P):
+                    a, b = stats[p][k], r.workers[p]
+                    assert (a.n_pos, a.n_neg, a.n_zero, a.n_nan) == (b.n_pos, b.n_neg, b.n_zero, b.n_nan), f"step {t} tensor {k} worker {p}"
+                    close(a.mu_pos, b.mu_pos, f"step {t} tensor {k} worker {p} mu_pos")
+                    close(a.mu_neg, b.mu_neg, f"step {t} tensor {k} worker {p} mu_neg")
+                close(gmu[k][0], r.gmu_pos, f"step {t} tensor {k} gmu_pos")
+                close(gmu[k][1], r.gmu_neg, f"step {t} tensor {k} gmu_neg")
+            w_got = wd.cpu().numpy()
+            for k in range(len(seg)):
+                lo, hi = int(offs[k]), int(offs[k + 1])
+                assert_array_close(w_got[lo:hi], w_o[lo:hi], f"step {t} w tensor {k}")
+                for p in range(P):
+                    assert_array_close(ed[p][lo:hi].cpu().numpy(), e_o[p][lo:hi], f"step {t} e[{p}] tensor {k}")
+        for k in range(len(seg)):
+            lo, hi = int(offs[k]), int(offs[k + 1])
+            assert_array_close(w3[lo:hi].cpu().numpy(), w_o[lo:hi], f"three calls: w tensor {k}")
+
+
+def test_single_launch_step_on_tensors_is_deterministic_and_graph_capturable(A):
+    """Same inputs twice: bit-identical outputs.  Captured in a HIP graph and replayed with eager work between the
+    replays: every replay equals the eager step from the same state."""
+    wl = workloads.table1("resnet20", num_workers=4)
+    n, P = wl.n, wl.num_workers
+    seg = [numel for _, numel in wl.tensors]
+    plan = A.a2sgd_plan(n, P, 0, 0, seg_lengths=seg)
+    ws = A.alloc_workspace(plan)
+    g = [wl.gradient(p, 0, device="cuda") for p in range(P)]
+    e0 = [wl.synthetic_error(p, device="cuda") for p in range(P)]
+    w0 = wl.weights(device="cuda")
+    runs = []
+    for _ in range(2):
+        e, w = [x.clone() for x in e0], w0.clone()
+        A.a2sgd_step(plan, g, e, w, wl.eta, ws)
+        runs.append((e, w))
+    torch.cuda.synchronize()
+    assert torch.equal(runs[0][1], runs[1][1]) and all(torch.equal(a, b) for a, b in zip(runs[0][0], runs[1][0]))
+    ws_ref = A.alloc_workspace(plan)
+    e_ref, w_ref = [x.clone() for x in e0], w0.clone()
+    expected = []
+    for _ in range(3):
+        A.a2sgd_step(plan, g, e_ref, w_ref, wl.eta, ws_ref)
+        expected.append(([x.clone() for x in e_ref], w_ref.clone()))
+    e, w = [x.clone() for x in e0], w0.clone()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        A.a2sgd_step(plan, g, e, w, wl.eta, ws)
+    for k in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        busy = (w0 * 2.0).sum().item()  # unrelated eager work and a host wait between replays
+        assert busy == busy
+        assert torch.equal(w, expected[k][1]), f"replay {k}: w differs from the eager step"
+        assert all(torch.equal(a, b) for a, b in zip(e, expected[k][0])), f"replay {k}: e differs from the eager step"

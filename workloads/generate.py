@@ -187,6 +187,15 @@ def config5(layers: int = 48, d_model: int = 1600, d_ff: int = 6400, vocab: int 
                     params=dict(sigma=1e-4, outlier_prob=1e-3, outlier_factor=100.0))
 
 
+def table1(model: str, num_workers: int = 4) -> Workload:
+    """The paper's own small models (Table 1) as per-layer tensor lists, with the per-tensor scales and Laplace
+    values of config 2: stand-ins for their gradients, which would need MNIST / CIFAR10 and training."""
+    tensors = {"fnn3": shapes.fnn3, "resnet20": shapes.resnet20, "vgg16_cifar": shapes.vgg16_cifar}[model]()
+    seed = {"fnn3": 11, "resnet20": 12, "vgg16_cifar": 13}[model]
+    return Workload(f"table1_{model}", tensors, num_workers, seed=seed, recipe="laplace_per_tensor",
+                    params=dict(scale_lo=1e-5, scale_hi=1e-2))
+
+
 FULL = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
 
 

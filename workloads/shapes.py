@@ -117,6 +117,53 @@ def transformer(layers: int = 48, d_model: int = 1600, d_ff: int = 6400, vocab: 
     return t
 
 
+def fnn3() -> Tensors:
+    """Table 1's FNN-3 on MNIST: 784-200-200-10 with biases, 199,210 elements in 6 tensors."""
+    t: Tensors = []
+    for i, (cin, cout) in enumerate([(784, 200), (200, 200), (200, 10)]):
+        t.append((f"fc{i}.weight", cin * cout))
+        t.append((f"fc{i}.bias", cout))
+    return t
+
+
+def resnet20(num_classes: int = 10) -> Tensors:
+    """Table 1's ResNet-20 on CIFAR10: 3x3 stem, three stages of three basic blocks with 16/32/64 channels,
+    parameter-free shortcuts, a BN weight and bias after every conv, FC + bias: 269,722 elements in 59 tensors."""
+    t: Tensors = []
+
+    def conv_bn(name: str, cin: int, cout: int) -> None:
+        t.append((f"{name}.weight", cout * cin * 9))
+        t.append((f"{name}.bn.weight", cout))
+        t.append((f"{name}.bn.bias", cout))
+
+    conv_bn("stem", 3, 16)
+    cin = 16
+    for s, ch in enumerate([16, 32, 64]):
+        for b in range(3):
+            conv_bn(f"stage{s + 1}.block{b}.conv1", cin, ch)
+            conv_bn(f"stage{s + 1}.block{b}.conv2", ch, ch)
+            cin = ch
+    t.append(("fc.weight", cin * num_classes))
+    t.append(("fc.bias", num_classes))
+    return t
+
+
+def vgg16_cifar(num_classes: int = 10) -> Tensors:
+    """Table 1's VGG-16 on CIFAR10: 13 conv 3x3 with biases, each followed by a BN weight and bias, and one
+    512 x 10 classifier: 14,728,266 elements in 54 tensors."""
+    t: Tensors = []
+    cin = 3
+    for i, cout in enumerate([64, 64, 128, 128, 256, 256, 256, 512, 512, 512, 512, 512, 512]):
+        t.append((f"conv{i}.weight", cout * cin * 9))
+        t.append((f"conv{i}.bias", cout))
+        t.append((f"bn{i}.weight", cout))
+        t.append((f"bn{i}.bias", cout))
+        cin = cout
+    t.append(("classifier.weight", cin * num_classes))
+    t.append(("classifier.bias", num_classes))
+    return t
+
+
 def total(tensors: Tensors) -> int:
     return sum(numel for _, numel in tensors)
 
