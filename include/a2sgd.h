@@ -204,8 +204,9 @@ a2sgd_status_t a2sgd_dense_step(const a2sgd_plan_t *plan, const float *const *g,
  * a2sgd_read_stats unless the means are pooled.  The workspace of such a plan holds static lookup tables: */
 
 /* Uploads the plan's segment tables into the workspace, and last a tag that identifies them.  Required once per
- * workspace, before its first use, when the plan has num_segments >= 1; a no-op otherwise.  Asynchronous on
- * `stream`; the plan must outlive the copy.  A step call on a workspace that does not carry this plan's tag reads
+ * workspace, before its first use, when the plan has num_segments >= 1; a no-op otherwise.  Enqueues on `stream`
+ * and synchronises it before returning (a set-up call: the tables are copied from the plan's own host memory, which
+ * may then be released at any time).  A step call on a workspace that does not carry this plan's tag reads
  * no table and writes no output: its kernels exit at once and leave a mark, which a2sgd_read_segment_stats (and
  * a2sgd_read_stats with pooled means) reports as A2SGD_ERR_WORKSPACE_STATE until a2sgd_workspace_init has run. */
 a2sgd_status_t a2sgd_workspace_init(const a2sgd_plan_t *plan, void *workspace, a2sgd_stream_t stream);

@@ -179,6 +179,10 @@ void build_segments(a2sgd_plan_t &pl, uint32_t S, const uint64_t *len, const uin
     o = align_up(o + 8ull * S, 256);
     sp.off_records = o;
     o = align_up(o + 5ull * 8ull * pl.P * sp.item.size(), 256);
+    if (pl.apply.two_kernels) {  // one sign bit per element and worker
+        sp.off_sign = o;
+        o = align_up(o + 4ull * pl.P * (64ull * pl.lazy_blocks), 256);
+    }
     if (!sp.fitem.empty()) {
         sp.off_fitem = o;
         o = align_up(o + sizeof(SegItem) * sp.fitem.size(), 256);
@@ -501,8 +505,7 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
     pl->apply.dense_lds_bytes = pl->streaming ? dense_lds_bytes(pl->P) : 0;
     // From kTwoKernelWorkers workers on, a workgroup of the one-kernel apply pass has so many buffers open (2P + 1)
     // that address translation costs it more than the sign words cost the two-kernel form (nP/4 extra bytes).
-    pl->apply.two_kernels = pl->streaming && cfg->num_segments == 0 && pl->mode == A2SGD_MODE_RETAINED_ERROR &&
-                            pl->P >= kTwoKernelWorkers;
+    pl->apply.two_kernels = pl->streaming && pl->mode == A2SGD_MODE_RETAINED_ERROR && pl->P >= kTwoKernelWorkers;
     pl->device = cfg->device;
     // Single-launch step while everything fits the caches: one workgroup of kFusedBlock threads per 2048 elements,
     // at most kFusedGridMax of them.  It needs a grid-barrier cell of its own; without one the plan runs the three
@@ -523,12 +526,14 @@ a2sgd_status_t a2sgd_plan(const a2sgd_config_t *cfg, a2sgd_plan_t **out_plan)
     const size_t drift = 2ull * 8ull * pl->P * (kDriftBlocks + 1);  // the drift diagnostic reuses the same region
     pl->workspace_bytes = kHeaderBytes + (partials > drift ? partials : drift);
     pl->eager_bytes = pl->workspace_bytes;
-    pl->lazy_blocks = pl->lazy_folded = 0;
+    pl->lazy_folded = 0;
     pl->lazy_offset = pl->lazy_sign_offset = 0;
-    if (cfg->num_segments == 0) {
-        // one record per workgroup of the lazy state's one-shot reduction pass, and their folded table
+    {
         const uint64_t per = 64ull * kLazyItems, nvec = pl->n >> 2;
         pl->lazy_blocks = static_cast<uint32_t>(nvec ? (nvec + per - 1) / per : 1);
+    }
+    if (cfg->num_segments == 0) {
+        // one record per workgroup of the lazy state's one-shot reduction pass, and their folded table
         pl->lazy_folded = (pl->lazy_blocks + kFoldSpan - 1) / kFoldSpan;
         pl->lazy_offset = (pl->workspace_bytes + 255) & ~static_cast<size_t>(255);
         pl->lazy_sign_offset = pl->lazy_offset + 5ull * 8ull * pl->P * (static_cast<size_t>(pl->lazy_blocks) + pl->lazy_folded);
@@ -1126,7 +1131,10 @@ a2sgd_status_t a2sgd_workspace_init(const a2sgd_plan_t *plan, void *workspace, a
          hipMemcpyAsync(b + sp.off_fitem_lo, sp.fitem_lo.data(), 4ull * sp.fitem_lo.size(), hipMemcpyHostToDevice, s) != hipSuccess))
         return A2SGD_ERR_DEVICE;
     // last, in stream order: the tag that tells the kernels whose tables these are
-    return dev(launch_seg_mark(*plan, workspace, s));
+    if ((st = dev(launch_seg_mark(*plan, workspace, s))) != A2SGD_OK)
+        return st;
+    // the copies read the plan's own host vectors: wait for them, so that the plan may be destroyed at any time
+    return hipStreamSynchronize(s) == hipSuccess ? A2SGD_OK : A2SGD_ERR_DEVICE;
 }
 
 a2sgd_status_t a2sgd_read_segment_stats(const a2sgd_plan_t *plan, const void *workspace, a2sgd_stream_t stream,

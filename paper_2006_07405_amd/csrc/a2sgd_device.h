@@ -143,6 +143,24 @@ __device__ __forceinline__ bool seg_tables_ok(const SegView &sv)
     return false;
 }
 
+// Where the sign words of worker p for half h of the 2048-element block b start: uint16_t sign[blocks][2][P][64].
+// A workgroup of the pass that reads them covers one (b, h) and finds every worker's 128 bytes side by side.
+__device__ __forceinline__ uint16_t *sign_row(uint16_t *sign, const uint32_t P, const uint64_t b, const uint32_t h,
+                                              const uint32_t p)
+{
+    return sign + ((b * 2 + h) * P + p) * 64;
+}
+
+// Shifts pos(v) of the four components into the low end of `bits`, x first.
+__device__ __forceinline__ uint32_t push_signs(uint32_t bits, vf4 v)
+{
+    bits = bits * 2u + (v.x >= 0.0f ? 1u : 0u);
+    bits = bits * 2u + (v.y >= 0.0f ? 1u : 0u);
+    bits = bits * 2u + (v.z >= 0.0f ? 1u : 0u);
+    bits = bits * 2u + (v.w >= 0.0f ? 1u : 0u);
+    return bits;
+}
+
 // A zero the compiler cannot see through, in a vector register.  Added to an index it turns a load with a
 // wavefront-uniform address into an ordinary vector load.  The apply pass wants that for the handful of means
 // it reads from the workspace: vector loads return in issue order and are counted apart from the scalar loads

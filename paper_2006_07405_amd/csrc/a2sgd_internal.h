@@ -151,6 +151,7 @@ struct SegPlan {
     std::vector<SegItem> fitem;       // items of the single-launch step; empty if the plan cannot take it
     std::vector<uint32_t> fitem_lo;
     size_t off_fitem = 0, off_fitem_lo = 0, off_frecords = 0;
+    size_t off_sign = 0;  // sign words of the two-kernel apply pass (plans that take it)
     uint64_t tag = 0;  // checksum of the tables above and of the sizes that fix their layout; never 0
     // byte offsets into the workspace
     size_t off_seg_start = 0, off_seg_end = 0, off_item = 0, off_item_lo = 0, off_coarse = 0, off_sched_lo = 0, off_sched_item = 0,
@@ -174,7 +175,8 @@ struct a2sgd_plan {
     int32_t barrier_cell;         // the grid-barrier cell this plan owns until it is destroyed; -1 = none
     mutable uint32_t last_token;  // token of the last single-launch step enqueued with this plan; 0 = none
     a2sgd::SegPlan seg;
-    uint32_t lazy_blocks;  // workgroups per worker of the lazy state's reduction pass (one record each)
+    uint32_t lazy_blocks;  // blocks of 2048 elements: workgroups per worker of the lazy state's reduction pass (one
+                           // record each) and rows of sign words
     uint32_t lazy_folded;  // records per worker after k_fold_partials
     size_t lazy_offset;    // byte offset of those records in the workspace; 0 = the plan has no lazy state
     size_t lazy_sign_offset;  // byte offset of the sign words

@@ -1043,24 +1043,6 @@ __global__ void k_replica_drift_finalize(const uint64_t n, const uint32_t P, con
 // groups per thread, all loads issued before the first store (a loop would wait for its own older stores before
 // it could use newer loads, since both are counted together).  Every workgroup writes one record; the records
 // of a worker are combined in index order by k_fold_partials and k_local_finalize.
-// Where the sign words of worker p for half h of the 2048-element block b start: uint16_t sign[blocks][2][P][64].
-// A workgroup of the pass that reads them covers one (b, h) and finds every worker's 128 bytes side by side.
-__device__ __forceinline__ uint16_t *sign_row(uint16_t *sign, const uint32_t P, const uint64_t b, const uint32_t h,
-                                              const uint32_t p)
-{
-    return sign + ((b * 2 + h) * P + p) * 64;
-}
-
-// Shifts pos(v) of the four components into the low end of `bits`, x first.
-__device__ __forceinline__ uint32_t push_signs(uint32_t bits, vf4 v)
-{
-    bits = bits * 2u + (v.x >= 0.0f ? 1u : 0u);
-    bits = bits * 2u + (v.y >= 0.0f ? 1u : 0u);
-    bits = bits * 2u + (v.z >= 0.0f ? 1u : 0u);
-    bits = bits * 2u + (v.w >= 0.0f ? 1u : 0u);
-    return bits;
-}
-
 // With SIGNS the pass also leaves pos(v) of Eq. 2 as one bit per element for the apply pass: thread `tid` of
 // workgroup b collects 32 bits, bit 31 - (4 * u + c) for component c of its float4 group u (0 where the group lies
 // past the end), and writes them as two 16-bit halves, sign[b][h][p][tid] (h = 0: groups 0-3), so that a

@@ -164,6 +164,8 @@ __global__ __launch_bounds__(64) void k_seg_finalize(const SegView sv)
     const uint32_t s = blockIdx.x, p = blockIdx.y, lane = threadIdx.x;
     if (!seg_tables_ok(sv))
         return;
+    if (s == 0 && p == 0 && lane == 0)
+        sv.hdr->any_nan = 0u;  // k_seg_global, next on the stream, raises it if any worker counted a NaN in any tensor
     const uint32_t lo = sv.item_lo[s], hi = sv.item_lo[s + 1];
     const size_t row = static_cast<size_t>(p) * sv.num_items;
     double sp = 0.0, sn = 0.0;
@@ -200,6 +202,8 @@ __global__ __launch_bounds__(kBlock) void k_seg_finalize_pooled(const SegView sv
 {
     const uint32_t p = blockIdx.x, tid = threadIdx.x;
     const size_t row = static_cast<size_t>(p) * sv.num_items;
+    if (p == 0 && tid == 0)
+        sv.hdr->any_nan = 0u;  // as in k_seg_finalize
     double sp = 0.0, sn = 0.0;
     uint64_t cp = 0, cn = 0, cz = 0;
     for (uint32_t j = tid; j < sv.num_items; j += kBlock) {
@@ -258,8 +262,10 @@ __global__ __launch_bounds__(64) void k_seg_global(const uint32_t P, const SegVi
     if (s >= sv.S)
         return;
     double sp = 0.0, sn = 0.0;
+    bool any_nan = false;
     for (uint32_t p = 0; p < P; ++p) {
         const a2sgd_worker_stats_t &r = sv.stats[static_cast<size_t>(p) * sv.S + s];
+        any_nan |= r.n_nan != 0;
         sp += static_cast<double>(r.mu_pos);
         sn += static_cast<double>(r.mu_neg);
         sv.neg_mu_pos[static_cast<size_t>(s) * P + p] = -r.mu_pos;
@@ -267,6 +273,8 @@ __global__ __launch_bounds__(64) void k_seg_global(const uint32_t P, const SegVi
     }
     sv.gmu[2 * s] = static_cast<float>(sp / static_cast<double>(P));
     sv.gmu[2 * s + 1] = -static_cast<float>(sn / static_cast<double>(P));
+    if (any_nan)
+        atomicOr(&sv.hdr->any_nan, 1u);  // an integer flag: a NaN has no sign bit for the two-kernel apply pass
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -422,6 +430,216 @@ __global__ __launch_bounds__(BLOCK) void k_seg_apply(const PtrTable tab, float *
         const uint32_t s = seg_of(sv, sv.coarse[idx >> kSegCoarseShift] & ~kSegInsideBit, idx);
         if (sv.seg_start[s] <= idx)
             seg_apply_element<MODE, HAS_E>(tab, w, idx, s, P, eta_over_P, sv);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Apply pass as two kernels (retained-error mode, many workers, streaming sizes): as in the whole-model form the
+// update of a parameter depends only on how many workers have it in the positive group, now with the global means
+// of the parameter's tensor.  k_seg_error_signs rewrites one worker's errors per workgroup and leaves pos(v) in
+// the sign words; k_seg_apply_signs updates w from them.  A workgroup covers 1024 elements, i.e. four entries of
+// the lookup table; a chunk that lies wholly inside one tensor takes that tensor's means for all its elements, the
+// others look every element up (padding is neither written nor given a sign bit).
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kSegSignItems = 4;  // float4 groups per array per thread: half a sign row per workgroup
+
+// The segment of each of a float4 group's four elements (or S where the element is padding), scanning from s0.
+__device__ __forceinline__ void seg_of4(const SegView &sv, uint32_t s0, const uint64_t first, uint32_t sc[4])
+{
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        s0 = seg_of(sv, s0, first + c);
+        sc[c] = sv.seg_start[s0] <= first + c ? s0 : sv.S;
+    }
+}
+
+template <bool NT>
+__global__ __launch_bounds__(64) void k_seg_error_signs(const PtrTable tab, const uint64_t n, const uint64_t chunks,
+                                                        const SegView sv, uint16_t *__restrict__ sign)
+{
+    const uint32_t p = blockIdx.y, P = gridDim.y, lane = threadIdx.x;
+    const vf4 *__restrict__ g4 = reinterpret_cast<const vf4 *>(tab.g[p]);
+    float *e = tab.e[p];
+    vf4 *e4 = reinterpret_cast<vf4 *>(e);
+    const uint64_t nvec = n >> 2;
+    const uint64_t base = static_cast<uint64_t>(blockIdx.x) * (64 * kSegSignItems) + lane;
+    vf4 gv[kSegSignItems], ev[kSegSignItems];
+#pragma unroll
+    for (int u = 0; u < kSegSignItems; ++u)
+        if (base + u * 64 < nvec) {
+            gv[u] = ld4<NT>(g4 + base + u * 64);
+            ev[u] = ld4<NT>(e4 + base + u * 64);
+        }
+    __builtin_amdgcn_sched_barrier(0);
+    static_assert(64 * 4 == (1 << kSegCoarseShift), "one lookup entry per 64 float4 groups");
+    uint32_t entry[kSegSignItems];
+#pragma unroll
+    for (int u = 0; u < kSegSignItems; ++u) {
+        const uint64_t c = static_cast<uint64_t>(blockIdx.x) * kSegSignItems + u;
+        entry[u] = c < chunks ? sv.coarse[c] : 0u;
+    }
+    if (!seg_tables_ok(sv))
+        return;
+    // the means of every chunk's first tensor, all asked for at once (behind the entries, ahead of the arithmetic):
+    // fetched chunk by chunk, each would cost the workgroup a memory latency with nothing else in flight
+    float nmp[kSegSignItems], mn[kSegSignItems];
+#pragma unroll
+    for (int u = 0; u < kSegSignItems; ++u) {
+        const uint32_t t = min(entry[u] & ~kSegInsideBit, sv.S - 1);  // S where no tensor follows: not used then
+        nmp[u] = sv.neg_mu_pos[static_cast<size_t>(t) * P + p];
+        mn[u] = sv.mu_neg[static_cast<size_t>(t) * P + p];
+    }
+    uint32_t bits = 0;
+#pragma unroll
+    for (int u = 0; u < kSegSignItems; ++u) {
+        const uint64_t i = base + u * 64;
+        if (i >= nvec) {
+            bits <<= 4;
+            continue;
+        }
+        const vf4 v = gv[u] + ev[u];
+        const uint32_t s0 = entry[u] & ~kSegInsideBit;
+        if (entry[u] & kSegInsideBit) {
+            bits = push_signs(bits, v);
+            const vf4 err = pending_error4(v, nmp[u], mn[u]);  // v - enc(v) with this tensor's means
+            st4<NT>(e4 + i, err);
+        } else {
+            uint32_t sc[4];
+            seg_of4(sv, s0, i << 2, sc);
+            const float x[4] = {v.x, v.y, v.z, v.w};
+            float err[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bool in = sc[c] != sv.S;
+                bits = bits * 2u + (in && x[c] >= 0.0f ? 1u : 0u);
+                err[c] = in ? pending_error(x[c], sv.neg_mu_pos[static_cast<size_t>(sc[c]) * P + p],
+                                            sv.mu_neg[static_cast<size_t>(sc[c]) * P + p])
+                            : 0.0f;
+            }
+            if (sc[0] != sv.S && sc[1] != sv.S && sc[2] != sv.S && sc[3] != sv.S) {
+                const vf4 out = vf4{err[0], err[1], err[2], err[3]};
+                st4<NT>(e4 + i, out);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (sc[c] != sv.S)
+                        e[(i << 2) + c] = err[c];
+            }
+        }
+    }
+    sign_row(sign, P, blockIdx.x / 2, blockIdx.x % 2, p)[lane] = static_cast<uint16_t>(bits);
+}
+
+template <bool NT, int UP>
+__global__ __launch_bounds__(64) void k_seg_apply_signs(const PtrTable tab, const uint16_t *__restrict__ sign,
+                                                        float *__restrict__ w, const uint64_t n, const uint64_t chunks,
+                                                        const uint32_t P, const float eta_over_P, const SegView sv)
+{
+    const uint32_t lane = threadIdx.x;
+    const uint64_t nvec = n >> 2;
+    const uint64_t base = static_cast<uint64_t>(blockIdx.x) * (64 * kSegSignItems) + lane;
+    vf4 *w4 = reinterpret_cast<vf4 *>(w);
+    vf4 wv[kSegSignItems];
+#pragma unroll
+    for (int u = 0; u < kSegSignItems; ++u)
+        if (base + u * 64 < nvec)
+            wv[u] = ld4<NT>(w4 + base + u * 64);
+    // k[u][c]: how many workers have component c of group u in the positive group
+    const uint16_t *half = sign + static_cast<uint64_t>(blockIdx.x) * P * 64 + lane;
+    uint32_t k[kSegSignItems][4];
+#pragma unroll
+    for (int u = 0; u < kSegSignItems; ++u)
+        k[u][0] = k[u][1] = k[u][2] = k[u][3] = 0;
+    uint32_t p0 = 0;
+    for (; p0 + UP <= P; p0 += UP) {
+        uint32_t d[UP];
+#pragma unroll
+        for (int q = 0; q < UP; ++q)
+            d[q] = half[(p0 + q) * 64];
+#pragma unroll
+        for (int q = 0; q < UP; ++q)
+#pragma unroll
+            for (int u = 0; u < kSegSignItems; ++u)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    k[u][c] += (d[q] >> (15u - (4u * u + c))) & 1u;
+    }
+    for (; p0 < P; ++p0) {
+        const uint32_t d = half[p0 * 64];
+#pragma unroll
+        for (int u = 0; u < kSegSignItems; ++u)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                k[u][c] += (d >> (15u - (4u * u + c))) & 1u;
+    }
+    uint32_t entry[kSegSignItems];
+#pragma unroll
+    for (int u = 0; u < kSegSignItems; ++u) {
+        const uint64_t c = static_cast<uint64_t>(blockIdx.x) * kSegSignItems + u;
+        entry[u] = c < chunks ? sv.coarse[c] : 0u;
+    }
+    if (!seg_tables_ok(sv))
+        return;
+    const bool any_nan = sv.hdr->any_nan != 0;  // the same for the whole grid
+    const float fP = static_cast<float>(P);
+    float gp0[kSegSignItems], ngn0[kSegSignItems];  // global means of every chunk's first tensor, asked for at once
+#pragma unroll
+    for (int u = 0; u < kSegSignItems; ++u) {
+        const uint32_t t = min(entry[u] & ~kSegInsideBit, sv.S - 1);
+        gp0[u] = sv.gmu[2 * t];
+        ngn0[u] = sv.gmu[2 * t + 1];
+    }
+#pragma unroll
+    for (int u = 0; u < kSegSignItems; ++u) {
+        const uint64_t i = base + u * 64;
+        if (i >= nvec)
+            continue;
+        // acc: the sum over the workers of +gmu_pos or -gmu_neg of the element's tensor (the table keeps -gmu_neg)
+        const uint32_t s0 = entry[u] & ~kSegInsideBit;
+        uint32_t sc[4] = {s0, s0, s0, s0};
+        float acc[4];
+        if (entry[u] & kSegInsideBit) {  // one tensor for the whole chunk
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                acc[c] = static_cast<float>(k[u][c]) * (gp0[u] - ngn0[u]) + fP * ngn0[u];
+        } else {
+            seg_of4(sv, s0, i << 2, sc);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t t = sc[c] != sv.S ? sc[c] : 0u;
+                const float gp = sv.gmu[2 * t], ngn = sv.gmu[2 * t + 1];
+                acc[c] = static_cast<float>(k[u][c]) * (gp - ngn) + fP * ngn;
+            }
+        }
+        if (any_nan) {
+            // a NaN has no sign bit, but it left a NaN in that worker's new error: that element's update is NaN
+            for (uint32_t p = 0; p < P; ++p) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (sc[c] != sv.S) {
+                        const float x = tab.e[p][(i << 2) + c];
+                        acc[c] = (x != x) ? x : acc[c];
+                    }
+            }
+        }
+        const float x[4] = {wv[u].x, wv[u].y, wv[u].z, wv[u].w};
+        if (sc[0] != sv.S && sc[1] != sv.S && sc[2] != sv.S && sc[3] != sv.S) {
+            const vf4 wn = vf4{x[0] - eta_over_P * acc[0], x[1] - eta_over_P * acc[1], x[2] - eta_over_P * acc[2],
+                               x[3] - eta_over_P * acc[3]};
+            st4<NT>(w4 + i, wn);
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (sc[c] != sv.S)
+                    w[(i << 2) + c] = x[c] - eta_over_P * acc[c];
+        }
+    }
+    // the last n % 4 elements, which k_seg_error_signs left alone, get the whole of lines 4, 6 and 7 here
+    if (blockIdx.x == gridDim.x - 1 && lane < (n & 3)) {
+        const uint64_t idx = (nvec << 2) + lane;
+        const uint32_t s = seg_of(sv, sv.coarse[idx >> kSegCoarseShift] & ~kSegInsideBit, idx);
+        if (sv.seg_start[s] <= idx)
+            seg_apply_element<A2SGD_MODE_RETAINED_ERROR, true>(tab, w, idx, s, P, eta_over_P, sv);
     }
 }
 
@@ -632,12 +850,36 @@ static hipError_t launch_seg_apply_shape(const a2sgd_plan_t &pl, const PtrTable 
     return hipGetLastError();
 }
 
+static hipError_t launch_seg_apply_two_kernels(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eop,
+                                               const SegView &sv, void *ws, hipStream_t s)
+{
+    uint16_t *sign = reinterpret_cast<uint16_t *>(static_cast<char *>(ws) + pl.seg.off_sign);
+    const uint64_t chunks = (pl.n + (1ull << kSegCoarseShift) - 1) >> kSegCoarseShift;
+    const uint32_t halves = pl.lazy_blocks * 2;  // workgroups of 1024 elements: two per row of sign words
+    // The lookup (table entries, then the means they point to) leaves a workgroup with nothing in flight for a while,
+    // so more of them share a compute unit than in the whole-model form: 13 per CU at 16 workers and more, 16 below
+    // (measured at configs 4 and 2: 4.18 ms against 5.06 ms and 0.417 ms against 0.510 ms with the whole-model
+    // form's 8 per CU).
+    const uint32_t lds = pl.P >= 16 ? 12 * 1024 : 10 * 1024;
+    k_seg_error_signs<true><<<dim3(halves, pl.P), dim3(64), lds, s>>>(tab, pl.n, chunks, sv, sign);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess)
+        return err;
+    if (pl.P >= 16)
+        k_seg_apply_signs<true, 16><<<dim3(halves), dim3(64), 8 * 1024, s>>>(tab, sign, w, pl.n, chunks, pl.P, eop, sv);
+    else
+        k_seg_apply_signs<true, 8><<<dim3(halves), dim3(64), 8 * 1024, s>>>(tab, sign, w, pl.n, chunks, pl.P, eop, sv);
+    return hipGetLastError();
+}
+
 hipError_t launch_seg_apply(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, float *w, float eta, void *ws,
                             hipStream_t s)
 {
     const float eop = static_cast<float>(static_cast<double>(eta) / static_cast<double>(pl.P));
     const SegView sv = seg_view(pl, ws);
     const bool lit = pl.mode == A2SGD_MODE_ALG1_LITERAL;
+    if (pl.apply.two_kernels && !lit && has_e)
+        return launch_seg_apply_two_kernels(pl, tab, w, eop, sv, ws, s);
 #define A2SGD_SEG_CASE(L, E, N)                                                                                  \
     if (lit == L && has_e == E && pl.streaming == N)                                                             \
         return launch_seg_apply_shape<L ? A2SGD_MODE_ALG1_LITERAL : A2SGD_MODE_RETAINED_ERROR, E, N>(pl, tab, w, eop, \

@@ -276,7 +276,8 @@ def test_dense_step(A):
         assert_array_close(wd.cpu().numpy(), O.dense_step(g, w, 0.1), f"dense n={n} P={P}")
 
 
-@pytest.mark.parametrize("n,P", [(8_000_003, 3), (3_500_003, 7), (2_100_001, 12), (1_700_003, 15), (1_000_001, 33)])
+@pytest.mark.parametrize("n,P", [(8_000_003, 3), (3_500_003, 7), (2_100_001, 12), (1_700_003, 15), (1_000_001, 33),
+                                 (420_001, 64)])
 def test_streaming_path_with_worker_counts_that_leave_a_short_group(A, n, P):
     """Footprints above the cache limit take the streaming kernels (non-temporal loads, write-through stores, capped
     residency); these P are not multiples of the group size, so the last group of workers is a short one.  Eager

@@ -183,9 +183,45 @@ def test_streaming_size_with_padding(A):
     n = 3_500_003
     run_padded_case(A, 11, n, 7, 0, seg, off, pooled=False)
     run_padded_case(A, 12, n, 7, 0, seg, off, pooled=True)
+    # from 8 workers on the apply pass is two kernels (errors and sign bits, then the weights from the sign bits)
+    run_padded_case(A, 13, n, 8, 0, seg, off, pooled=False)
+    run_padded_case(A, 14, n, 9, 0, seg, off, pooled=True)
 
 
-@pytest.mark.parametrize("P,mode", [(7, 0), (12, 1), (16, 0), (33, 1)])
+def test_two_kernel_apply_on_a_tensor_plan_with_nans(A):
+    """The per-tensor apply pass in its two-kernel form (8 workers, streaming size) when some gradients are NaN: a
+    NaN has no sign bit; its element of e and w becomes NaN and nothing else changes.  Two steps on carried state."""
+    seg = [1_000_003, 5, 777_777, 64, 1_300_001, 131_072, 2, 291_079]
+    n, P = sum(seg), 8
+    assert (2 * P + 1) * 4 * n > 192 << 20
+    g, e, w = make_case(n, n, P, scales_for(seg, 5))
+    rng = np.random.default_rng(8)
+    for p in (0, 3, P - 1):
+        g[p][rng.integers(0, n, 6)] = np.nan
+    g[2][n - 1] = np.nan   # the scalar tail
+    g[5][1_000_003] = np.nan  # a tensor of five elements
+    plan = A.a2sgd_plan(n, P, 0, 0, seg_lengths=seg)
+    ws = A.alloc_workspace(plan)
+    gd, ed, wd = [dev(x) for x in g], [dev(x) for x in e], dev(w)
+    e_o, w_o = e, w
+    for t in range(2):
+        A.a2sgd_local_averages(plan, gd, ed, ws)
+        A.a2sgd_global_average(plan, ws)
+        A.a2sgd_apply_and_update_error(plan, gd, ed, wd, 0.1, ws)
+        stats, gmu = A.a2sgd_read_segment_stats(plan, ws)
+        res, e_o, w_o = O.step_segmented(g, e_o, w_o, 0.1, 0, seg)
+        assert sum(stats[p][k].n_nan for p in range(P) for k in range(len(seg))) == sum(r.workers[p].n_nan for r in res for p in range(P)) > 0
+        off = 0
+        for k, length in enumerate(seg):
+            for p in range(P):
+                a, b = stats[p][k], res[k].workers[p]
+                assert (a.n_pos, a.n_neg, a.n_zero, a.n_nan) == (b.n_pos, b.n_neg, b.n_zero, b.n_nan)
+                assert_array_close(ed[p][off:off + length].cpu().numpy(), e_o[p][off:off + length], f"step {t} e[{p}] tensor {k}")
+            assert_array_close(wd[off:off + length].cpu().numpy(), w_o[off:off + length], f"step {t} w tensor {k}")
+            off += length
+
+
+@pytest.mark.parametrize("P,mode", [(7, 0), (12, 1), (16, 0), (33, 1), (9, 0), (33, 0)])
 def test_streaming_size_with_a_short_group_of_workers(A, P, mode):
     """A footprint above the cache limit (streaming kernels) with tensor boundaries of every alignment and a worker
     count that is not a multiple of the group size; 16 and 33 workers take the widest groups of the apply pass, two
