@@ -290,6 +290,27 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout == ""
 
 
+def test_streaming_kernel_library_loads_and_validates():
+    """The benchmark's plain streaming kernels (bandwidth ceilings) are a library of their own: it loads, prices its
+    launches, and turns bad arguments down before any launch."""
+    path = os.path.join(ROOT, "paper_2006_07405_amd", "libhbm_streams.so")
+    assert os.path.exists(path), "run build() first"
+    L = C.CDLL(path)
+    L.hbm_stream_bytes.restype = C.c_uint64
+    L.hbm_stream_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.c_uint64]
+    L.hbm_stream_run.argtypes = [C.c_int, C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_uint64, C.c_void_p]
+    n = 1 << 20
+    assert [L.hbm_stream_bytes(k, 9, 5, n) for k in (0, 1, 2, 3, 4)] == [4 * n, 8 * n, 12 * n, 56 * n, 0]
+    tab = (C.c_void_p * 9)(*[0x10000 * (k + 1) for k in range(9)])
+    assert L.hbm_stream_run(1, None, 2, 1, n, None) == 1       # no table
+    assert L.hbm_stream_run(7, tab, 2, 1, n, None) == 1        # unknown kind
+    assert L.hbm_stream_run(1, tab, 2, 1, n + 1, None) == 1    # whole float4 groups only
+    assert L.hbm_stream_run(3, tab, 8, 4, n, None) == 1        # the mix is 2P + 1 read, P + 1 written
+    assert L.hbm_stream_run(3, tab, 9, 4, n, None) == 1
+    bad = (C.c_void_p * 2)(0x10000, 0x20004)
+    assert L.hbm_stream_run(1, bad, 2, 1, n, None) == 2        # alignment
+
+
 def test_header_is_plain_c(tmp_path):
     """include/a2sgd.h compiles as C99 with no extensions and no other headers than the two standard ones."""
     import subprocess
