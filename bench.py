@@ -296,10 +296,12 @@ def main() -> int:
                                "params_per_s": n / (ms_rep * 1e-3)}
         del wr
 
-    if not plan.num_segments:  # the lazy state is not offered with per-tensor means
+    if True:
         # The same step on the lazy error state: the buffers keep v, the error is formed on the next read, and in
         # this mode the apply pass reads one sign bit per element-worker that the reduction pass left (12nP + 8n
-        # bytes plus nP/8 written and read).  A different contract for what e holds.
+        # bytes plus nP/8 written and read; with per-tensor means it reads v: 16nP + 8n).  A different contract for
+        # what e holds.
+        lazy_bytes = (16 * n * P + 8 * n) if plan.num_segments else (12.25 * n * P + 8 * n)
         A.a2sgd_lazy_reset(plan, ws)
         for _ in range(2):
             A.a2sgd_lazy_step(plan, g, e, w, wl.eta, ws)
@@ -313,7 +315,7 @@ def main() -> int:
         A.a2sgd_lazy_materialize(plan, e, ws)
         ev1.record()
         torch.cuda.synchronize()
-        out["lazy_step"] = {"ms": ms_lazy, "gbps": (12.25 * n * P + 8 * n) / (ms_lazy * 1e-3) / 1e9,
+        out["lazy_step"] = {"ms": ms_lazy, "gbps": lazy_bytes / (ms_lazy * 1e-3) / 1e9,
                             "params_per_s": n / (ms_lazy * 1e-3), "materialize_ms": ev0.elapsed_time(ev1)}
 
     if not args.no_cpu_baseline:

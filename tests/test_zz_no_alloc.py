@@ -100,6 +100,33 @@ def test_carried_state_over_several_calls_and_literal_mode_without_e(A):
     assert_array_close(wd.cpu().numpy(), O.step(g, None, w, 0.05, 1).w_new, "literal mode, e = NULL")
 
 
+def test_captured_in_a_hip_graph(A):
+    """One of the callers the entry point is for: code under stream capture.  After one eager call (which looks the
+    array's address up), the call is captured and replayed three times with eager work and host waits between the
+    replays; every replay must leave what an eager call leaves."""
+    n, P = 2_000_003, 4
+    g, e, w = make_case(11, n, P)
+    plan = A.a2sgd_plan(n, P, 0)
+    gd = [dev(x) for x in g]
+    e_ref, w_ref = [dev(x) for x in e], dev(w)
+    expected = []
+    for _ in range(3):
+        A.a2sgd_step_static(plan, gd, e_ref, w_ref, 0.1)
+        expected.append(([x.clone() for x in e_ref], w_ref.clone()))
+    ed, wd = [dev(x) for x in e], dev(w)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        A.a2sgd_step_static(plan, gd, ed, wd, 0.1)
+    for k in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        busy = (w_ref * 2.0).sum().item()  # unrelated eager work and a host wait between replays
+        assert busy == busy
+        assert torch.equal(wd, expected[k][1]), f"replay {k}: w differs from the eager call"
+        assert all(torch.equal(a, b) for a, b in zip(ed, expected[k][0])), f"replay {k}: e differs from the eager call"
+
+
 def test_limits_and_argument_errors(A):
     n, P = 1_000_000, 2
     g, e, w = make_case(9, n, P)
