@@ -146,9 +146,11 @@ a2sgd_status_t a2sgd_apply_and_update_error(const a2sgd_plan_t *plan, const floa
  * another fixed order).  When g, e and w together are small enough to stay in the on-chip caches (below 192 MiB)
  * the step is ONE kernel launch with a grid-wide barrier inside; larger models run the three passes.  The
  * barrier's cell is library-owned device memory, one of 64 cells: such a plan owns one from a2sgd_plan to
- * a2sgd_plan_destroy, so no two live plans share a cell and their steps may run at the same time on different
- * streams; a plan made while all 64 are taken runs the three passes, as does any plan on a device with fewer
- * compute units than its grid has workgroups (a2sgd_plan_single_launch_cell tells).  Calls with the same plan must
+ * a2sgd_plan_destroy, so no two live plans share a cell; a plan made while all 64 are taken runs the three passes,
+ * as does any plan on a device with fewer compute units than its grid has workgroups
+ * (a2sgd_plan_single_launch_cell tells).  The launch needs its whole grid on the device at once, and the device
+ * holds two such grids: single-launch steps of two plans may run at the same time on two streams; with more than two
+ * in flight at once a grid may have to wait for another to drain, within the bounded wait described next.  Calls with the same plan must
  * not overlap (they share the workspace anyway).  The barrier's wait is bounded; should it ever run out, that
  * step's outputs are invalid and later single-launch steps of the plan do nothing, until a2sgd_read_stats reports
  * it once with A2SGD_ERR_DEVICE; from then on the plan runs the three passes. */

@@ -31,8 +31,9 @@ constexpr uint64_t kMaxN = 1ull << 38;
 constexpr uint32_t kComputeUnits = 256;
 constexpr uint32_t kReduceBlocksPerCU = 2;
 // The single-launch step asks for at most this many workgroups of kFusedBlock threads; a2sgd_step launches it only
-// on a device that has at least as many compute units as the plan's grid has workgroups (one per CU, where four
-// would fit: the whole grid is resident at once, which its grid-wide barrier relies on).
+// on a device that has at least as many compute units as the plan's grid has workgroups.  Its kernels are built for
+// two workgroups per compute unit (launch bounds), so one grid is resident as a whole even next to a second one:
+// that is what its grid-wide barrier relies on.
 constexpr uint32_t kFusedGridMax = 256;
 
 // The apply pass runs single-wavefront workgroups and caps how many share a CU through its dynamic-LDS request

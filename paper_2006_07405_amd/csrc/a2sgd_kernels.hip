@@ -432,8 +432,11 @@ constexpr int kFusedUnroll = 4;  // float4 groups per thread per loop trip in th
 // grid-wide barrier every workgroup combines the G records of each worker in the same fixed order, so all of
 // them hold bit-identical means without a second barrier; phase 3 is the apply pass on the slice.  Workgroup 0
 // also writes the header that a2sgd_read_stats reads.  The last n % 4 elements belong to the last workgroup.
+// The second launch bound asks for 4 wavefronts per SIMD, i.e. two workgroups per compute unit (at most 128 vector
+// registers, which is why the workers are taken in groups of 4 at most here): the single-launch steps of two plans
+// then fit the device together whatever their grids.
 template <int MODE, bool HAS_E, int UP>
-__global__ __launch_bounds__(kFusedBlock) void k_fused_step(const PtrTable tab, float *__restrict__ w, const uint64_t n,
+__global__ __launch_bounds__(kFusedBlock, 4) void k_fused_step(const PtrTable tab, float *__restrict__ w, const uint64_t n,
                                                        const uint32_t P, const float eta_over_P, const Partials part,
                                                        WsHeader *__restrict__ hdr, const uint32_t slot,
                                                        const uint32_t token)
@@ -570,6 +573,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused_step(const PtrTable tab, 
     const float gmu_pos = s_gmu[0], neg_gmu_neg = -s_gmu[1];
 
     // ---- phase 3: error write-back and weight update on the same slice (bounds: hi instead of nvec)
+    static_assert(UP <= 4, "groups of 8 workers would need more than 128 vector registers");
     for (uint64_t i = lo + tid; i < hi; i += 2 * kFusedBlock)
         apply_body<MODE, HAS_E, false, UP, 2, kFusedBlock, false>(tab, w, hi, i, P, eta_over_P, s_neg_mu_pos, s_mu_neg,
                                                              gmu_pos, neg_gmu_neg);
@@ -599,7 +603,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused_step(const PtrTable tab, 
 // before its first and after its last 16-byte boundary go one per thread.  Everything that crosses a barrier is
 // written and read with device-scope accesses, as in k_fused_step.
 template <int MODE, bool HAS_E, int UP>
-__global__ __launch_bounds__(kFusedBlock) void k_seg_fused_step(const PtrTable tab, float *__restrict__ w, const uint32_t P,
+__global__ __launch_bounds__(kFusedBlock, 4) void k_seg_fused_step(const PtrTable tab, float *__restrict__ w, const uint32_t P,
                                                                 const float eta_over_P, const SegView sv,
                                                                 const FusedSegView fv, const uint32_t slot,
                                                                 const uint32_t token)
@@ -768,6 +772,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_seg_fused_step(const PtrTable t
             scalar(lo + tid);
         // an item has at most kFusedItemElems / 4 float4 groups: two per thread
         static_assert(kFusedItemElems == 2 * 4 * kFusedBlock, "apply_body covers an item with ITEMS = 2");
+        static_assert(UP <= 4, "groups of 8 workers would need more than 128 vector registers");
         if ((a >> 2) + tid < (z >> 2))
             apply_body<MODE, HAS_E, false, UP, 2, kFusedBlock, false>(tab, w, z >> 2, (a >> 2) + tid, P, eta_over_P,
                                                                      s_neg_mu_pos, s_mu_neg, gmu_pos, neg_gmu_neg);
@@ -1626,7 +1631,7 @@ static hipError_t launch_fused_inst(const a2sgd_plan_t &pl, const PtrTable &tab,
     const Partials part = partials_of(ws, pl.P, pl.fused_grid);
     WsHeader *hdr = static_cast<WsHeader *>(ws);
     switch (pl.apply.up) {
-    case 8: k_fused_step<MODE, HAS_E, 8><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, static_cast<uint32_t>(pl.barrier_cell), token); break;
+    case 8:
     case 4: k_fused_step<MODE, HAS_E, 4><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, static_cast<uint32_t>(pl.barrier_cell), token); break;
     case 2: k_fused_step<MODE, HAS_E, 2><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, static_cast<uint32_t>(pl.barrier_cell), token); break;
     default: k_fused_step<MODE, HAS_E, 1><<<grid, block, 0, s>>>(tab, w, pl.n, pl.P, eop, part, hdr, static_cast<uint32_t>(pl.barrier_cell), token); break;
@@ -1671,7 +1676,7 @@ static hipError_t launch_seg_fused_inst(const a2sgd_plan_t &pl, const PtrTable &
     const FusedSegView fv = fused_seg_view(pl, ws);
     const uint32_t cell = static_cast<uint32_t>(pl.barrier_cell);
     switch (pl.apply.up) {
-    case 8: k_seg_fused_step<MODE, HAS_E, 8><<<grid, block, 0, s>>>(tab, w, pl.P, eop, sv, fv, cell, token); break;
+    case 8:
     case 4: k_seg_fused_step<MODE, HAS_E, 4><<<grid, block, 0, s>>>(tab, w, pl.P, eop, sv, fv, cell, token); break;
     case 2: k_seg_fused_step<MODE, HAS_E, 2><<<grid, block, 0, s>>>(tab, w, pl.P, eop, sv, fv, cell, token); break;
     default: k_seg_fused_step<MODE, HAS_E, 1><<<grid, block, 0, s>>>(tab, w, pl.P, eop, sv, fv, cell, token); break;

@@ -24,11 +24,12 @@ def A():
     return A
 
 
-def test_two_single_launch_steps_at_once_on_two_streams(A):
+@pytest.mark.parametrize("n,P", [(1_048_576, 4), (1_048_576, 8)])
+def test_two_single_launch_steps_at_once_on_two_streams(A, n, P):
     """Two plans made 64 plans apart (the distance at which cells used to repeat), each with its own cell, run their
-    single-launch steps on two streams at the same time for several steps; both must match the oracle."""
+    single-launch steps on two streams at the same time for several steps; both must match the oracle.  Both grids
+    have 256 workgroups: the device must hold the two together (two workgroups per compute unit at every P)."""
     gc.collect()
-    n, P = 1_048_576, 4
     first = A.a2sgd_plan(n, P, 0)
     fillers = [A.a2sgd_plan(4096, 1, 0) for _ in range(63)]
     del fillers[1:]  # 62 cells free again; the next plan gets the lowest free one, not first's
