@@ -3,7 +3,8 @@
 // the global means, the new errors and the new weights to another file.  Built by build(); run by a GPU test, which
 // writes the input with numpy and checks the output against the CPU oracle.
 //
-//   client <in> <out> <n> <P> <mode> <eta> <calls: 0 = a2sgd_step, 1 = the three calls>
+//   client <in> <out> <n> <P> <mode> <eta> <calls: 0 = a2sgd_step, 1 = the three calls, 2 = a2sgd_step_static>
+// After a2sgd_step_static there are no statistics to read (it has no workspace): that part of the output is zeros.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -39,7 +40,7 @@ int main(int argc, char **argv)
     const uint32_t P = static_cast<uint32_t>(std::atoi(argv[4]));
     const int mode = std::atoi(argv[5]);
     const float eta = static_cast<float>(std::atof(argv[6]));
-    const int three_calls = std::atoi(argv[7]);
+    const int calls = std::atoi(argv[7]);
 
     std::vector<float> host(n * (2ull * P + 1));
     std::FILE *in = std::fopen(argv[1], "rb");
@@ -66,20 +67,30 @@ int main(int argc, char **argv)
     }
     CHECK_HIP(hipMalloc(reinterpret_cast<void **>(&w), n * sizeof(float)));
     CHECK_HIP(hipMemcpy(w, host.data() + 2ull * P * n, n * sizeof(float), hipMemcpyHostToDevice));
-    CHECK_HIP(hipMalloc(&workspace, a2sgd_workspace_bytes(plan)));
+    const size_t workspace_bytes = a2sgd_workspace_bytes(plan);
+    CHECK_HIP(hipMalloc(&workspace, workspace_bytes));
+    CHECK_A2SGD(a2sgd_workspace_check(plan, workspace, workspace_bytes));
+    if (a2sgd_workspace_check(plan, workspace, workspace_bytes - 1) != A2SGD_ERR_WORKSPACE_TOO_SMALL) {
+        std::fprintf(stderr, "a2sgd_workspace_check accepted a workspace one byte short\n");
+        return 4;
+    }
 
     hipStream_t stream;
     CHECK_HIP(hipStreamCreate(&stream));
-    if (three_calls) {
+    std::vector<a2sgd_worker_stats_t> stats(P);
+    a2sgd_global_stats_t global = {};
+    if (calls == 2) {
+        CHECK_A2SGD(a2sgd_step_static(plan, g.data(), e.data(), w, eta, stream));
+        CHECK_HIP(hipStreamSynchronize(stream));
+    } else if (calls == 1) {
         CHECK_A2SGD(a2sgd_local_averages(plan, g.data(), e.data(), workspace, stream));
         CHECK_A2SGD(a2sgd_global_average(plan, workspace, stream));
         CHECK_A2SGD(a2sgd_apply_and_update_error(plan, g.data(), e.data(), w, eta, workspace, stream));
     } else {
         CHECK_A2SGD(a2sgd_step(plan, g.data(), e.data(), w, eta, workspace, stream));
     }
-    std::vector<a2sgd_worker_stats_t> stats(P);
-    a2sgd_global_stats_t global;
-    CHECK_A2SGD(a2sgd_read_stats(plan, workspace, stream, stats.data(), &global));  // waits for the stream
+    if (calls != 2)
+        CHECK_A2SGD(a2sgd_read_stats(plan, workspace, stream, stats.data(), &global));  // waits for the stream
 
     std::FILE *out = std::fopen(argv[2], "wb");
     if (out == nullptr)
