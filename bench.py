@@ -299,9 +299,9 @@ def main() -> int:
     if True:
         # The same step on the lazy error state: the buffers keep v, the error is formed on the next read, and in
         # this mode the apply pass reads one sign bit per element-worker that the reduction pass left (12nP + 8n
-        # bytes plus nP/8 written and read; with per-tensor means it reads v: 16nP + 8n).  A different contract for
+        # bytes plus nP/8 written and read), with whole-model and with per-tensor means.  A different contract for
         # what e holds.
-        lazy_bytes = (16 * n * P + 8 * n) if plan.num_segments else (12.25 * n * P + 8 * n)
+        lazy_bytes = 12.25 * n * P + 8 * n
         A.a2sgd_lazy_reset(plan, ws)
         for _ in range(2):
             A.a2sgd_lazy_step(plan, g, e, w, wl.eta, ws)

@@ -201,8 +201,7 @@ a2sgd_status_t a2sgd_dense_step(const a2sgd_plan_t *plan, const float *const *g,
  * (a2sgd_step is one kernel launch for such a plan too, when the model stays in the caches, has at most about 4 M
  * elements and its means are not pooled: the paper's own FNN-3 and ResNet-20 with a pair of means per layer),
  * and so do the replica calls and the lazy calls further down, each element with the means of its tensor (the lazy
- * state carries one pair of means per worker and tensor; its apply pass reads v in both modes, 16nP + 8n bytes per
- * step).  Not available on such a plan (A2SGD_ERR_INVALID_ARG): a2sgd_step_static, the export/import pair, and
+ * state carries one pair of means per worker and tensor, and the same bytes per step as on a whole-model plan).  Not available on such a plan (A2SGD_ERR_INVALID_ARG): a2sgd_step_static, the export/import pair, and
  * a2sgd_read_stats unless the means are pooled.  The workspace of such a plan holds static lookup tables: */
 
 /* Uploads the plan's segment tables into the workspace, and last a tag that identifies them.  Required once per

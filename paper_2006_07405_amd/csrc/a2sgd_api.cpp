@@ -154,6 +154,39 @@ void build_segments(a2sgd_plan_t &pl, uint32_t S, const uint64_t *len, const uin
         }
         sp.fitem_lo[S] = static_cast<uint32_t>(sp.fitem.size());
     }
+    // The lazy state's reduction: which blocks lie wholly inside one tensor (the kernel decides the same way, from
+    // the same lookup entries), and from that every tensor's slots in the folded table and the folds that fill them.
+    {
+        const uint64_t elems = kSegLazyElems, per = elems / 4, nvec = pl.n >> 2;
+        sp.lz_blocks = static_cast<uint32_t>((pl.n + elems - 1) / elems);
+        auto whole = [&](uint64_t b) {
+            if ((b + 1) * per > nvec)
+                return false;
+            const uint32_t first = sp.coarse[b * kSegLazyItems];
+            for (int u = 1; u < kSegLazyItems; ++u)
+                if (sp.coarse[b * kSegLazyItems + u] != first)
+                    return false;
+            return (first & kSegInsideBit) != 0;
+        };
+        sp.lz_slot_lo.resize(S + 1);
+        uint32_t slot = 0;
+        for (uint32_t k = 0; k < S; ++k) {
+            sp.lz_slot_lo[k] = slot;
+            const uint64_t f = sp.seg_start[k] / elems, l = (sp.seg_end[k] - 1) / elems;
+            const bool f_whole = whole(f), l_whole = whole(l);
+            if (f_whole)  // the tensor starts on a block of its own: nothing is left in its first slot
+                sp.lz_fold.push_back(SegFold{slot, 0, 0});
+            ++slot;
+            const uint64_t lo = f + (f_whole ? 0 : 1), hi = l + (l_whole ? 1 : 0);
+            for (uint64_t x = lo; x < hi; x += kSegFoldSpan)
+                sp.lz_fold.push_back(SegFold{slot++, static_cast<uint32_t>(x),
+                                             static_cast<uint32_t>(x + kSegFoldSpan < hi ? x + kSegFoldSpan : hi)});
+            if (l == f || l_whole)  // no shared last block
+                sp.lz_fold.push_back(SegFold{slot, 0, 0});
+            ++slot;
+        }
+        sp.lz_slot_lo[S] = slot;
+    }
     size_t o = pl.workspace_bytes;  // after the header and the whole-model partials region
     o = align_up(o, 256);
     sp.off_seg_start = o;
@@ -180,10 +213,14 @@ void build_segments(a2sgd_plan_t &pl, uint32_t S, const uint64_t *len, const uin
     o = align_up(o + 8ull * S, 256);
     sp.off_records = o;
     o = align_up(o + 5ull * 8ull * pl.P * sp.item.size(), 256);
-    if (pl.apply.two_kernels) {  // one sign bit per element and worker
-        sp.off_sign = o;
-        o = align_up(o + 4ull * pl.P * (64ull * pl.lazy_blocks), 256);
-    }
+    sp.off_lz_slot_lo = o;
+    o = align_up(o + 4ull * (S + 1), 256);
+    sp.off_lz_fold = o;
+    o = align_up(o + sizeof(SegFold) * sp.lz_fold.size(), 256);
+    sp.off_lz_records = o;
+    o = align_up(o + 5ull * 8ull * pl.P * sp.lz_blocks, 256);
+    sp.off_lz_folded = o;
+    o = align_up(o + 5ull * 8ull * pl.P * sp.lz_slot_lo[S], 256);
     if (!sp.fitem.empty()) {
         sp.off_fitem = o;
         o = align_up(o + sizeof(SegItem) * sp.fitem.size(), 256);
@@ -191,6 +228,10 @@ void build_segments(a2sgd_plan_t &pl, uint32_t S, const uint64_t *len, const uin
         o = align_up(o + 4ull * (S + 1), 256);
         sp.off_frecords = o;
         o = align_up(o + 5ull * 8ull * pl.P * sp.fitem.size(), 256);
+    }
+    if (pl.mode == A2SGD_MODE_RETAINED_ERROR) {  // one sign bit per element and worker, for the lazy state and the
+        sp.off_sign = o;                         // two-kernel apply pass: the last thing in the workspace
+        o += 4ull * pl.P * (64ull * pl.lazy_blocks);
     }
     sp.end = o;
 }
@@ -227,6 +268,8 @@ uint64_t tables_tag(const a2sgd_plan_t &pl)
     h = tag_words(h, sp.sched_item.data(), 4 * sp.sched_item.size());
     h = tag_words(h, sp.fitem.data(), sizeof(SegItem) * sp.fitem.size());
     h = tag_words(h, sp.fitem_lo.data(), 4 * sp.fitem_lo.size());
+    h = tag_words(h, sp.lz_slot_lo.data(), 4 * sp.lz_slot_lo.size());
+    h = tag_words(h, sp.lz_fold.data(), sizeof(SegFold) * sp.lz_fold.size());
     return h != 0 ? h : 1;
 }
 
@@ -986,12 +1029,8 @@ a2sgd_status_t a2sgd_lazy_local_averages(const a2sgd_plan_t *plan, const float *
     PtrTable tab;
     fill_table(tab, plan->P, g, s);
     plan->last_token = 0;
-    if (segmented(plan)) {
-        hipStream_t s = static_cast<hipStream_t>(stream);
-        if ((st = dev(launch_seg_lazy_partials(*plan, tab, workspace, s))) != A2SGD_OK)
-            return st;
-        return dev(launch_seg_finalize(*plan, workspace, s));
-    }
+    if (segmented(plan))
+        return dev(launch_seg_lazy_partials(*plan, tab, workspace, static_cast<hipStream_t>(stream)));
     return dev(launch_lazy_partials(*plan, tab, workspace, static_cast<hipStream_t>(stream)));
 }
 
@@ -1017,11 +1056,15 @@ a2sgd_status_t a2sgd_lazy_apply(const a2sgd_plan_t *plan, const float *const *s,
     if ((st = check_device(plan)) != A2SGD_OK)
         return st;
     PtrTable tab;
-    if (segmented(plan)) {
+    if (segmented(plan) && plan->mode == A2SGD_MODE_ALG1_LITERAL) {
         // the per-tensor apply pass with the stored v in the place of the gradient and no error buffer: it reads v,
-        // forms the update from its sign group (literal mode: and its error) and writes w only
+        // forms the update from its sign group and its error and writes w only
         fill_table(tab, plan->P, s, nullptr);
         return dev(launch_seg_apply(*plan, tab, false, w, eta, workspace, static_cast<hipStream_t>(stream)));
+    }
+    if (segmented(plan)) {  // retained-error mode: from the sign bits that the reduction pass left
+        fill_table(tab, plan->P, s, s);
+        return dev(launch_seg_lazy_apply_signs(*plan, tab, w, eta, workspace, static_cast<hipStream_t>(stream)));
     }
     fill_table(tab, plan->P, s, s);  // the pass reads the state buffers only
     return dev(launch_lazy_apply(*plan, tab, w, eta, workspace, static_cast<hipStream_t>(stream)));
@@ -1123,7 +1166,9 @@ a2sgd_status_t a2sgd_workspace_init(const a2sgd_plan_t *plan, void *workspace, a
                  {sp.off_item_lo, sp.item_lo.data(), 4ull * sp.item_lo.size()},
                  {sp.off_coarse, sp.coarse.data(), 4ull * sp.coarse.size()},
                  {sp.off_sched_lo, sp.sched_lo.data(), 4ull * sp.sched_lo.size()},
-                 {sp.off_sched_item, sp.sched_item.data(), 4ull * sp.sched_item.size()}};
+                 {sp.off_sched_item, sp.sched_item.data(), 4ull * sp.sched_item.size()},
+                 {sp.off_lz_slot_lo, sp.lz_slot_lo.data(), 4ull * sp.lz_slot_lo.size()},
+                 {sp.off_lz_fold, sp.lz_fold.data(), sizeof(SegFold) * sp.lz_fold.size()}};
     for (const auto &part : parts)
         if (hipMemcpyAsync(b + part.off, part.src, part.bytes, hipMemcpyHostToDevice, s) != hipSuccess)
             return A2SGD_ERR_DEVICE;

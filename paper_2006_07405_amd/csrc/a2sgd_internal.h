@@ -139,6 +139,20 @@ struct FusedSegView {
     uint64_t *r_npos, *r_nneg, *r_nzero;
 };
 
+// The lazy error state on a plan with tensors.  Its reduction is a one-shot pass over blocks of kSegLazyElems elements
+// by position, whatever the tensors: a block that lies wholly inside one tensor leaves one record in a table with a
+// row per block; any other block (a tensor boundary, padding, the end of the buffers) leaves one record per tensor it
+// touches, straight into that tensor's slots of the folded table.  Tensor s owns the folded records
+// lz_slot_lo[s] .. lz_slot_lo[s + 1] - 1: the first is its part of a shared first block, the last its part of a
+// shared last block, and between them its whole blocks added up kSegFoldSpan at a time by the entries of `lz_fold`
+// (an entry with hi == lo clears a first or last slot that no block writes).
+constexpr int kSegLazyItems = 8;  // float4 groups per array per thread, as in the whole-model form: a full sign row
+constexpr uint32_t kSegLazyElems = 256u * kSegLazyItems;
+constexpr uint32_t kSegFoldSpan = 1024;
+struct SegFold {
+    uint32_t slot, lo, hi;  // folded record `slot` = the block records [lo, hi) added in index order
+};
+
 struct SegPlan {
     uint32_t S = 0;  // 0 = the plan has no segments: whole-model means over [0, n)
     bool pooled = false;  // one pair of means per worker over all segments together
@@ -151,7 +165,11 @@ struct SegPlan {
     std::vector<SegItem> fitem;       // items of the single-launch step; empty if the plan cannot take it
     std::vector<uint32_t> fitem_lo;
     size_t off_fitem = 0, off_fitem_lo = 0, off_frecords = 0;
-    size_t off_sign = 0;  // sign words of the two-kernel apply pass (plans that take it)
+    size_t off_sign = 0;  // sign words of the two-kernel apply pass and of the lazy state (retained-error mode)
+    uint32_t lz_blocks = 0;              // blocks of kSegLazyElems elements by position: ceil(n / kSegLazyElems)
+    std::vector<uint32_t> lz_slot_lo;    // [S + 1]
+    std::vector<SegFold> lz_fold;
+    size_t off_lz_slot_lo = 0, off_lz_fold = 0, off_lz_records = 0, off_lz_folded = 0;
     uint64_t tag = 0;  // checksum of the tables above and of the sizes that fix their layout; never 0
     // byte offsets into the workspace
     size_t off_seg_start = 0, off_seg_end = 0, off_item = 0, off_item_lo = 0, off_coarse = 0, off_sched_lo = 0, off_sched_item = 0,
@@ -230,7 +248,11 @@ hipError_t launch_seg_fused_step(const a2sgd_plan_t &pl, const PtrTable &tab, bo
 // Replica calls and the lazy state on plans with tensors.
 hipError_t launch_seg_apply_replicas(const a2sgd_plan_t &pl, const PtrTable &tab, const ReplicaTable &wt, bool has_e,
                                      float eta, void *ws, hipStream_t s);
+// the whole reduction on the lazy state: first level, fold, second level (means and statistics per tensor)
 hipError_t launch_seg_lazy_partials(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s);
+// retained-error mode: w from the sign words that launch_seg_lazy_partials left (tab.g = tab.e = the state buffers)
+hipError_t launch_seg_lazy_apply_signs(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eta, void *ws,
+                                       hipStream_t s);
 hipError_t launch_seg_lazy_reset(const a2sgd_plan_t &pl, void *ws, hipStream_t s);
 hipError_t launch_seg_materialize(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s);
 hipError_t launch_export_mask(const a2sgd_plan_t &pl, const PtrTable &tab, bool has_e, uint64_t *mask, hipStream_t s);

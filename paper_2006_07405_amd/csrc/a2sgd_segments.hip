@@ -55,20 +55,19 @@ __global__ void k_seg_mark(WsHeader *__restrict__ hdr, const uint64_t tag)
 // last one are taken one per thread, the float4 groups in between kSegUnroll per thread per trip.
 // ---------------------------------------------------------------------------------------------------------
 constexpr int kSegUnroll = 4;
+// Dynamic LDS request of the lazy state's reduction: 6 workgroups per CU, as in the whole-model form (measured at
+// configs 5 / 4 / 2, lazy step in ms: 8 per CU 13.75 / 4.58 / 0.447, 6 per CU 13.47 / 4.46 / 0.457, 5 per CU 13.63 /
+// 4.52 / 0.492, 4 per CU 14.77 / 5.02 / 0.573).
+constexpr uint32_t kSegLazyLds = 25 * 1024;
 
-// LAZY: the reduction on the lazy error state.  tab.e holds the state buffers, which keep the folded vector of the
-// last step; an element's error is its pending error with the carried means of its tensor (the tables the last
-// step's global pass filled), v = fl32(g + that error) is written back in place of the stored value and enters the
-// sums and counts.
-template <bool HAS_E, bool NT, bool LAZY>
+template <bool HAS_E, bool NT>
 __global__ __launch_bounds__(kBlock) void k_seg_partials(const PtrTable tab, const SegView sv)
 {
-    static_assert(HAS_E || !LAZY, "the lazy state is the e table");
-    const uint32_t p = blockIdx.y, P = gridDim.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t p = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *__restrict__ g = tab.g[p];
-    float *e = HAS_E ? tab.e[p] : nullptr;
+    const float *__restrict__ e = HAS_E ? tab.e[p] : nullptr;
     const vf4 *g4 = reinterpret_cast<const vf4 *>(g);
-    vf4 *e4 = reinterpret_cast<vf4 *>(e);
+    const vf4 *e4 = reinterpret_cast<const vf4 *>(e);
     __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
     __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
 
@@ -83,18 +82,8 @@ __global__ __launch_bounds__(kBlock) void k_seg_partials(const PtrTable tab, con
         if (a > hi)
             a = hi;
         const uint64_t z = a + ((hi - a) & ~static_cast<uint64_t>(3));  // end of the float4 groups
-        float nmp = 0.0f, mn = 0.0f;  // the carried means of this item's tensor
-        if (LAZY) {
-            nmp = sv.neg_mu_pos[static_cast<size_t>(item.seg) * P + p];
-            mn = sv.mu_neg[static_cast<size_t>(item.seg) * P + p];
-        }
         auto scalar = [&](const uint64_t i) {  // one element outside the float4 groups
-            float v = g[i];
-            if (HAS_E)
-                v += LAZY ? pending_error(e[i], nmp, mn) : e[i];
-            if (LAZY)
-                e[i] = v;
-            return v;
+            return HAS_E ? g[i] + e[i] : g[i];
         };
         LaneAcc acc;
         if (tid < a - lo) {  // head, at most 3 elements
@@ -114,10 +103,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_partials(const PtrTable tab, con
 #pragma unroll
             for (int u = 0; u < kSegUnroll; ++u)
                 if (i0 + u * kBlock < v_hi) {
-                    const vf4 v = !HAS_E ? gv[u] : LAZY ? gv[u] + pending_error4(ev[u], nmp, mn) : gv[u] + ev[u];
-                    if (LAZY)
-                        st4<NT>(e4 + i0 + u * kBlock, v);
-                    acc.add4(v);
+                    acc.add4(HAS_E ? gv[u] + ev[u] : gv[u]);
                 }
             acc.flush();
         }
@@ -530,7 +516,8 @@ __global__ __launch_bounds__(64) void k_seg_error_signs(const PtrTable tab, cons
     sign_row(sign, P, blockIdx.x / 2, blockIdx.x % 2, p)[lane] = static_cast<uint16_t>(bits);
 }
 
-template <bool NT, int UP>
+// LAZY: the sign words are those of the lazy state's reduction and tab.g = tab.e = the state buffers, which hold v.
+template <bool NT, int UP, bool LAZY>
 __global__ __launch_bounds__(64) void k_seg_apply_signs(const PtrTable tab, const uint16_t *__restrict__ sign,
                                                         float *__restrict__ w, const uint64_t n, const uint64_t chunks,
                                                         const uint32_t P, const float eta_over_P, const SegView sv)
@@ -634,12 +621,13 @@ __global__ __launch_bounds__(64) void k_seg_apply_signs(const PtrTable tab, cons
                     w[(i << 2) + c] = x[c] - eta_over_P * acc[c];
         }
     }
-    // the last n % 4 elements, which k_seg_error_signs left alone, get the whole of lines 4, 6 and 7 here
+    // the last n % 4 elements, which k_seg_error_signs left alone, get the whole of lines 4, 6 and 7 here (on the
+    // lazy state: lines 6 and 7 from the stored v, which has no sign bit in the words)
     if (blockIdx.x == gridDim.x - 1 && lane < (n & 3)) {
         const uint64_t idx = (nvec << 2) + lane;
         const uint32_t s = seg_of(sv, sv.coarse[idx >> kSegCoarseShift] & ~kSegInsideBit, idx);
         if (sv.seg_start[s] <= idx)
-            seg_apply_element<A2SGD_MODE_RETAINED_ERROR, true>(tab, w, idx, s, P, eta_over_P, sv);
+            seg_apply_element<A2SGD_MODE_RETAINED_ERROR, !LAZY>(tab, w, idx, s, P, eta_over_P, sv);
     }
 }
 
@@ -764,6 +752,233 @@ __global__ __launch_bounds__(64) void k_seg_materialize(const PtrTable tab, cons
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Lazy error state on a plan with tensors: the reduction (Algorithm 1 line 3 per tensor on v = fl32(g + the pending
+// error of the stored value, formed with the carried means of the element's tensor); v is written back in place of
+// the stored value).  Because it stores, it has the one-shot shape of the whole-model form: grid = (blocks of
+// kSegLazyElems elements by position, P), single wavefronts, all loads ahead of the first store.  A block that lies
+// wholly inside one tensor takes that tensor's carried means for all its elements and leaves one record in the
+// table of block records.  Any other block walks the tensors it touches: per tensor the elements inside it are
+// folded, summed and counted (the others enter as NaN, which is counted nowhere), and the record goes straight into
+// that tensor's first or last slot of the folded table.  Padding is neither written nor given a sign bit.
+// With SIGNS the pass leaves pos(v) in the sign words, in the layout of k_seg_error_signs (both halves of a row).
+// ---------------------------------------------------------------------------------------------------------
+template <bool NT, bool SIGNS>
+__global__ __launch_bounds__(64) void k_seg_lazy_partials(const PtrTable tab, const uint64_t n, const uint64_t chunks,
+                                                          const SegView lv, const uint32_t blocks, const Partials rec,
+                                                          const uint32_t sign_rows, uint16_t *__restrict__ sign)
+{
+    static_assert(4 * kSegLazyItems == 32, "one thread's sign bits fill two 16-bit halves");
+    const uint32_t p = blockIdx.y, P = gridDim.y, b = blockIdx.x, lane = threadIdx.x;
+    const float *__restrict__ g = tab.g[p];
+    float *st = tab.e[p];
+    const vf4 *__restrict__ g4 = reinterpret_cast<const vf4 *>(g);
+    vf4 *s4 = reinterpret_cast<vf4 *>(st);
+    const uint64_t nvec = n >> 2;
+    constexpr uint64_t kPer = 64ull * kSegLazyItems;
+    const uint64_t base = static_cast<uint64_t>(b) * kPer + lane;
+    const bool full = (static_cast<uint64_t>(b) + 1) * kPer <= nvec;  // all float4 groups of the block exist
+    vf4 gv[kSegLazyItems], sx[kSegLazyItems];
+    if (full) {
+#pragma unroll
+        for (int u = 0; u < kSegLazyItems; ++u)
+            gv[u] = ld4<NT>(g4 + base + u * 64);
+#pragma unroll
+        for (int u = 0; u < kSegLazyItems; ++u)
+            sx[u] = ld4<NT>(s4 + base + u * 64);
+    } else {
+#pragma unroll
+        for (int u = 0; u < kSegLazyItems; ++u) {
+            const bool there = base + u * 64 < nvec;
+            gv[u] = there ? ld4<NT>(g4 + base + u * 64) : vf4{0.0f, 0.0f, 0.0f, 0.0f};
+            sx[u] = there ? ld4<NT>(s4 + base + u * 64) : vf4{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    static_assert(64 * 4 == (1 << kSegCoarseShift), "one lookup entry per 64 float4 groups");
+    uint32_t entry[kSegLazyItems];
+#pragma unroll
+    for (int u = 0; u < kSegLazyItems; ++u) {
+        const uint64_t c = static_cast<uint64_t>(b) * kSegLazyItems + u;
+        entry[u] = c < chunks ? lv.coarse[c] : 0u;
+    }
+    if (!seg_tables_ok(lv))
+        return;
+    bool whole = full && (entry[0] & kSegInsideBit) != 0;  // the same for every thread of the block
+#pragma unroll
+    for (int u = 1; u < kSegLazyItems; ++u)
+        whole = whole && entry[u] == entry[0];
+
+    if (whole) {
+        const uint32_t t = entry[0] & ~kSegInsideBit;
+        const float nmp = lv.neg_mu_pos[static_cast<size_t>(t) * P + p], mn = lv.mu_neg[static_cast<size_t>(t) * P + p];
+        LaneAcc acc;
+        uint32_t bits = 0;
+#pragma unroll
+        for (int u = 0; u < kSegLazyItems; ++u) {
+            const vf4 v = gv[u] + pending_error4(sx[u], nmp, mn);
+            st4<NT>(s4 + base + u * 64, v);
+            acc.add4(v);
+            if (SIGNS)
+                bits = push_signs(bits, v);
+        }
+        if (SIGNS) {
+            sign_row(sign, P, b, 0, p)[lane] = static_cast<uint16_t>(bits >> 16);
+            sign_row(sign, P, b, 1, p)[lane] = static_cast<uint16_t>(bits & 0xffffu);
+        }
+        acc.flush();
+        const double wp = wave_sum(acc.s_pos), wn = wave_sum(acc.s_neg);
+        if (lane == 0) {
+            const size_t slot = static_cast<size_t>(p) * blocks + b;
+            rec.s_pos[slot] = wp;
+            rec.s_neg[slot] = wn;
+            rec.n_pos[slot] = acc.c_pos;
+            rec.n_neg[slot] = acc.c_neg;
+            rec.n_zero[slot] = acc.c_zero;
+        }
+        return;
+    }
+
+    // A block with a tensor boundary, padding or the end of the buffers in it.
+    const uint64_t blo = static_cast<uint64_t>(b) * kSegLazyElems, bhi = blo + kSegLazyElems;
+    // the last n % 4 elements, outside every float4 group, belong to the block at their position: one per lane
+    const uint64_t tail_idx = (nvec << 2) + lane;
+    const bool tail_block = (n & 3) != 0 && (nvec << 2) >= blo && (nvec << 2) < bhi;  // uniform
+    const bool tail_lane = tail_block && lane < (n & 3);
+    const float tail_g = tail_lane ? g[tail_idx] : 0.0f, tail_s = tail_lane ? st[tail_idx] : 0.0f;
+    float tail_v = 0.0f;
+    bool tail_in = false;
+    float out[kSegLazyItems][4];
+    uint32_t inside = 0;  // bit 4 * u + c: the element belongs to a tensor and out[u][c] holds its v
+#pragma unroll
+    for (int u = 0; u < kSegLazyItems; ++u)
+        out[u][0] = out[u][1] = out[u][2] = out[u][3] = 0.0f;
+    const float nan = __builtin_nanf("");
+    for (uint32_t t = entry[0] & ~kSegInsideBit; t < lv.S; ++t) {  // entry[0]: the first tensor that ends after blo
+        const uint64_t ts = lv.seg_start[t], te = lv.seg_end[t];
+        if (ts >= bhi)
+            break;
+        const float nmp = lv.neg_mu_pos[static_cast<size_t>(t) * P + p], mn = lv.mu_neg[static_cast<size_t>(t) * P + p];
+        LaneAcc acc;
+#pragma unroll
+        for (int u = 0; u < kSegLazyItems; ++u) {
+            const uint64_t clo = blo + u * 256ull;
+            if (ts >= clo + 256 || te <= clo)  // this chunk has nothing of tensor t (uniform)
+                continue;
+            const uint64_t e0 = (base + u * 64) << 2;
+            const bool there = base + u * 64 < nvec;
+            const float x[4] = {gv[u].x, gv[u].y, gv[u].z, gv[u].w}, y[4] = {sx[u].x, sx[u].y, sx[u].z, sx[u].w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bool in = there && e0 + c >= ts && e0 + c < te;
+                const float v = in ? x[c] + pending_error(y[c], nmp, mn) : nan;
+                acc.add(v);
+                out[u][c] = in ? v : out[u][c];
+                inside |= in ? 1u << (4 * u + c) : 0u;
+            }
+        }
+        if (tail_block) {
+            const bool in = tail_lane && tail_idx >= ts && tail_idx < te;
+            const float v = in ? tail_g + pending_error(tail_s, nmp, mn) : nan;
+            acc.add(v);
+            tail_v = in ? v : tail_v;
+            tail_in = tail_in || in;
+        }
+        acc.flush();
+        const double wp = wave_sum(acc.s_pos), wn = wave_sum(acc.s_neg);
+        if (lane == 0) {
+            // the block holds the tensor's first element (its first slot) or, failing that, its last one
+            const uint32_t k = ts >= blo ? lv.item_lo[t] : lv.item_lo[t + 1] - 1;
+            const size_t slot = static_cast<size_t>(p) * lv.num_items + k;
+            lv.r_spos[slot] = wp;
+            lv.r_sneg[slot] = wn;
+            lv.r_npos[slot] = acc.c_pos;
+            lv.r_nneg[slot] = acc.c_neg;
+            lv.r_nzero[slot] = acc.c_zero;
+        }
+    }
+    uint32_t bits = 0;
+#pragma unroll
+    for (int u = 0; u < kSegLazyItems; ++u) {
+        const uint32_t m = (inside >> (4 * u)) & 15u;
+        const uint64_t i = base + u * 64;
+        if (m == 15u) {
+            const vf4 v = vf4{out[u][0], out[u][1], out[u][2], out[u][3]};
+            st4<NT>(s4 + i, v);
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (m >> c & 1u)
+                    st[(i << 2) + c] = out[u][c];
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            bits = bits * 2u + ((m >> c & 1u) != 0 && out[u][c] >= 0.0f ? 1u : 0u);
+    }
+    if (tail_in)
+        st[tail_idx] = tail_v;
+    if (SIGNS && b < sign_rows) {
+        sign_row(sign, P, b, 0, p)[lane] = static_cast<uint16_t>(bits >> 16);
+        sign_row(sign, P, b, 1, p)[lane] = static_cast<uint16_t>(bits & 0xffffu);
+    }
+}
+
+// Between that pass and the second level: workgroup (j, p) adds the block records [lo, hi) of fold entry j in a
+// fixed order (strided per thread, shuffle tree, wavefronts in index order) into its slot of the folded table; an
+// empty range clears the slot.
+__global__ __launch_bounds__(kBlock) void k_seg_lazy_fold(const SegFold *__restrict__ fold, const uint32_t blocks,
+                                                          const Partials in, const SegView lv)
+{
+    const uint32_t p = blockIdx.y, tid = threadIdx.x;
+    if (!seg_tables_ok(lv))
+        return;
+    const SegFold f = fold[blockIdx.x];
+    const size_t row = static_cast<size_t>(p) * blocks;
+    double sp = 0.0, sn = 0.0;
+    uint64_t cp = 0, cn = 0, cz = 0;
+    for (uint32_t k = f.lo + tid; k < f.hi; k += kBlock) {
+        sp += in.s_pos[row + k];
+        sn += in.s_neg[row + k];
+        cp += in.n_pos[row + k];
+        cn += in.n_neg[row + k];
+        cz += in.n_zero[row + k];
+    }
+    __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
+    __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
+    sp = wave_sum(sp);
+    sn = wave_sum(sn);
+    cp = wave_sum(cp);
+    cn = wave_sum(cn);
+    cz = wave_sum(cz);
+    const uint32_t lane = tid & 63, wave = tid >> 6;
+    if (lane == 0) {
+        sh_pos[wave] = sp;
+        sh_neg[wave] = sn;
+        sh_cp[wave] = cp;
+        sh_cn[wave] = cn;
+        sh_cz[wave] = cz;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double tp = 0.0, tn = 0.0;
+        uint64_t np = 0, nn = 0, nz = 0;
+#pragma unroll
+        for (int k = 0; k < kBlock / 64; ++k) {
+            tp += sh_pos[k];
+            tn += sh_neg[k];
+            np += sh_cp[k];
+            nn += sh_cn[k];
+            nz += sh_cz[k];
+        }
+        const size_t slot = static_cast<size_t>(p) * lv.num_items + f.slot;
+        lv.r_spos[slot] = tp;
+        lv.r_sneg[slot] = tn;
+        lv.r_npos[slot] = np;
+        lv.r_nneg[slot] = nn;
+        lv.r_nzero[slot] = nz;
+    }
+}
+
 // Clears the carried means of every tensor and worker: from here on the state buffers are read as true errors.
 __global__ __launch_bounds__(256) void k_seg_lazy_reset(const uint64_t entries, const SegView sv)
 {
@@ -784,26 +999,98 @@ hipError_t launch_seg_partials(const a2sgd_plan_t &pl, const PtrTable &tab, bool
     const dim3 grid(pl.seg.blocks, pl.P), block(kBlock);
     if (has_e) {
         if (pl.streaming)
-            k_seg_partials<true, true, false><<<grid, block, 0, s>>>(tab, sv);
+            k_seg_partials<true, true><<<grid, block, 0, s>>>(tab, sv);
         else
-            k_seg_partials<true, false, false><<<grid, block, 0, s>>>(tab, sv);
+            k_seg_partials<true, false><<<grid, block, 0, s>>>(tab, sv);
     } else {
         if (pl.streaming)
-            k_seg_partials<false, true, false><<<grid, block, 0, s>>>(tab, sv);
+            k_seg_partials<false, true><<<grid, block, 0, s>>>(tab, sv);
         else
-            k_seg_partials<false, false, false><<<grid, block, 0, s>>>(tab, sv);
+            k_seg_partials<false, false><<<grid, block, 0, s>>>(tab, sv);
     }
     return hipGetLastError();
 }
 
+// The tables as the lazy state's second level sees them: a tensor's records are its slots of the folded table.
+static SegView seg_lazy_view(const a2sgd_plan_t &pl, void *ws)
+{
+    char *b = static_cast<char *>(ws);
+    const SegPlan &sp = pl.seg;
+    SegView v = seg_view(pl, ws);
+    v.num_items = sp.lz_slot_lo[sp.S];
+    v.item = nullptr;  // the lazy passes go by position, not by item
+    v.item_lo = reinterpret_cast<const uint32_t *>(b + sp.off_lz_slot_lo);
+    const size_t stride = 8ull * pl.P * v.num_items;
+    v.r_spos = reinterpret_cast<double *>(b + sp.off_lz_folded);
+    v.r_sneg = reinterpret_cast<double *>(b + sp.off_lz_folded + stride);
+    v.r_npos = reinterpret_cast<uint64_t *>(b + sp.off_lz_folded + 2 * stride);
+    v.r_nneg = reinterpret_cast<uint64_t *>(b + sp.off_lz_folded + 3 * stride);
+    v.r_nzero = reinterpret_cast<uint64_t *>(b + sp.off_lz_folded + 4 * stride);
+    return v;
+}
+
 hipError_t launch_seg_lazy_partials(const a2sgd_plan_t &pl, const PtrTable &tab, void *ws, hipStream_t s)
 {
-    const SegView sv = seg_view(pl, ws);
-    const dim3 grid(pl.seg.blocks, pl.P), block(kBlock);
-    if (pl.streaming)
-        k_seg_partials<true, true, true><<<grid, block, 0, s>>>(tab, sv);
+    const SegPlan &sp = pl.seg;
+    const SegView lv = seg_lazy_view(pl, ws);
+    const Partials rec = partials_at(ws, sp.off_lz_records, pl.P, sp.lz_blocks);
+    const SegFold *fold = reinterpret_cast<const SegFold *>(static_cast<char *>(ws) + sp.off_lz_fold);
+    uint16_t *sign = reinterpret_cast<uint16_t *>(static_cast<char *>(ws) + sp.off_sign);
+    const uint64_t chunks = (pl.n + (1ull << kSegCoarseShift) - 1) >> kSegCoarseShift;
+    const bool signs = pl.mode == A2SGD_MODE_RETAINED_ERROR;  // the literal mode's apply pass needs v itself
+    const dim3 grid(sp.lz_blocks, pl.P), block(64);
+    const uint32_t lds = kSegLazyLds;
+    if (pl.streaming) {
+        if (signs)
+            k_seg_lazy_partials<true, true><<<grid, block, lds, s>>>(tab, pl.n, chunks, lv, sp.lz_blocks, rec, pl.lazy_blocks, sign);
+        else
+            k_seg_lazy_partials<true, false><<<grid, block, lds, s>>>(tab, pl.n, chunks, lv, sp.lz_blocks, rec, pl.lazy_blocks, sign);
+    } else {
+        if (signs)
+            k_seg_lazy_partials<false, true><<<grid, block, 0, s>>>(tab, pl.n, chunks, lv, sp.lz_blocks, rec, pl.lazy_blocks, sign);
+        else
+            k_seg_lazy_partials<false, false><<<grid, block, 0, s>>>(tab, pl.n, chunks, lv, sp.lz_blocks, rec, pl.lazy_blocks, sign);
+    }
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess)
+        return err;
+    if (!sp.lz_fold.empty()) {  // empty if no tensor has a block to itself and every first and last slot is in use
+        k_seg_lazy_fold<<<dim3(static_cast<uint32_t>(sp.lz_fold.size()), pl.P), dim3(kBlock), 0, s>>>(fold, sp.lz_blocks, rec, lv);
+        if ((err = hipGetLastError()) != hipSuccess)
+            return err;
+    }
+    if (sp.pooled)
+        k_seg_finalize_pooled<<<dim3(pl.P), dim3(kBlock), 0, s>>>(lv, sp.covered);
     else
-        k_seg_partials<true, false, true><<<grid, block, 0, s>>>(tab, sv);
+        k_seg_finalize<<<dim3(lv.S, pl.P), dim3(64), 0, s>>>(lv);
+    return hipGetLastError();
+}
+
+hipError_t launch_seg_lazy_apply_signs(const a2sgd_plan_t &pl, const PtrTable &tab, float *w, float eta, void *ws,
+                                       hipStream_t s)
+{
+    const float eop = static_cast<float>(static_cast<double>(eta) / static_cast<double>(pl.P));
+    const SegView sv = seg_view(pl, ws);
+    const uint16_t *sign = reinterpret_cast<const uint16_t *>(static_cast<char *>(ws) + pl.seg.off_sign);
+    const uint64_t chunks = (pl.n + (1ull << kSegCoarseShift) - 1) >> kSegCoarseShift;
+    const dim3 grid(pl.lazy_blocks * 2), block(64);  // workgroups of 1024 elements: two per row of sign words
+    const uint32_t lds = pl.streaming ? 8 * 1024 : 0;
+#define A2SGD_SEG_LAZY_SIGNS(NT, UP) \
+    k_seg_apply_signs<NT, UP, true><<<grid, block, lds, s>>>(tab, sign, w, pl.n, chunks, pl.P, eop, sv)
+    if (pl.streaming) {
+        if (pl.P >= 16)
+            A2SGD_SEG_LAZY_SIGNS(true, 16);
+        else if (pl.P >= 8)
+            A2SGD_SEG_LAZY_SIGNS(true, 8);
+        else
+            A2SGD_SEG_LAZY_SIGNS(true, 4);
+    } else {
+        if (pl.P >= 8)
+            A2SGD_SEG_LAZY_SIGNS(false, 8);
+        else
+            A2SGD_SEG_LAZY_SIGNS(false, 4);
+    }
+#undef A2SGD_SEG_LAZY_SIGNS
     return hipGetLastError();
 }
 
@@ -866,9 +1153,9 @@ static hipError_t launch_seg_apply_two_kernels(const a2sgd_plan_t &pl, const Ptr
     if (err != hipSuccess)
         return err;
     if (pl.P >= 16)
-        k_seg_apply_signs<true, 16><<<dim3(halves), dim3(64), 8 * 1024, s>>>(tab, sign, w, pl.n, chunks, pl.P, eop, sv);
+        k_seg_apply_signs<true, 16, false><<<dim3(halves), dim3(64), 8 * 1024, s>>>(tab, sign, w, pl.n, chunks, pl.P, eop, sv);
     else
-        k_seg_apply_signs<true, 8><<<dim3(halves), dim3(64), 8 * 1024, s>>>(tab, sign, w, pl.n, chunks, pl.P, eop, sv);
+        k_seg_apply_signs<true, 8, false><<<dim3(halves), dim3(64), 8 * 1024, s>>>(tab, sign, w, pl.n, chunks, pl.P, eop, sv);
     return hipGetLastError();
 }
 

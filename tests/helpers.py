@@ -103,3 +103,19 @@ def check_against_oracle(A, g, e, w, eta, mode=0, **kw):
         for p in range(len(g)):
             assert np.array_equal(mask[p], ref.mask[p]), f"mask[{p}] differs from pos(v)"
     return (stats, gmu, e_new, w_new, mask), ref
+
+
+def stored_sign_bits(A, plan, ws, n, P):
+    """Decodes the sign words that a2sgd_lazy_local_averages leaves at the end of the workspace in retained-error
+    mode: uint16 sign[b][h][p][tid], block b covering 2048 elements, thread tid owning the float4 groups
+    b*512 + (4h + u)*64 + tid, u = 0..3, whose component c is bit 15 - (4u + c).  Returns bits[P][blocks*2048] in
+    element order."""
+    nvec = n >> 2
+    blocks = max(1, -(-nvec // 512))
+    off = A.a2sgd_workspace_bytes(plan) - 256 * P * blocks
+    words = ws.view(torch.uint8)[off:off + 256 * P * blocks].cpu().numpy().view(np.uint16).reshape(blocks, 2, P, 64)
+    bits = np.zeros((P, blocks, 2, 4, 64, 4), np.uint8)  # [p][b][h][u][tid][c]: element b*2048 + h*1024 + u*256 + tid*4 + c
+    for u in range(4):
+        for c in range(4):
+            bits[:, :, :, u, :, c] = ((words >> (15 - (4 * u + c))) & 1).transpose(2, 0, 1, 3)
+    return bits.reshape(P, blocks * 2048)

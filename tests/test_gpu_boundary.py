@@ -10,7 +10,7 @@ import torch
 
 import workloads
 from oracle import a2sgd_oracle as O
-from tests.helpers import assert_array_close, compare_stats, dev
+from tests.helpers import stored_sign_bits, assert_array_close, compare_stats, dev
 from tests.test_gpu_parity import make_case
 
 pytestmark = pytest.mark.gpu
@@ -134,22 +134,6 @@ def test_tensor_plan_on_a_workspace_that_was_not_initialised(A):
     with pytest.raises(A.A2sgdError) as ei:
         A.a2sgd_step(plan, gd, ed, wd, 0.1, ws[:16])
     assert ei.value.status == A.A2SGD_ERR_WORKSPACE_TOO_SMALL
-
-
-def stored_sign_bits(A, plan, ws, n, P):
-    """Decodes the sign words that a2sgd_lazy_local_averages leaves at the end of the workspace in retained-error
-    mode: uint16 sign[b][h][p][tid], block b covering 2048 elements, thread tid owning the float4 groups
-    b*512 + (4h + u)*64 + tid, u = 0..3, whose component c is bit 15 - (4u + c).  Returns bits[P][blocks*2048] in
-    element order."""
-    nvec = n >> 2
-    blocks = max(1, -(-nvec // 512))
-    off = A.a2sgd_workspace_bytes(plan) - 256 * P * blocks
-    words = ws.view(torch.uint8)[off:off + 256 * P * blocks].cpu().numpy().view(np.uint16).reshape(blocks, 2, P, 64)
-    bits = np.zeros((P, blocks, 2, 4, 64, 4), np.uint8)  # [p][b][h][u][tid][c]: element b*2048 + h*1024 + u*256 + tid*4 + c
-    for u in range(4):
-        for c in range(4):
-            bits[:, :, :, u, :, c] = ((words >> (15 - (4 * u + c))) & 1).transpose(2, 0, 1, 3)
-    return bits.reshape(P, blocks * 2048)
 
 
 SIGN_SIZES = [1, 2, 3, 4, 5, 7, 8, 255, 256, 257, 1023, 2044, 2047, 2048, 2049, 2051, 2052, 4095, 4096, 4097, 4099,

@@ -6,7 +6,7 @@ import torch
 
 import workloads
 from oracle import a2sgd_oracle as O
-from tests.helpers import assert_array_close, close, compare_stats, dev
+from tests.helpers import assert_array_close, close, compare_stats, dev, stored_sign_bits
 
 pytestmark = pytest.mark.gpu
 f32 = np.float32
@@ -404,7 +404,18 @@ def run_lazy_case(A, seed, n, P, mode, lengths, offsets=None, pooled=False, step
         assert_array_close(wd.cpu().numpy()[o:o + l], w_o[o:o + l], f"eager step after materialise, w tensor at {o}")
 
 
-@pytest.mark.parametrize("seg", LAYOUTS, ids=[f"layout{i}" for i in range(len(LAYOUTS))])
+# The lazy state's reduction goes by blocks of 2048 elements: tensors that start and end on block boundaries, a tensor
+# inside one block next to such tensors, and a tensor with more whole blocks than one fold of the block records takes.
+LAZY_LAYOUTS = LAYOUTS + [
+    [2048, 4096, 100, 1948, 3 * 2048 + 1],
+    [2048] * 5,
+    [2047, 2049, 2048, 1, 4095],
+    [2048 * 1100 + 5, 3],
+    [7, 2048 * 2050 + 2041, 2048, 9],
+]
+
+
+@pytest.mark.parametrize("seg", LAZY_LAYOUTS, ids=[f"layout{i}" for i in range(len(LAZY_LAYOUTS))])
 def test_lazy_state_on_tensor_plans(A, seg):
     n = sum(seg)
     for P, mode in ((1, 0), (3, 1), (4, 0), (9, 0)):
@@ -425,6 +436,98 @@ def test_lazy_state_on_a_tensor_plan_streaming(A):
     assert (2 * 7 + 1) * 4 * sum(seg) > 192 << 20
     run_lazy_case(A, 78, sum(seg), 7, 0, seg, steps=2)
     run_lazy_case(A, 79, sum(seg), 7, 1, seg, steps=2)
+
+
+def test_lazy_state_on_a_tensor_plan_with_nans(A):
+    """Retained-error mode on the lazy state of a plan with tensors when some gradients are NaN: a NaN has no sign bit
+    in the stored words; its element of the state and of w becomes NaN, its tensor counts it, nothing else changes."""
+    seg = [1_000_003, 5, 777_777, 64, 1_300_001, 131_072, 2, 291_079]
+    n, P = sum(seg), 7
+    assert (2 * P + 1) * 4 * n > 192 << 20
+    g, e, w = make_case(n, n, P, scales_for(seg, 6))
+    rng = np.random.default_rng(9)
+    for p in (0, 3, P - 1):
+        g[p][rng.integers(0, n, 6)] = np.nan
+    g[2][n - 1] = np.nan   # the scalar tail
+    g[5][1_000_003] = np.nan  # a tensor of five elements
+    plan = A.a2sgd_plan(n, P, 0, 0, seg_lengths=seg)
+    ws = A.alloc_workspace(plan)
+    gd, s, wd = [dev(x) for x in g], [dev(x) for x in e], dev(w)
+    e_o, w_o = e, w
+    A.a2sgd_lazy_reset(plan, ws)
+    for t in range(2):
+        A.a2sgd_lazy_step(plan, gd, s, wd, 0.1, ws)
+        stats, gmu = A.a2sgd_read_segment_stats(plan, ws)
+        res, e_o, w_o = O.step_segmented(g, e_o, w_o, 0.1, 0, seg)
+        assert sum(r.workers[p].n_nan for r in res for p in range(P)) > 0
+        off = 0
+        for k, length in enumerate(seg):
+            for p in range(P):
+                a, b = stats[p][k], res[k].workers[p]
+                assert (a.n_pos, a.n_neg, a.n_zero, a.n_nan) == (b.n_pos, b.n_neg, b.n_zero, b.n_nan), f"step {t} tensor {k} worker {p}"
+            assert_array_close(wd[off:off + length].cpu().numpy(), w_o[off:off + length], f"step {t} w tensor {k}")
+            off += length
+    A.a2sgd_lazy_materialize(plan, s, ws)
+    off = 0
+    for k, length in enumerate(seg):
+        for p in range(P):
+            assert_array_close(s[p][off:off + length].cpu().numpy(), e_o[p][off:off + length], f"materialised e[{p}] tensor {k}")
+        off += length
+
+
+SIGN_CASES = [  # (n, lengths, offsets or None)
+    (sum(LAZY_LAYOUTS[9]), LAZY_LAYOUTS[9], None),
+    (sum(LAZY_LAYOUTS[11]), LAZY_LAYOUTS[11], None),
+    (sum(LAYOUTS[7]), LAYOUTS[7], None),
+    (sum(LAYOUTS[2]), LAYOUTS[2], None),
+    PADDED[3], PADDED[4], PADDED[6],
+    (8195, [2048, 2046], [2048, 6149]),
+]
+
+
+@pytest.mark.parametrize("case", SIGN_CASES, ids=[f"signs{i}" for i in range(len(SIGN_CASES))])
+def test_stored_sign_words_on_tensor_plans(A, case):
+    """pos(v) of Eq. 2 as the lazy state of a plan with tensors stores it: every bit of the sign words after each of
+    two lazy reductions against the per-tensor oracle's masks; padding, float4 groups past the end and the last n % 4
+    elements have no bit."""
+    n, lengths, offsets = case
+    P = 3
+    rng = np.random.default_rng(n)
+    offs = offsets if offsets is not None else list(np.concatenate([[0], np.cumsum(lengths)[:-1]]))
+    member = np.zeros(n, bool)
+    for o, l in zip(offs, lengths):
+        member[o:o + l] = True
+    e_o = [(rng.standard_normal(n) * 0.5).astype(f32) for _ in range(P)]
+    w_o = (rng.standard_normal(n) * 0.02).astype(f32)
+    for x in e_o + [w_o]:
+        x[~member] = np.nan
+    plan = A.a2sgd_plan(n, P, 0, 0, seg_lengths=lengths, seg_offsets=offsets)
+    ws = A.alloc_workspace(plan)
+    ws.fill_(-1)  # stale ones everywhere: whatever is 0 afterwards was written
+    A.a2sgd_workspace_init(plan, ws)
+    s, wd = [dev(x) for x in e_o], dev(w_o)
+    A.a2sgd_lazy_reset(plan, ws)
+    covered = (n >> 2) << 2
+    for t in range(2):
+        g = [rng.standard_normal(n).astype(f32) for _ in range(P)]
+        for x in g:
+            x[~member] = np.nan
+        gd = [dev(x) for x in g]
+        res, e_o, w_o = O.step_segmented(g, e_o, w_o, 0.1, 0, lengths, offsets)
+        A.a2sgd_lazy_local_averages(plan, gd, s, ws)
+        torch.cuda.synchronize()
+        bits = stored_sign_bits(A, plan, ws, n, P)
+        for p in range(P):
+            want = np.zeros(max(n, bits.shape[1]), np.uint8)
+            for k, (o, l) in enumerate(zip(offs, lengths)):
+                want[o:o + l] = res[k].mask[p]
+            want[covered:] = 0
+            assert np.array_equal(bits[p], want[:bits.shape[1]]), f"step {t} worker {p}: stored signs differ"
+        A.a2sgd_global_average(plan, ws)
+        A.a2sgd_lazy_apply(plan, s, wd, 0.1, ws)
+        w_got = wd.cpu().numpy()
+        for o, l in zip(offs, lengths):
+            assert_array_close(w_got[o:o + l], w_o[o:o + l], f"step {t} w tensor at {o}")
 
 
 def test_config2_full_size_replicas_and_lazy_state_per_tensor(A):
