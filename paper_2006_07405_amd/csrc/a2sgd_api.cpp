@@ -50,11 +50,17 @@ uint32_t apply_lds_bytes(uint32_t P)
         return 25 * 1024;  // 6 per CU
     return 16 * 1024;      // 10 per CU
 }
-// The dense step has items * (up + 1) loads per lane in flight (items = 2).
+// The dense step has items * (up + 1) loads per lane in flight (items = 2), about half of what the apply pass has,
+// and takes its workers in groups of at most 8 one after the other, so from 8 workers on it wants more workgroups
+// per CU than the apply pass (measured: config 4, 16 workers, 1.97 ms with 3 per CU, 1.82 with 6, 1.75 with 10,
+// 1.69 with 13, 1.71 with 16 and more; config 2, 8 workers, 0.169 ms with 4 per CU, 0.160 with 6, 0.161 with 8
+// to 11, 0.164 with 13 and more; config 5, 4 workers, best with 6).
 uint32_t dense_lds_bytes(uint32_t P)
 {
+    if (P >= 16)
+        return 12 * 1024;  // 13 per CU
     if (P >= 4)
-        return apply_lds_bytes(P);
+        return 25 * 1024;  // 6 per CU
     return P >= 2 ? 16 * 1024 : 12 * 1024;  // 10 and 13 per CU
 }
 // Above this many bytes of g + e + w the step cannot live in the 256 MiB last-level cache between its two

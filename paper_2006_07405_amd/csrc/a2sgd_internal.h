@@ -19,6 +19,7 @@ constexpr uint32_t kMaxBlocksPerWorker = 65536;
 constexpr int kFusedBlock = 512;       // threads per workgroup of the single-launch step
 constexpr uint32_t kBarrierSlots = 64;  // grid-barrier cells of the single-launch step: a live plan owns at most one
 constexpr int kLazyItems = 8;           // float4 groups per array per thread in the lazy state's reduction pass
+constexpr uint32_t kPerWorkerReplicas = 8;  // from this many workers on the replica apply pass takes one worker per workgroup
 constexpr uint32_t kFoldSpan = 4096;    // records that one workgroup of k_fold_partials adds up
 
 // Device workspace, in this order:

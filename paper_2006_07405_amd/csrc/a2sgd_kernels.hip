@@ -916,6 +916,81 @@ __global__ __launch_bounds__(BLOCK) void k_apply_replicas(const PtrTable tab, co
     }
 }
 
+// The same pass with one worker per workgroup: grid = (workgroups of 64 * ITEMS float4 groups, P).  Nothing is summed
+// over the workers here, so a workgroup needs only its own worker's three buffers (g^p, e^p, w^p), and the
+// workgroups that run at one time are on the same worker or two: with many workers the grouped form above loses to
+// address translation what this one does not (as the shared-weight apply pass does from 8 workers on).  Single
+// wavefronts launched once, ITEMS groups of each buffer per thread, all loads ahead of the first store.
+template <int MODE, bool HAS_E, bool NT, int ITEMS>
+__global__ __launch_bounds__(64) void k_apply_replicas_per_worker(const PtrTable tab, const ReplicaTable wt,
+                                                                  const uint64_t n, const float eta,
+                                                                  const WsHeader *__restrict__ hdr)
+{
+    const uint32_t p = blockIdx.y, tid = threadIdx.x;
+    const uint32_t lz = opaque_zero();
+    const float nmp = hdr->neg_mu_pos[p + lz], mn = hdr->mu_neg[p + lz];
+    const float gmu_pos = (&hdr->gmu_pos)[lz];
+    const float neg_gmu_neg = -(&hdr->gmu_neg)[lz];
+    const vf4 *__restrict__ g4 = reinterpret_cast<const vf4 *>(tab.g[p]);
+    vf4 *e4 = HAS_E ? reinterpret_cast<vf4 *>(tab.e[p]) : nullptr;
+    vf4 *w4 = reinterpret_cast<vf4 *>(wt.w[p]);
+    const uint64_t nvec = n >> 2;
+    constexpr uint64_t kPer = 64ull * ITEMS;
+    const uint64_t base = static_cast<uint64_t>(blockIdx.x) * kPer + tid;
+    if ((static_cast<uint64_t>(blockIdx.x) + 1) * kPer <= nvec) {
+        vf4 v[ITEMS], ev[ITEMS], wv[ITEMS];
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u)
+            v[u] = ld4<NT>(g4 + base + u * 64);
+        if (HAS_E) {
+#pragma unroll
+            for (int u = 0; u < ITEMS; ++u)
+                ev[u] = ld4<NT>(e4 + base + u * 64);
+        }
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u)
+            wv[u] = ld4<NT>(w4 + base + u * 64);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u) {
+            const vf4 vv = HAS_E ? v[u] + ev[u] : v[u];
+            vf4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
+            const vf4 err = apply4<MODE>(vv, upd, nmp, mn, gmu_pos, neg_gmu_neg);
+            if (HAS_E)
+                st4<NT>(e4 + base + u * 64, err);
+            const vf4 wn = wv[u] - eta * upd;
+            st4<NT>(w4 + base + u * 64, wn);
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u) {
+            const uint64_t i = base + static_cast<uint64_t>(u) * 64;
+            if (i < nvec) {
+                vf4 vv = ld4<NT>(g4 + i);
+                if (HAS_E)
+                    vv += ld4<NT>(e4 + i);
+                const vf4 wv = ld4<NT>(w4 + i);
+                vf4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
+                const vf4 err = apply4<MODE>(vv, upd, nmp, mn, gmu_pos, neg_gmu_neg);
+                if (HAS_E)
+                    st4<NT>(e4 + i, err);
+                const vf4 wn = wv - eta * upd;
+                st4<NT>(w4 + i, wn);
+            }
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1 && tid < (n & 3)) {
+        const uint64_t k = (nvec << 2) + tid;
+        float v = tab.g[p][k];
+        if (HAS_E)
+            v += tab.e[p][k];
+        const float u = apply1<MODE>(v, nmp, mn, gmu_pos, neg_gmu_neg);
+        if (HAS_E)
+            tab.e[p][k] = v;
+        wt.w[p][k] -= eta * u;
+    }
+}
+
 // Algorithm 1 lines 9-10 on replicas: the dense average of the gradients, applied to every w^p.
 template <bool NT, int UP, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void k_dense_step_replicas(const PtrTable tab, const ReplicaTable wt,
@@ -1701,6 +1776,18 @@ static hipError_t launch_apply_replicas_shape(const a2sgd_plan_t &pl, const PtrT
 {
     constexpr int kThreads = 64;
     const uint64_t nvec = (pl.n + 3) >> 2;
+    if (NT && pl.P >= kPerWorkerReplicas) {
+        // one worker per workgroup, 2 float4 groups of g, e and w^p per thread, 8 workgroups per CU (measured, whole
+        // replica step in ms at configs 4 / 2: grouped form 10.42 / 0.914; this form with 2 groups per thread and 10, 8,
+        // 6, 4 workgroups per CU 9.64 / 0.890, 9.36 / 0.877, 9.53 / 0.905, 10.62 / 1.019; with 4 groups per thread
+        // 9.73 / 0.934, 9.52 / 0.915, 9.43 / 0.884, 9.74 / 0.926; at config 5, 4 workers, the grouped form wins,
+        // 25.5 against 26.3)
+        constexpr int kItems = 2;
+        const uint64_t per = 64ull * kItems;
+        const dim3 per_worker(static_cast<uint32_t>((nvec + per - 1) / per), pl.P);
+        k_apply_replicas_per_worker<MODE, HAS_E, NT, kItems><<<per_worker, dim3(64), 18 * 1024, s>>>(tab, wt, pl.n, eta, hdr);
+        return hipGetLastError();
+    }
     const dim3 grid(static_cast<uint32_t>((nvec + kThreads - 1) / kThreads)), block(kThreads);
     // 3 loads per worker instead of 2: groups of 4 workers at most, and then 6 workgroups per CU whatever P is
     // (the shared pass has groups of 8 for P >= 8 and caps residency lower)

@@ -398,6 +398,30 @@ def test_replicas(A, n, P):
             assert_array_close(wd[p].cpu().numpy(), ref[p], f"dense w[{p}]")
 
 
+@pytest.mark.parametrize("n,P,mode,with_e", [(3_100_003, 8, 0, True), (3_100_001, 8, 1, True), (800_002, 33, 1, False),
+                                              (400_003, 64, 0, True), (1_700_000, 15, 1, True)])
+def test_replicas_streaming_one_worker_per_workgroup(A, n, P, mode, with_e):
+    """From 8 workers on the streaming replica pass gives every workgroup one worker's g, e and w^p: against the
+    oracle at sizes with a ragged last workgroup and a scalar tail, both modes, with and without an error buffer."""
+    assert (2 * P + 1) * 4 * n > 192 << 20
+    g, e, w = make_case(n + P, n, P)
+    rng = np.random.default_rng(n + P)
+    wr = [(w + (rng.standard_normal(n) * 1e-3).astype(f32)) for _ in range(P)]
+    plan = A.a2sgd_plan(n, P, mode)
+    ws = A.alloc_workspace(plan)
+    gd, wd = [dev(x) for x in g], [dev(x) for x in wr]
+    ed = [dev(x) for x in e] if with_e else None
+    A.a2sgd_step_replicas(plan, gd, ed, wd, 0.1, ws)
+    stats, gmu = A.a2sgd_read_stats(plan, ws)
+    workers, gmu_ref, e_ref, w_ref = O.step_replicas(g, e if with_e else None, wr, 0.1, mode)
+    compare_stats(stats, gmu, O.StepResult(workers, gmu_ref[0], gmu_ref[1], [], np.empty(0, f32), []))
+    for p in range(P):
+        if with_e:
+            assert_array_close(ed[p].cpu().numpy(), e_ref[p], f"e[{p}]")
+        assert_array_close(wd[p].cpu().numpy(), w_ref[p], f"w[{p}]")
+        assert np.array_equal(gd[p].cpu().numpy().view(np.uint32), g[p].view(np.uint32)), "g is read-only"
+
+
 def test_replicas_full_size_config2(A):
     """Config 2 shape (25.6 M parameters, 8 workers) on device-generated inputs: the replica mean against the
     shared path, elementwise, and identical errors."""

@@ -436,6 +436,11 @@ def test_lazy_state_on_a_tensor_plan_streaming(A):
     assert (2 * 7 + 1) * 4 * sum(seg) > 192 << 20
     run_lazy_case(A, 78, sum(seg), 7, 0, seg, steps=2)
     run_lazy_case(A, 79, sum(seg), 7, 1, seg, steps=2)
+    # the widest groups of the sign-reading apply pass: 16 workers at a time, then a short group
+    seg = [600_003, 5, 477_777, 64, 500_001, 131_072, 2, 91_079]
+    for P in (16, 33):
+        assert (2 * P + 1) * 4 * sum(seg) > 192 << 20
+        run_lazy_case(A, 80 + P, sum(seg), P, 0, seg, steps=2)
 
 
 def test_lazy_state_on_a_tensor_plan_with_nans(A):

@@ -22,7 +22,8 @@ def asm():
                                   stderr=subprocess.DEVNULL)
             text += open(out).read()
     kernels = {}
-    for m in re.finditer(r"^(_ZN5a2sgd\w+):.*?s_endpgm", text, flags=re.S | re.M):
+    # a kernel's code: from its label to the end-of-function label (an early exit has an s_endpgm of its own)
+    for m in re.finditer(r"^(_ZN5a2sgd\w+):.*?^\.Lfunc_end\d+:", text, flags=re.S | re.M):
         kernels[m.group(1)] = m.group(0)
     assert any("k_seg_apply" in k for k in kernels) and any("k_apply" in k for k in kernels)
     return text, kernels
@@ -66,7 +67,9 @@ def test_every_hand_written_store_has_its_wait_states(asm):
     assert seen > 100
     for pat in (r"_ZN5a2sgd15k_lazy_partialsILb1E", r"_ZN5a2sgd18k_lazy_materializeILb1E", r"_ZN5a2sgd13k_apply_signsILb1E",
                 r"_ZN5a2sgd13k_error_signsILb1E", r"_ZN5a2sgd12k_dense_stepILb1E",
-                r"_ZN5a2sgd11k_seg_applyILi[01]ELb[01]ELb1E"):
+                r"_ZN5a2sgd11k_seg_applyILi[01]ELb[01]ELb1E", r"_ZN5a2sgd19k_seg_lazy_partialsILb1E",
+                r"_ZN5a2sgd17k_seg_error_signsILb1E", r"_ZN5a2sgd17k_seg_apply_signsILb1E",
+                r"_ZN5a2sgd17k_seg_materializeILb1E", r"_ZN5a2sgd27k_apply_replicas_per_workerILi[01]ELb[01]ELb1E"):
         names = [k for k in kernels if re.match(pat, k)]
         assert names, pat
         for name in names:
