@@ -124,8 +124,10 @@ def other_config(A, torch, workloads, k, steps, warmup):
 
 def hbm_ceilings(torch, g, e, w):
     """Plain streaming kernels (csrc/hbm_streams.hip) on the headline workload's own buffers, after everything else
-    has been measured (they overwrite e and w): GB/s of a read stream, a copy, an add of two streams and the apply
-    pass's mix of 2P + 1 read and P + 1 write streams.  None for a figure that cannot be measured here."""
+    has been measured (they overwrite e and w): GB/s of a read stream, a write stream, a copy, an add of two streams
+    and the apply pass's mix of 2P + 1 read and P + 1 write streams.  None for a figure that cannot be measured here.
+    `apply_pass_ms_at_plain_rates`: the time the apply pass's bytes would take if its reads went at the plain read
+    stream's rate and its writes at the plain write stream's, one after the other."""
     path = os.path.join(ROOT, "paper_2006_07405_amd", "libhbm_streams.so")
     if not os.path.exists(path):
         return {"error": "libhbm_streams.so is not built"}
@@ -152,6 +154,9 @@ def hbm_ceilings(torch, g, e, w):
     sink = torch.zeros(4, dtype=torch.float32, device="cuda")
     out = {"read_gbps": run(0, [g[0], sink], 1, 0), "copy_gbps": run(1, [g[0], e[0]], 2, 1)}
     out["add_gbps"] = run(2, [e[0], g[0], g[1 % P]], 3, 1)
+    out["fill_gbps"] = run(4, [e[0]], 0, 1)
+    if out["read_gbps"] and out["fill_gbps"]:
+        out["apply_pass_ms_at_plain_rates"] = ((8 * P + 4) * n / out["read_gbps"] + (4 * P + 4) * n / out["fill_gbps"]) / 1e6
     mix = f"mix_{2 * P + 1}r_{P + 1}w_gbps"
     out[mix] = run(3, list(e) + [w] + list(g), 2 * P + 1, P + 1) if P in (1, 2, 4, 8, 16) else None
     return out

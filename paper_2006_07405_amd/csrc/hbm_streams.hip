@@ -9,13 +9,15 @@
 //   kind 2  add       2 read streams, 1 write stream
 //   kind 3  mix       R read streams of which the first W are updated in place: the apply pass's mix, R = 2P + 1,
 //                     W = P + 1 (e^p and w are read and written, g^p only read)
+//   kind 4  fill      1 write stream, nothing read        (what the writes of a pass cost on their own)
 //
 // C ABI (built into libhbm_streams.so, loaded by bench.py with ctypes):
 //   int hbm_stream_run(int kind, float *const *buf, int reads, int writes, uint64_t n, void *stream)
 //     buf: HOST array of `reads` DEVICE pointers to n floats each, 16-byte aligned; buffers 0..writes-1 are written.
 //     kind 0: reads = 1, writes = 0 (buf[1] must point to at least 4 bytes: receives a value that is never set in
 //     practice, which keeps the loads alive); kind 1: reads = 2 (buf[1] <- buf[0]); kind 2: reads = 3
-//     (buf[0] <- buf[1] + buf[2]); kind 3: reads = 2P + 1 and writes = P + 1 for P = 1, 2, 4, 8 or 16.
+//     (buf[0] <- buf[1] + buf[2]); kind 3: reads = 2P + 1 and writes = P + 1 for P = 1, 2, 4, 8 or 16; kind 4:
+//     reads = 0, writes = 1 (buf[0] <- a constant).
 //     Enqueues one kernel on `stream` and returns 0, or a nonzero code if the arguments are wrong or the launch failed.
 //   uint64_t hbm_stream_bytes(int kind, int reads, int writes, uint64_t n): bytes that launch moves.
 #include <hip/hip_runtime.h>
@@ -58,6 +60,13 @@ __global__ __launch_bounds__(256) void k_copy(const vf4 *__restrict__ a, vf4 *__
     const uint64_t i = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (i < nvec)
         __builtin_nontemporal_store(__builtin_nontemporal_load(a + i), b + i);
+}
+
+__global__ __launch_bounds__(256) void k_fill(vf4 *__restrict__ a, const uint64_t nvec, const float value)
+{
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < nvec)
+        __builtin_nontemporal_store(vf4{value, value, value, value}, a + i);
 }
 
 __global__ __launch_bounds__(256) void k_add(vf4 *__restrict__ c, const vf4 *__restrict__ a, const vf4 *__restrict__ b,
@@ -103,6 +112,7 @@ uint64_t hbm_stream_bytes(int kind, int reads, int writes, uint64_t n)
     case 1: return 8 * n;
     case 2: return 12 * n;
     case 3: return 4 * n * static_cast<uint64_t>(reads + writes);
+    case 4: return 4 * n;
     }
     return 0;
 }
@@ -111,8 +121,8 @@ int hbm_stream_run(int kind, float *const *buf, int reads, int writes, uint64_t 
 {
     if (buf == nullptr || n == 0 || (n & 3) != 0 || n > (1ull << 38))
         return 1;
-    const int need = kind == 0 ? 2 : kind == 1 ? 2 : kind == 2 ? 3 : reads;
-    if (kind < 0 || kind > 3)
+    const int need = kind == 0 ? 2 : kind == 1 ? 2 : kind == 2 ? 3 : kind == 4 ? 1 : reads;
+    if (kind < 0 || kind > 4)
         return 1;
     if (kind == 3 && ((reads != 3 && reads != 5 && reads != 9 && reads != 17 && reads != 33) || writes != (reads + 1) / 2))
         return 1;
@@ -134,6 +144,9 @@ int hbm_stream_run(int kind, float *const *buf, int reads, int writes, uint64_t 
         k_add<<<dim3(static_cast<uint32_t>((nvec + 255) / 256)), dim3(256), 0, s>>>(
             reinterpret_cast<vf4 *>(buf[0]), reinterpret_cast<const vf4 *>(buf[1]),
             reinterpret_cast<const vf4 *>(buf[2]), nvec);
+    } else if (kind == 4) {
+        k_fill<<<dim3(static_cast<uint32_t>((nvec + 255) / 256)), dim3(256), 0, s>>>(reinterpret_cast<vf4 *>(buf[0]), nvec,
+                                                                                       1.0e-3f);
     } else {
         StreamTable tab;
         for (int k = 0; k < kMaxStreams; ++k)

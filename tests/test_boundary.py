@@ -300,7 +300,7 @@ def test_streaming_kernel_library_loads_and_validates():
     L.hbm_stream_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.c_uint64]
     L.hbm_stream_run.argtypes = [C.c_int, C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_uint64, C.c_void_p]
     n = 1 << 20
-    assert [L.hbm_stream_bytes(k, 9, 5, n) for k in (0, 1, 2, 3, 4)] == [4 * n, 8 * n, 12 * n, 56 * n, 0]
+    assert [L.hbm_stream_bytes(k, 9, 5, n) for k in (0, 1, 2, 3, 4, 5)] == [4 * n, 8 * n, 12 * n, 56 * n, 4 * n, 0]
     tab = (C.c_void_p * 9)(*[0x10000 * (k + 1) for k in range(9)])
     assert L.hbm_stream_run(1, None, 2, 1, n, None) == 1       # no table
     assert L.hbm_stream_run(7, tab, 2, 1, n, None) == 1        # unknown kind
