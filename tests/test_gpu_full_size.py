@@ -192,6 +192,90 @@ def test_config5_two_steps_from_zero_error_as_the_benchmark_runs_them(A):
         print(f"  step {t}: counts equal, every element of e and w within tolerance, {time.time() - t1:.1f}s", flush=True)
 
 
+@pytest.mark.parametrize("lazy", [False, True])
+def test_config5_full_size_per_tensor(A, lazy):
+    """The headline size with one pair of means per worker and tensor (557 tensors), as `bench.py --per-tensor` runs
+    it: one step from a nonzero error, counts equal for every worker and tensor, every element of e and w against the
+    oracle applied tensor by tensor.  lazy = through a2sgd_lazy_step and a2sgd_lazy_materialize (the one-shot
+    reduction by blocks of 2048 elements, the apply pass from the stored sign bits)."""
+    t0 = time.time()
+    wl = workloads.FULL[5]()
+    n, P = wl.n, wl.num_workers
+    seg = [numel for _, numel in wl.tensors]
+    S = len(seg)
+    bounds = np.concatenate([[0], np.cumsum(seg)]).astype(np.int64)
+    assert bounds[-1] == n
+    g = [wl.gradient(p, 0, device="cuda") for p in range(P)]
+    e = [wl.synthetic_error(p, device="cuda") for p in range(P)]
+    w = wl.weights(device="cuda")
+    e0 = [x.clone() for x in e]
+    w0 = w.clone()
+    stages = Stages(3 * P + 2)
+    print(f"config 5 per tensor lazy={lazy}: {S} tensors, generated in {time.time() - t0:.1f}s", flush=True)
+
+    def pieces(lo, hi):
+        """(tensor, a, b): the parts of the tensors that lie in [lo, hi)."""
+        k = int(np.searchsorted(bounds, lo, side="right")) - 1
+        while k < S and bounds[k] < hi:
+            yield k, max(lo, int(bounds[k])), min(hi, int(bounds[k + 1]))
+            k += 1
+
+    t1 = time.time()
+    accs = [[O.LocalAccumulator() for _ in range(S)] for _ in range(P)]
+    torch.cuda.synchronize()
+
+    def pass_a(p):  # one thread per worker, every tensor fed in index order
+        st = stages.free.get()
+        try:
+            for lo in range(0, n, stages.chunk):
+                hi = min(n, lo + stages.chunk)
+                gh, eh = st.fetch([g[p][lo:hi], e0[p][lo:hi]])
+                for k, a, b in pieces(lo, hi):
+                    accs[p][k].feed(gh[a - lo:b - lo], eh[a - lo:b - lo])
+        finally:
+            stages.free.put(st)
+
+    with ThreadPoolExecutor(P) as pool:
+        list(pool.map(pass_a, range(P)))
+    stats_ref = [[accs[p][k].stats() for p in range(P)] for k in range(S)]
+    gmu_ref = [O.global_means(stats_ref[k]) for k in range(S)]
+    print(f"  oracle pass A in {time.time() - t1:.1f}s", flush=True)
+
+    plan = A.a2sgd_plan(n, P, 0, 0, seg_lengths=seg)
+    ws = A.alloc_workspace(plan)
+    if lazy:
+        A.a2sgd_lazy_reset(plan, ws)
+        A.a2sgd_lazy_step(plan, g, e, w, wl.eta, ws)
+        A.a2sgd_lazy_materialize(plan, e, ws)
+    else:
+        A.a2sgd_local_averages(plan, g, e, ws)
+        A.a2sgd_global_average(plan, ws)
+        A.a2sgd_apply_and_update_error(plan, g, e, w, wl.eta, ws)
+    stats, gmu = A.a2sgd_read_segment_stats(plan, ws)
+    for k in range(S):
+        for p in range(P):
+            a, b = stats[p][k], stats_ref[k][p]
+            assert (a.n_pos, a.n_neg, a.n_zero, a.n_nan) == (b.n_pos, b.n_neg, b.n_zero, b.n_nan), f"tensor {k} worker {p}"
+            assert abs(a.mu_pos - b.mu_pos) <= 1e-5 * abs(b.mu_pos) and abs(a.mu_neg - b.mu_neg) <= 1e-5 * abs(b.mu_neg)
+        assert abs(gmu[k][0] - gmu_ref[k][0]) <= 1e-5 * abs(gmu_ref[k][0])
+        assert abs(gmu[k][1] - gmu_ref[k][1]) <= 1e-5 * abs(gmu_ref[k][1])
+
+    t2 = time.time()
+
+    def pass_b(st, lo, hi):
+        h = st.fetch([x[lo:hi] for x in g] + [x[lo:hi] for x in e0] + [w0[lo:hi]] + [x[lo:hi] for x in e] + [w[lo:hi]])
+        for k, a, b in pieces(lo, hi):
+            sl = slice(a - lo, b - lo)
+            e_ref, w_ref, _ = O.apply_chunk([x[sl] for x in h[:P]], [x[sl] for x in h[P:2 * P]], h[2 * P][sl],
+                                            stats_ref[k], gmu_ref[k][0], gmu_ref[k][1], wl.eta, O.RETAINED_ERROR)
+            for p in range(P):
+                assert_chunk_close(h[2 * P + 1 + p][sl], e_ref[p], f"tensor {k} e[{p}][{a}:{b}]")
+            assert_chunk_close(h[3 * P + 1][sl], w_ref, f"tensor {k} w[{a}:{b}]")
+
+    stages.run(n, pass_b)
+    print(f"  oracle pass B on all {-(-n // CHUNK)} chunks in {time.time() - t2:.1f}s, total {time.time() - t0:.1f}s", flush=True)
+
+
 def oracle_step_threaded(g, e, w, eta, chunk=1 << 22, threads=THREADS):
     """One whole oracle step on host arrays, the oracle's own calls spread over host threads: one accumulator per
     worker fed in index order, then the elementwise pass chunk by chunk.  Returns (stats, gmu, e_new, w_new)."""
