@@ -287,7 +287,7 @@ def main() -> int:
     out["dense_step"] = {"ms": ms_dense, "gbps": (4 * n * P + 8 * n) / (ms_dense * 1e-3) / 1e9,
                          "params_per_s": n / (ms_dense * 1e-3)}
 
-    if args.replicas and not plan.num_segments:
+    if args.replicas:
         # Algorithm 1 line 7 as each worker runs it: 8nP bytes for the reduction, 20nP for the apply pass
         wr = [w.clone() for _ in range(P)]
         A.a2sgd_step_replicas(plan, g, e, wr, wl.eta, ws)

@@ -712,6 +712,110 @@ __global__ __launch_bounds__(BLOCK) void k_seg_apply_replicas(const PtrTable tab
     }
 }
 
+// The same pass with one worker per workgroup, for many workers at streaming sizes (as k_apply_replicas_per_worker
+// on whole-model plans: a workgroup has three buffers open instead of 3P).  grid = (workgroups of 512 elements, P);
+// a workgroup covers two entries of the lookup table and asks for the means of both chunks' first tensors at once.
+constexpr int kSegReplItems = 2;
+template <int MODE, bool HAS_E, bool NT>
+__global__ __launch_bounds__(64) void k_seg_apply_replicas_per_worker(const PtrTable tab, const ReplicaTable wt,
+                                                                      const uint64_t n, const uint64_t chunks,
+                                                                      const float eta, const SegView sv)
+{
+    const uint32_t p = blockIdx.y, P = gridDim.y, lane = threadIdx.x;
+    const vf4 *__restrict__ g4 = reinterpret_cast<const vf4 *>(tab.g[p]);
+    float *e = HAS_E ? tab.e[p] : nullptr;
+    vf4 *e4 = reinterpret_cast<vf4 *>(e);
+    float *w = wt.w[p];
+    vf4 *w4 = reinterpret_cast<vf4 *>(w);
+    const uint64_t nvec = n >> 2;
+    const uint64_t base = static_cast<uint64_t>(blockIdx.x) * (64 * kSegReplItems) + lane;
+    vf4 gv[kSegReplItems], ev[kSegReplItems], wv[kSegReplItems];
+#pragma unroll
+    for (int u = 0; u < kSegReplItems; ++u)
+        if (base + u * 64 < nvec) {
+            gv[u] = ld4<NT>(g4 + base + u * 64);
+            if (HAS_E)
+                ev[u] = ld4<NT>(e4 + base + u * 64);
+            wv[u] = ld4<NT>(w4 + base + u * 64);
+        }
+    __builtin_amdgcn_sched_barrier(0);
+    uint32_t entry[kSegReplItems];
+#pragma unroll
+    for (int u = 0; u < kSegReplItems; ++u) {
+        const uint64_t c = static_cast<uint64_t>(blockIdx.x) * kSegReplItems + u;
+        entry[u] = c < chunks ? sv.coarse[c] : 0u;
+    }
+    if (!seg_tables_ok(sv))
+        return;
+    float nmp[kSegReplItems], mn[kSegReplItems], gp[kSegReplItems], ngn[kSegReplItems];
+#pragma unroll
+    for (int u = 0; u < kSegReplItems; ++u) {
+        const uint32_t t = min(entry[u] & ~kSegInsideBit, sv.S - 1);  // S where no tensor follows: not used then
+        nmp[u] = sv.neg_mu_pos[static_cast<size_t>(t) * P + p];
+        mn[u] = sv.mu_neg[static_cast<size_t>(t) * P + p];
+        gp[u] = sv.gmu[2 * t];
+        ngn[u] = sv.gmu[2 * t + 1];
+    }
+#pragma unroll
+    for (int u = 0; u < kSegReplItems; ++u) {
+        const uint64_t i = base + u * 64;
+        if (i >= nvec)
+            continue;
+        const vf4 vv = HAS_E ? gv[u] + ev[u] : gv[u];
+        if (entry[u] & kSegInsideBit) {  // one tensor for the whole chunk
+            vf4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
+            const vf4 err = apply4<MODE>(vv, upd, nmp[u], mn[u], gp[u], ngn[u]);
+            if (HAS_E)
+                st4<NT>(e4 + i, err);
+            const vf4 wn = wv[u] - eta * upd;
+            st4<NT>(w4 + i, wn);
+        } else {
+            uint32_t sc[4];
+            seg_of4(sv, entry[u] & ~kSegInsideBit, i << 2, sc);
+            float x[4] = {vv.x, vv.y, vv.z, vv.w};
+            const float wo[4] = {wv[u].x, wv[u].y, wv[u].z, wv[u].w};
+            float wn[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t t = sc[c] != sv.S ? sc[c] : 0u;
+                const float upd = apply1<MODE>(x[c], sv.neg_mu_pos[static_cast<size_t>(t) * P + p],
+                                               sv.mu_neg[static_cast<size_t>(t) * P + p], sv.gmu[2 * t], sv.gmu[2 * t + 1]);
+                wn[c] = wo[c] - eta * upd;
+            }
+            if (sc[0] != sv.S && sc[1] != sv.S && sc[2] != sv.S && sc[3] != sv.S) {
+                if (HAS_E) {
+                    const vf4 err = vf4{x[0], x[1], x[2], x[3]};
+                    st4<NT>(e4 + i, err);
+                }
+                const vf4 out = vf4{wn[0], wn[1], wn[2], wn[3]};
+                st4<NT>(w4 + i, out);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (sc[c] != sv.S) {  // padding is not touched
+                        if (HAS_E)
+                            e[(i << 2) + c] = x[c];
+                        w[(i << 2) + c] = wn[c];
+                    }
+            }
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1 && lane < (n & 3)) {
+        const uint64_t idx = (nvec << 2) + lane;
+        const uint32_t t = seg_of(sv, sv.coarse[idx >> kSegCoarseShift] & ~kSegInsideBit, idx);
+        if (sv.seg_start[t] <= idx) {
+            float v = tab.g[p][idx];
+            if (HAS_E)
+                v += e[idx];
+            const float upd = apply1<MODE>(v, sv.neg_mu_pos[static_cast<size_t>(t) * P + p],
+                                           sv.mu_neg[static_cast<size_t>(t) * P + p], sv.gmu[2 * t], sv.gmu[2 * t + 1]);
+            if (HAS_E)
+                e[idx] = v;
+            w[idx] -= eta * upd;
+        }
+    }
+}
+
 // Lazy state on a plan with tensors, back to true errors: s <- pending error of s with the carried means of the
 // element's tensor.  grid = (workgroups of 64 float4 groups, P).
 template <bool NT>
@@ -1189,6 +1293,16 @@ static hipError_t launch_seg_apply_replicas_shape(const a2sgd_plan_t &pl, const 
 {
     constexpr int kThreads = 64;
     const uint64_t nvec = (pl.n + 3) >> 2;
+    if (NT && pl.P >= kPerWorkerReplicas) {
+        // one worker per workgroup, 13 workgroups per CU (measured, whole replica step in ms at configs 4 / 2 with
+        // per-tensor means: grouped form 10.73 / 0.953; this form with 26, 20, 16, 13, 10, 8 workgroups per CU 10.72 /
+        // 0.913, 9.91 / 0.911, 10.04 / 0.901, 9.34 / 0.875, 9.55 / 0.913, 9.88 / 0.952)
+        const uint64_t chunks = (pl.n + (1ull << kSegCoarseShift) - 1) >> kSegCoarseShift;
+        const uint64_t per = 64ull * kSegReplItems;
+        const dim3 per_worker(static_cast<uint32_t>((nvec + per - 1) / per), pl.P);
+        k_seg_apply_replicas_per_worker<MODE, HAS_E, NT><<<per_worker, dim3(64), 12 * 1024, s>>>(tab, wt, pl.n, chunks, eta, sv);
+        return hipGetLastError();
+    }
     const dim3 grid(static_cast<uint32_t>((nvec + kThreads - 1) / kThreads)), block(kThreads);
     const uint32_t lds = pl.streaming ? 14 * 1024 : 0;  // 11 workgroups per CU, as the shared-weight pass at P = 4
     if (pl.P >= 4)

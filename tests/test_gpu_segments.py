@@ -347,6 +347,25 @@ def test_replicas_on_a_tensor_plan_streaming(A):
     run_replica_case(A, 77, sum(seg), 7, 0, seg)
 
 
+@pytest.mark.parametrize("P,mode,padded,pooled", [(8, 0, False, False), (9, 1, True, False), (16, 0, True, True),
+                                                  (33, 1, False, False)])
+def test_replicas_on_a_tensor_plan_streaming_one_worker_per_workgroup(A, P, mode, padded, pooled):
+    """From 8 workers on the streaming replica pass of a plan with tensors gives every workgroup one worker's g, e
+    and w^p: tensor boundaries of every alignment inside a workgroup's two lookup chunks, with and without padding
+    between the tensors (NaN there, which must come back untouched)."""
+    seg = [1_000_003, 5, 777_777, 64, 1_300_001, 131_072, 2, 291_079] if P < 16 else \
+        [600_003, 5, 477_777, 64, 500_001, 131_072, 2, 91_079]
+    offsets, n = None, sum(seg)
+    if padded:
+        offsets, pos = [], 3
+        for k, length in enumerate(seg):
+            offsets.append(pos)
+            pos += length + (0, 1, 255, 1027)[k % 4]
+        n = pos + 6
+    assert (2 * P + 1) * 4 * n > 192 << 20
+    run_replica_case(A, 90 + P, n, P, mode, seg, offsets, pooled)
+
+
 def run_lazy_case(A, seed, n, P, mode, lengths, offsets=None, pooled=False, steps=4):
     """Steps on the lazy state of a plan with tensors (the buffers hold v, every tensor's pending error is formed with
     that tensor's carried means) against eager steps of the per-tensor oracle: same statistics and w at every step,

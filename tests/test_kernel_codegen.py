@@ -69,7 +69,8 @@ def test_every_hand_written_store_has_its_wait_states(asm):
                 r"_ZN5a2sgd13k_error_signsILb1E", r"_ZN5a2sgd12k_dense_stepILb1E",
                 r"_ZN5a2sgd11k_seg_applyILi[01]ELb[01]ELb1E", r"_ZN5a2sgd19k_seg_lazy_partialsILb1E",
                 r"_ZN5a2sgd17k_seg_error_signsILb1E", r"_ZN5a2sgd17k_seg_apply_signsILb1E",
-                r"_ZN5a2sgd17k_seg_materializeILb1E", r"_ZN5a2sgd27k_apply_replicas_per_workerILi[01]ELb[01]ELb1E"):
+                r"_ZN5a2sgd17k_seg_materializeILb1E", r"_ZN5a2sgd27k_apply_replicas_per_workerILi[01]ELb[01]ELb1E",
+                r"_ZN5a2sgd31k_seg_apply_replicas_per_workerILi[01]ELb[01]ELb1E"):
         names = [k for k in kernels if re.match(pat, k)]
         assert names, pat
         for name in names:
