@@ -112,8 +112,10 @@ a2sgd_status_t a2sgd_plan_destroy(a2sgd_plan_t *plan);
 
 /* Bytes of device workspace the caller must provide (16-byte aligned) to the calls below.  Its contents need
  * no initialisation; it carries the block partials, the per-worker means and counts and the global means from
- * one call of a step to the next.  For a whole-model plan it includes the records of the lazy calls' reduction
- * pass (40 bytes per 2048 elements and worker).  Returns 0 for a NULL plan. */
+ * one call of a step to the next.  It includes the records of the lazy calls' reduction pass (40 bytes per 2048
+ * elements and worker) and, in A2SGD_MODE_RETAINED_ERROR, one sign bit per element and worker for the lazy calls
+ * and for the apply pass of plans with 8 workers or more: about 0.15 bytes per element and worker in all.
+ * Returns 0 for a NULL plan. */
 size_t a2sgd_workspace_bytes(const a2sgd_plan_t *plan);
 
 /* Host only.  The step calls take a workspace pointer without a size; a caller that wants the size checked passes
