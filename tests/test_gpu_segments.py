@@ -680,3 +680,50 @@ def test_single_launch_step_on_tensors_is_deterministic_and_graph_capturable(A):
         assert busy == busy
         assert torch.equal(w, expected[k][1]), f"replay {k}: w differs from the eager step"
         assert all(torch.equal(a, b) for a, b in zip(e, expected[k][0])), f"replay {k}: e differs from the eager step"
+
+
+@pytest.mark.parametrize("calls,P", [("lazy", 3), ("lazy", 8), ("three", 8)])
+def test_tensor_plan_steps_captured_in_a_hip_graph(A, calls, P):
+    """The lazy step on a plan with tensors (one-shot reduction, fold, second level, global pass, sign-reading apply
+    pass) and the eager step whose apply pass is two kernels only enqueue kernels: captured once and replayed three
+    times with eager work between the replays, they leave exactly what three eager calls leave."""
+    seg = [1_000_003, 5, 777_777, 64, 1_300_001, 131_072, 2, 291_079]
+    n = sum(seg)
+    rng = np.random.default_rng(P)
+    scale = torch.from_numpy(scales_for(seg, 3)).cuda()
+    g = [torch.from_numpy(rng.standard_normal(n).astype(f32)).cuda() * scale for _ in range(P)]
+    e0 = [torch.from_numpy((rng.standard_normal(n) * 0.5).astype(f32)).cuda() * scale for _ in range(P)]
+    w0 = torch.from_numpy((rng.standard_normal(n) * 0.02).astype(f32)).cuda()
+    plan = A.a2sgd_plan(n, P, 0, 0, seg_lengths=seg)
+
+    def one_step(e, w, ws):
+        if calls == "lazy":
+            A.a2sgd_lazy_step(plan, g, e, w, 0.1, ws)
+        else:
+            A.a2sgd_local_averages(plan, g, e, ws)
+            A.a2sgd_global_average(plan, ws)
+            A.a2sgd_apply_and_update_error(plan, g, e, w, 0.1, ws)
+
+    ws_ref = A.alloc_workspace(plan)
+    e_ref, w_ref = [x.clone() for x in e0], w0.clone()
+    if calls == "lazy":
+        A.a2sgd_lazy_reset(plan, ws_ref)
+    expected = []
+    for _ in range(3):
+        one_step(e_ref, w_ref, ws_ref)
+        expected.append(([x.clone() for x in e_ref], w_ref.clone()))
+    ws = A.alloc_workspace(plan)
+    e, w = [x.clone() for x in e0], w0.clone()
+    if calls == "lazy":
+        A.a2sgd_lazy_reset(plan, ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        one_step(e, w, ws)
+    for k in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        busy = (w0 * 2.0).sum().item()  # unrelated eager work and a host wait between replays
+        assert busy == busy
+        assert torch.equal(w, expected[k][1]), f"replay {k}: w differs from the eager step"
+        assert all(torch.equal(a, b) for a, b in zip(e, expected[k][0])), f"replay {k}: state differs from the eager step"
