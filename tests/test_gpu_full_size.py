@@ -106,48 +106,61 @@ def test_full_size_config(A, k, lazy):
     """One step at full size from a nonzero error, every element of e and w against the oracle.  lazy = the same
     step through a2sgd_lazy_step (the buffers then hold v) followed by a2sgd_lazy_materialize, after which they hold
     the same new errors as the eager step leaves."""
+    run_full_size(A, workloads.FULL[k](), (lazy,), k)
+
+
+def run_full_size(A, wl, variants, k):
+    """variants: which steps to run from the same inputs, False = eager, True = lazy; the oracle's first pass is taken
+    once."""
     t0 = time.time()
-    wl = workloads.FULL[k]()
     n, P = wl.n, wl.num_workers
-    print(f"config {k} lazy={lazy}: n={n} P={P}", flush=True)
+    print(f"config {k} lazy={variants}: n={n} P={P}", flush=True)
     g = [wl.gradient(p, 0, device="cuda") for p in range(P)]
-    e = [wl.synthetic_error(p, device="cuda") for p in range(P)]
-    w = wl.weights(device="cuda")
-    e0 = [x.clone() for x in e]
-    w0 = w.clone()
+    e0 = [wl.synthetic_error(p, device="cuda") for p in range(P)]
+    w0 = wl.weights(device="cuda")
     stages = Stages(3 * P + 2)
     print(f"  generated in {time.time() - t0:.1f}s", flush=True)
 
     t1 = time.time()
-    stats_ref = oracle_pass_a(g, e, n, P, stages)
+    stats_ref = oracle_pass_a(g, e0, n, P, stages)
     gp, gn = O.global_means(stats_ref)
     print(f"  oracle pass A in {time.time() - t1:.1f}s", flush=True)
 
     plan = A.a2sgd_plan(n, P, 0)
     ws = A.alloc_workspace(plan)
-    if lazy:
-        A.a2sgd_lazy_reset(plan, ws)
-        A.a2sgd_lazy_step(plan, g, e, w, wl.eta, ws)
-        A.a2sgd_lazy_materialize(plan, e, ws)
-    else:
-        A.a2sgd_step(plan, g, e, w, wl.eta, ws)
-    stats, gmu = A.a2sgd_read_stats(plan, ws)
-    compare_stats(stats, gmu, O.StepResult(stats_ref, gp, gn, [], np.empty(0, f32), []))
-    for p in range(P):
-        assert stats[p].n_pos + stats[p].n_neg == n and stats[p].n_nan == 0
-
-    t2 = time.time()
-
-    def pass_b(st, lo, hi):
-        h = st.fetch([x[lo:hi] for x in g] + [x[lo:hi] for x in e0] + [w0[lo:hi]] + [x[lo:hi] for x in e] + [w[lo:hi]])
-        e_ref, w_ref, _ = O.apply_chunk(h[:P], h[P:2 * P], h[2 * P], stats_ref, gp, gn, wl.eta, O.RETAINED_ERROR)
+    for lazy in variants:
+        e, w = [x.clone() for x in e0], w0.clone()
+        if lazy:
+            A.a2sgd_lazy_reset(plan, ws)
+            A.a2sgd_lazy_step(plan, g, e, w, wl.eta, ws)
+            A.a2sgd_lazy_materialize(plan, e, ws)
+        else:
+            A.a2sgd_step(plan, g, e, w, wl.eta, ws)
+        stats, gmu = A.a2sgd_read_stats(plan, ws)
+        compare_stats(stats, gmu, O.StepResult(stats_ref, gp, gn, [], np.empty(0, f32), []))
         for p in range(P):
-            assert_chunk_close(h[2 * P + 1 + p], e_ref[p], f"config {k} e[{p}][{lo}:{hi}]")
-        assert_chunk_close(h[3 * P + 1], w_ref, f"config {k} w[{lo}:{hi}]")
+            assert stats[p].n_pos + stats[p].n_neg == n and stats[p].n_nan == 0
 
-    stages.run(n, pass_b)
-    print(f"  oracle pass B on all {-(-n // CHUNK)} chunks in {time.time() - t2:.1f}s", flush=True)
+        t2 = time.time()
+
+        def pass_b(st, lo, hi):
+            h = st.fetch([x[lo:hi] for x in g] + [x[lo:hi] for x in e0] + [w0[lo:hi]] + [x[lo:hi] for x in e] + [w[lo:hi]])
+            e_ref, w_ref, _ = O.apply_chunk(h[:P], h[P:2 * P], h[2 * P], stats_ref, gp, gn, wl.eta, O.RETAINED_ERROR)
+            for p in range(P):
+                assert_chunk_close(h[2 * P + 1 + p], e_ref[p], f"config {k} lazy={lazy} e[{p}][{lo}:{hi}]")
+            assert_chunk_close(h[3 * P + 1], w_ref, f"config {k} lazy={lazy} w[{lo}:{hi}]")
+
+        stages.run(n, pass_b)
+        print(f"  lazy={lazy}: oracle pass B on all {-(-n // CHUNK)} chunks in {time.time() - t2:.1f}s", flush=True)
+        del e, w
     print(f"  total {time.time() - t0:.1f}s", flush=True)
+
+
+def test_more_than_two_to_the_32_elements(A):
+    """One worker with 2^32 + 4099 parameters (17 GB per buffer): element indices beyond 32 bits in every pass, a
+    ragged last workgroup and a scalar tail up there.  The eager and the lazy step from the same inputs, every element
+    of e and w against the oracle, as above."""
+    run_full_size(A, workloads.config1(n=(1 << 32) + 4099, num_workers=1), (False, True), "flat 2^32+4099")
 
 
 def test_config5_two_steps_from_zero_error_as_the_benchmark_runs_them(A):
@@ -198,20 +211,29 @@ def test_config5_full_size_per_tensor(A, lazy):
     it: one step from a nonzero error, counts equal for every worker and tensor, every element of e and w against the
     oracle applied tensor by tensor.  lazy = through a2sgd_lazy_step and a2sgd_lazy_materialize (the one-shot
     reduction by blocks of 2048 elements, the apply pass from the stored sign bits)."""
-    t0 = time.time()
     wl = workloads.FULL[5]()
+    run_full_size_per_tensor(A, wl, [numel for _, numel in wl.tensors], (lazy,))
+
+
+def test_tensor_boundaries_beyond_two_to_the_32(A):
+    """One worker, 2^32 + 4099 parameters in three tensors whose boundaries lie just below and just above element
+    2^32 (neither on a float4 group): the per-tensor passes, eager and lazy, with element indices beyond 32 bits."""
+    n = (1 << 32) + 4099
+    run_full_size_per_tensor(A, workloads.config1(n=n, num_workers=1), [(1 << 32) - 1001, 3003, n - (1 << 32) - 2002],
+                             (False, True))
+
+
+def run_full_size_per_tensor(A, wl, seg, variants):
+    t0 = time.time()
     n, P = wl.n, wl.num_workers
-    seg = [numel for _, numel in wl.tensors]
     S = len(seg)
     bounds = np.concatenate([[0], np.cumsum(seg)]).astype(np.int64)
     assert bounds[-1] == n
     g = [wl.gradient(p, 0, device="cuda") for p in range(P)]
-    e = [wl.synthetic_error(p, device="cuda") for p in range(P)]
-    w = wl.weights(device="cuda")
-    e0 = [x.clone() for x in e]
-    w0 = w.clone()
+    e0 = [wl.synthetic_error(p, device="cuda") for p in range(P)]
+    w0 = wl.weights(device="cuda")
     stages = Stages(3 * P + 2)
-    print(f"config 5 per tensor lazy={lazy}: {S} tensors, generated in {time.time() - t0:.1f}s", flush=True)
+    print(f"per tensor lazy={variants}: n={n} P={P}, {S} tensors, generated in {time.time() - t0:.1f}s", flush=True)
 
     def pieces(lo, hi):
         """(tensor, a, b): the parts of the tensors that lie in [lo, hi)."""
@@ -243,37 +265,40 @@ def test_config5_full_size_per_tensor(A, lazy):
 
     plan = A.a2sgd_plan(n, P, 0, 0, seg_lengths=seg)
     ws = A.alloc_workspace(plan)
-    if lazy:
-        A.a2sgd_lazy_reset(plan, ws)
-        A.a2sgd_lazy_step(plan, g, e, w, wl.eta, ws)
-        A.a2sgd_lazy_materialize(plan, e, ws)
-    else:
-        A.a2sgd_local_averages(plan, g, e, ws)
-        A.a2sgd_global_average(plan, ws)
-        A.a2sgd_apply_and_update_error(plan, g, e, w, wl.eta, ws)
-    stats, gmu = A.a2sgd_read_segment_stats(plan, ws)
-    for k in range(S):
-        for p in range(P):
-            a, b = stats[p][k], stats_ref[k][p]
-            assert (a.n_pos, a.n_neg, a.n_zero, a.n_nan) == (b.n_pos, b.n_neg, b.n_zero, b.n_nan), f"tensor {k} worker {p}"
-            assert abs(a.mu_pos - b.mu_pos) <= 1e-5 * abs(b.mu_pos) and abs(a.mu_neg - b.mu_neg) <= 1e-5 * abs(b.mu_neg)
-        assert abs(gmu[k][0] - gmu_ref[k][0]) <= 1e-5 * abs(gmu_ref[k][0])
-        assert abs(gmu[k][1] - gmu_ref[k][1]) <= 1e-5 * abs(gmu_ref[k][1])
-
-    t2 = time.time()
-
-    def pass_b(st, lo, hi):
-        h = st.fetch([x[lo:hi] for x in g] + [x[lo:hi] for x in e0] + [w0[lo:hi]] + [x[lo:hi] for x in e] + [w[lo:hi]])
-        for k, a, b in pieces(lo, hi):
-            sl = slice(a - lo, b - lo)
-            e_ref, w_ref, _ = O.apply_chunk([x[sl] for x in h[:P]], [x[sl] for x in h[P:2 * P]], h[2 * P][sl],
-                                            stats_ref[k], gmu_ref[k][0], gmu_ref[k][1], wl.eta, O.RETAINED_ERROR)
+    for lazy in variants:
+        e, w = [x.clone() for x in e0], w0.clone()
+        if lazy:
+            A.a2sgd_lazy_reset(plan, ws)
+            A.a2sgd_lazy_step(plan, g, e, w, wl.eta, ws)
+            A.a2sgd_lazy_materialize(plan, e, ws)
+        else:
+            A.a2sgd_local_averages(plan, g, e, ws)
+            A.a2sgd_global_average(plan, ws)
+            A.a2sgd_apply_and_update_error(plan, g, e, w, wl.eta, ws)
+        stats, gmu = A.a2sgd_read_segment_stats(plan, ws)
+        for k in range(S):
             for p in range(P):
-                assert_chunk_close(h[2 * P + 1 + p][sl], e_ref[p], f"tensor {k} e[{p}][{a}:{b}]")
-            assert_chunk_close(h[3 * P + 1][sl], w_ref, f"tensor {k} w[{a}:{b}]")
+                a, b = stats[p][k], stats_ref[k][p]
+                assert (a.n_pos, a.n_neg, a.n_zero, a.n_nan) == (b.n_pos, b.n_neg, b.n_zero, b.n_nan), f"tensor {k} worker {p}"
+                assert abs(a.mu_pos - b.mu_pos) <= 1e-5 * abs(b.mu_pos) and abs(a.mu_neg - b.mu_neg) <= 1e-5 * abs(b.mu_neg)
+            assert abs(gmu[k][0] - gmu_ref[k][0]) <= 1e-5 * abs(gmu_ref[k][0])
+            assert abs(gmu[k][1] - gmu_ref[k][1]) <= 1e-5 * abs(gmu_ref[k][1])
 
-    stages.run(n, pass_b)
-    print(f"  oracle pass B on all {-(-n // CHUNK)} chunks in {time.time() - t2:.1f}s, total {time.time() - t0:.1f}s", flush=True)
+        t2 = time.time()
+
+        def pass_b(st, lo, hi):
+            h = st.fetch([x[lo:hi] for x in g] + [x[lo:hi] for x in e0] + [w0[lo:hi]] + [x[lo:hi] for x in e] + [w[lo:hi]])
+            for k, a, b in pieces(lo, hi):
+                sl = slice(a - lo, b - lo)
+                e_ref, w_ref, _ = O.apply_chunk([x[sl] for x in h[:P]], [x[sl] for x in h[P:2 * P]], h[2 * P][sl],
+                                                stats_ref[k], gmu_ref[k][0], gmu_ref[k][1], wl.eta, O.RETAINED_ERROR)
+                for p in range(P):
+                    assert_chunk_close(h[2 * P + 1 + p][sl], e_ref[p], f"lazy={lazy} tensor {k} e[{p}][{a}:{b}]")
+                assert_chunk_close(h[3 * P + 1][sl], w_ref, f"lazy={lazy} tensor {k} w[{a}:{b}]")
+
+        stages.run(n, pass_b)
+        print(f"  lazy={lazy}: oracle pass B on all {-(-n // CHUNK)} chunks in {time.time() - t2:.1f}s, total {time.time() - t0:.1f}s", flush=True)
+        del e, w
 
 
 def oracle_step_threaded(g, e, w, eta, chunk=1 << 22, threads=THREADS):
