@@ -89,6 +89,72 @@ __device__ __forceinline__ uint64_t wave_sum(uint64_t x)
     return x;
 }
 
+// One record of the reduction: the sums of the two groups, their sizes, and the zeros among the first.
+struct Sums {
+    double s_pos = 0.0, s_neg = 0.0;
+    uint64_t n_pos = 0, n_neg = 0, n_zero = 0;
+};
+
+__device__ __forceinline__ void add_record(Sums &a, const Partials &t, const size_t slot)
+{
+    a.s_pos += t.s_pos[slot];
+    a.s_neg += t.s_neg[slot];
+    a.n_pos += t.n_pos[slot];
+    a.n_neg += t.n_neg[slot];
+    a.n_zero += t.n_zero[slot];
+}
+
+__device__ __forceinline__ void store_record(const Partials &t, const size_t slot, const Sums &r)
+{
+    t.s_pos[slot] = r.s_pos;
+    t.s_neg[slot] = r.s_neg;
+    t.n_pos[slot] = r.n_pos;
+    t.n_neg[slot] = r.n_neg;
+    t.n_zero[slot] = r.n_zero;
+}
+
+// Adds one record per wavefront (valid in lane 0 of each) over a workgroup of kBlock threads, wavefronts in index
+// order; the total is valid in thread 0.  Every thread of the workgroup calls it; before a second call the
+// workgroup needs a __syncthreads() of its own, since the staging slots are reused.
+__device__ __forceinline__ Sums block_sum_of_waves(const Sums &wave_total)
+{
+    __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
+    __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) {
+        sh_pos[wave] = wave_total.s_pos;
+        sh_neg[wave] = wave_total.s_neg;
+        sh_cp[wave] = wave_total.n_pos;
+        sh_cn[wave] = wave_total.n_neg;
+        sh_cz[wave] = wave_total.n_zero;
+    }
+    __syncthreads();
+    Sums total;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int k = 0; k < kBlock / 64; ++k) {
+            total.s_pos += sh_pos[k];
+            total.s_neg += sh_neg[k];
+            total.n_pos += sh_cp[k];
+            total.n_neg += sh_cn[k];
+            total.n_zero += sh_cz[k];
+        }
+    }
+    return total;
+}
+
+// The same for one record per thread: shuffle tree inside each wavefront first.  The order is fixed, so the result
+// is reproducible.
+__device__ __forceinline__ Sums block_sum(Sums mine)
+{
+    mine.s_pos = wave_sum(mine.s_pos);
+    mine.s_neg = wave_sum(mine.s_neg);
+    mine.n_pos = wave_sum(mine.n_pos);
+    mine.n_neg = wave_sum(mine.n_neg);
+    mine.n_zero = wave_sum(mine.n_zero);
+    return block_sum_of_waves(mine);
+}
+
 // One element of one worker: rewrites v into the new error and returns that worker's contribution u to the
 // update.  Written as selects on register values so that it compiles to v_cndmask, not to branches.  A NaN
 // fails v >= 0, so v + mu_neg keeps it NaN in e; the extra select keeps it NaN in u as well.

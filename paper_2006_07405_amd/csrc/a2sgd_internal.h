@@ -125,8 +125,7 @@ struct SegView {
     a2sgd_worker_stats_t *stats;  // [P][S]
     float *neg_mu_pos, *mu_neg;   // [S][P], packed for the apply pass
     float *gmu;                   // [S][2]: gmu_pos, -gmu_neg
-    double *r_spos, *r_sneg;      // [P][num_items] partial records of the reduction
-    uint64_t *r_npos, *r_nneg, *r_nzero;
+    Partials rec;                 // [P][num_items] partial records of the reduction
 };
 
 // The single-launch step on a plan with tensors works on finer items (at most kFusedItemElems elements inside one

@@ -62,37 +62,17 @@ __global__ __launch_bounds__(kBlock) void k_local_partials(const PtrTable tab, c
         acc.flush();
     }
 
-    // block reduction: shuffle tree inside each wavefront, then the 4 wavefront results in index order
-    __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
-    __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
-    const double wp = wave_sum(acc.s_pos), wn = wave_sum(acc.s_neg);
-    const uint32_t lane = tid & 63, wave = tid >> 6;
-    if (lane == 0) {
-        sh_pos[wave] = wp;
-        sh_neg[wave] = wn;
-        sh_cp[wave] = acc.c_pos;
-        sh_cn[wave] = acc.c_neg;
-        sh_cz[wave] = acc.c_zero;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        double sp = 0.0, sn = 0.0;
-        uint64_t cp = 0, cn = 0, cz = 0;
-#pragma unroll
-        for (int k = 0; k < kBlock / 64; ++k) {
-            sp += sh_pos[k];
-            sn += sh_neg[k];
-            cp += sh_cp[k];
-            cn += sh_cn[k];
-            cz += sh_cz[k];
-        }
-        const size_t slot = static_cast<size_t>(p) * B + b;
-        out.s_pos[slot] = sp;
-        out.s_neg[slot] = sn;
-        out.n_pos[slot] = cp;
-        out.n_neg[slot] = cn;
-        out.n_zero[slot] = cz;
-    }
+    // block reduction: shuffle tree inside each wavefront (the counts are wavefront totals already), then the 4
+    // wavefront results in index order
+    Sums mine;
+    mine.s_pos = wave_sum(acc.s_pos);
+    mine.s_neg = wave_sum(acc.s_neg);
+    mine.n_pos = acc.c_pos;
+    mine.n_neg = acc.c_neg;
+    mine.n_zero = acc.c_zero;
+    const Sums total = block_sum_of_waves(mine);
+    if (tid == 0)
+        store_record(out, static_cast<size_t>(p) * B + b, total);
 }
 
 // Second level, one block per worker: the B block partials in a fixed order (strided per thread, shuffle
@@ -103,49 +83,18 @@ __global__ __launch_bounds__(kBlock) void k_local_finalize(const uint64_t n, con
 {
     const uint32_t p = blockIdx.x, tid = threadIdx.x;
     const size_t row = static_cast<size_t>(p) * B;
-    double sp = 0.0, sn = 0.0;
-    uint64_t cp = 0, cn = 0, cz = 0;
-    for (uint32_t j = tid; j < B; j += kBlock) {
-        sp += in.s_pos[row + j];
-        sn += in.s_neg[row + j];
-        cp += in.n_pos[row + j];
-        cn += in.n_neg[row + j];
-        cz += in.n_zero[row + j];
-    }
-    __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
-    __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
-    sp = wave_sum(sp);
-    sn = wave_sum(sn);
-    cp = wave_sum(cp);
-    cn = wave_sum(cn);
-    cz = wave_sum(cz);
-    const uint32_t lane = tid & 63, wave = tid >> 6;
-    if (lane == 0) {
-        sh_pos[wave] = sp;
-        sh_neg[wave] = sn;
-        sh_cp[wave] = cp;
-        sh_cn[wave] = cn;
-        sh_cz[wave] = cz;
-    }
-    __syncthreads();
+    Sums mine;
+    for (uint32_t j = tid; j < B; j += kBlock)
+        add_record(mine, in, row + j);
+    const Sums t = block_sum(mine);
     if (tid == 0) {
-        double tp = 0.0, tn = 0.0;
-        uint64_t np = 0, nn = 0, nz = 0;
-#pragma unroll
-        for (int k = 0; k < kBlock / 64; ++k) {
-            tp += sh_pos[k];
-            tn += sh_neg[k];
-            np += sh_cp[k];
-            nn += sh_cn[k];
-            nz += sh_cz[k];
-        }
         a2sgd_worker_stats_t r;
-        r.mu_pos = np ? static_cast<float>(tp / static_cast<double>(np)) : 0.0f;
-        r.mu_neg = nn ? static_cast<float>(tn / static_cast<double>(nn)) : 0.0f;
-        r.n_pos = np;
-        r.n_neg = nn;
-        r.n_zero = nz;
-        r.n_nan = n - np - nn;
+        r.mu_pos = t.n_pos ? static_cast<float>(t.s_pos / static_cast<double>(t.n_pos)) : 0.0f;
+        r.mu_neg = t.n_neg ? static_cast<float>(t.s_neg / static_cast<double>(t.n_neg)) : 0.0f;
+        r.n_pos = t.n_pos;
+        r.n_neg = t.n_neg;
+        r.n_zero = t.n_zero;
+        r.n_nan = n - t.n_pos - t.n_neg;
         hdr->workers[p] = r;
     }
 }
@@ -1274,49 +1223,12 @@ __global__ __launch_bounds__(kBlock) void k_fold_partials(const uint32_t rows, c
     const uint32_t p = blockIdx.y, j = blockIdx.x, tid = threadIdx.x;
     const size_t row = static_cast<size_t>(p) * rows;
     const uint32_t lo = j * kFoldSpan, hi = rows - lo < kFoldSpan ? rows : lo + kFoldSpan;
-    double sp = 0.0, sn = 0.0;
-    uint64_t cp = 0, cn = 0, cz = 0;
-    for (uint32_t k = lo + tid; k < hi; k += kBlock) {
-        sp += in.s_pos[row + k];
-        sn += in.s_neg[row + k];
-        cp += in.n_pos[row + k];
-        cn += in.n_neg[row + k];
-        cz += in.n_zero[row + k];
-    }
-    __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
-    __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
-    sp = wave_sum(sp);
-    sn = wave_sum(sn);
-    cp = wave_sum(cp);
-    cn = wave_sum(cn);
-    cz = wave_sum(cz);
-    const uint32_t lane = tid & 63, wave = tid >> 6;
-    if (lane == 0) {
-        sh_pos[wave] = sp;
-        sh_neg[wave] = sn;
-        sh_cp[wave] = cp;
-        sh_cn[wave] = cn;
-        sh_cz[wave] = cz;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        double tp = 0.0, tn = 0.0;
-        uint64_t np = 0, nn = 0, nz = 0;
-#pragma unroll
-        for (int k = 0; k < kBlock / 64; ++k) {
-            tp += sh_pos[k];
-            tn += sh_neg[k];
-            np += sh_cp[k];
-            nn += sh_cn[k];
-            nz += sh_cz[k];
-        }
-        const size_t slot = static_cast<size_t>(p) * folded + j;
-        out.s_pos[slot] = tp;
-        out.s_neg[slot] = tn;
-        out.n_pos[slot] = np;
-        out.n_neg[slot] = nn;
-        out.n_zero[slot] = nz;
-    }
+    Sums mine;
+    for (uint32_t k = lo + tid; k < hi; k += kBlock)
+        add_record(mine, in, row + k);
+    const Sums total = block_sum(mine);
+    if (tid == 0)
+        store_record(out, static_cast<size_t>(p) * folded + j, total);
 }
 
 // Apply pass on the lazy state: the buffers already hold v, so all that is left of Algorithm 1 lines 6-7 is to

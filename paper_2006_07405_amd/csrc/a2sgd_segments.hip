@@ -16,7 +16,6 @@ SegView seg_view(const a2sgd_plan_t &pl, void *ws)
 {
     char *b = static_cast<char *>(ws);
     const SegPlan &sp = pl.seg;
-    const size_t stride = 8ull * pl.P * sp.item.size();
     SegView v;
     v.S = sp.S;
     v.num_items = static_cast<uint32_t>(sp.item.size());
@@ -33,11 +32,7 @@ SegView seg_view(const a2sgd_plan_t &pl, void *ws)
     v.neg_mu_pos = reinterpret_cast<float *>(b + sp.off_nmp);
     v.mu_neg = reinterpret_cast<float *>(b + sp.off_mn);
     v.gmu = reinterpret_cast<float *>(b + sp.off_gmu);
-    v.r_spos = reinterpret_cast<double *>(b + sp.off_records);
-    v.r_sneg = reinterpret_cast<double *>(b + sp.off_records + stride);
-    v.r_npos = reinterpret_cast<uint64_t *>(b + sp.off_records + 2 * stride);
-    v.r_nneg = reinterpret_cast<uint64_t *>(b + sp.off_records + 3 * stride);
-    v.r_nzero = reinterpret_cast<uint64_t *>(b + sp.off_records + 4 * stride);
+    v.rec = partials_at(ws, sp.off_records, pl.P, v.num_items);
     return v;
 }
 
@@ -63,14 +58,11 @@ constexpr uint32_t kSegLazyLds = 25 * 1024;
 template <bool HAS_E, bool NT>
 __global__ __launch_bounds__(kBlock) void k_seg_partials(const PtrTable tab, const SegView sv)
 {
-    const uint32_t p = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t p = blockIdx.y, tid = threadIdx.x;
     const float *__restrict__ g = tab.g[p];
     const float *__restrict__ e = HAS_E ? tab.e[p] : nullptr;
     const vf4 *g4 = reinterpret_cast<const vf4 *>(g);
     const vf4 *e4 = reinterpret_cast<const vf4 *>(e);
-    __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
-    __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
-
     if (!seg_tables_ok(sv))
         return;
     const uint32_t k_end = sv.sched_lo[blockIdx.x + 1];
@@ -112,33 +104,15 @@ __global__ __launch_bounds__(kBlock) void k_seg_partials(const PtrTable tab, con
             acc.flush();
         }
         // block reduction of this item (the counts are wavefront totals, valid in lane 0: indices grow with the lane)
-        const double wp = wave_sum(acc.s_pos), wn = wave_sum(acc.s_neg);
-        if (lane == 0) {
-            sh_pos[wave] = wp;
-            sh_neg[wave] = wn;
-            sh_cp[wave] = acc.c_pos;
-            sh_cn[wave] = acc.c_neg;
-            sh_cz[wave] = acc.c_zero;
-        }
-        __syncthreads();
-        if (tid == 0) {
-            double sp = 0.0, sn = 0.0;
-            uint64_t cp = 0, cn = 0, cz = 0;
-#pragma unroll
-            for (int k = 0; k < kBlock / 64; ++k) {
-                sp += sh_pos[k];
-                sn += sh_neg[k];
-                cp += sh_cp[k];
-                cn += sh_cn[k];
-                cz += sh_cz[k];
-            }
-            const size_t slot = static_cast<size_t>(p) * sv.num_items + it;
-            sv.r_spos[slot] = sp;
-            sv.r_sneg[slot] = sn;
-            sv.r_npos[slot] = cp;
-            sv.r_nneg[slot] = cn;
-            sv.r_nzero[slot] = cz;
-        }
+        Sums mine;
+        mine.s_pos = wave_sum(acc.s_pos);
+        mine.s_neg = wave_sum(acc.s_neg);
+        mine.n_pos = acc.c_pos;
+        mine.n_neg = acc.c_neg;
+        mine.n_zero = acc.c_zero;
+        const Sums total = block_sum_of_waves(mine);
+        if (tid == 0)
+            store_record(sv.rec, static_cast<size_t>(p) * sv.num_items + it, total);
         __syncthreads();  // the LDS slots are free again for the next item
     }
 }
@@ -154,29 +128,23 @@ __global__ __launch_bounds__(64) void k_seg_finalize(const SegView sv)
         sv.hdr->any_nan = 0u;  // k_seg_global, next on the stream, raises it if any worker counted a NaN in any tensor
     const uint32_t lo = sv.item_lo[s], hi = sv.item_lo[s + 1];
     const size_t row = static_cast<size_t>(p) * sv.num_items;
-    double sp = 0.0, sn = 0.0;
-    uint64_t cp = 0, cn = 0, cz = 0;
-    for (uint32_t j = lo + lane; j < hi; j += 64) {
-        sp += sv.r_spos[row + j];
-        sn += sv.r_sneg[row + j];
-        cp += sv.r_npos[row + j];
-        cn += sv.r_nneg[row + j];
-        cz += sv.r_nzero[row + j];
-    }
-    sp = wave_sum(sp);
-    sn = wave_sum(sn);
-    cp = wave_sum(cp);
-    cn = wave_sum(cn);
-    cz = wave_sum(cz);
+    Sums t;
+    for (uint32_t j = lo + lane; j < hi; j += 64)
+        add_record(t, sv.rec, row + j);
+    t.s_pos = wave_sum(t.s_pos);
+    t.s_neg = wave_sum(t.s_neg);
+    t.n_pos = wave_sum(t.n_pos);
+    t.n_neg = wave_sum(t.n_neg);
+    t.n_zero = wave_sum(t.n_zero);
     if (lane == 0) {
         const uint64_t len = sv.seg_end[s] - sv.seg_start[s];
         a2sgd_worker_stats_t r;
-        r.mu_pos = cp ? static_cast<float>(sp / static_cast<double>(cp)) : 0.0f;
-        r.mu_neg = cn ? static_cast<float>(sn / static_cast<double>(cn)) : 0.0f;
-        r.n_pos = cp;
-        r.n_neg = cn;
-        r.n_zero = cz;
-        r.n_nan = len - cp - cn;
+        r.mu_pos = t.n_pos ? static_cast<float>(t.s_pos / static_cast<double>(t.n_pos)) : 0.0f;
+        r.mu_neg = t.n_neg ? static_cast<float>(t.s_neg / static_cast<double>(t.n_neg)) : 0.0f;
+        r.n_pos = t.n_pos;
+        r.n_neg = t.n_neg;
+        r.n_zero = t.n_zero;
+        r.n_nan = len - t.n_pos - t.n_neg;
         sv.stats[static_cast<size_t>(p) * sv.S + s] = r;
     }
 }
@@ -190,50 +158,19 @@ __global__ __launch_bounds__(kBlock) void k_seg_finalize_pooled(const SegView sv
     const size_t row = static_cast<size_t>(p) * sv.num_items;
     if (p == 0 && tid == 0)
         sv.hdr->any_nan = 0u;  // as in k_seg_finalize
-    double sp = 0.0, sn = 0.0;
-    uint64_t cp = 0, cn = 0, cz = 0;
-    for (uint32_t j = tid; j < sv.num_items; j += kBlock) {
-        sp += sv.r_spos[row + j];
-        sn += sv.r_sneg[row + j];
-        cp += sv.r_npos[row + j];
-        cn += sv.r_nneg[row + j];
-        cz += sv.r_nzero[row + j];
-    }
-    __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
-    __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
+    Sums mine;
+    for (uint32_t j = tid; j < sv.num_items; j += kBlock)
+        add_record(mine, sv.rec, row + j);
     __shared__ a2sgd_worker_stats_t sh_result;
-    sp = wave_sum(sp);
-    sn = wave_sum(sn);
-    cp = wave_sum(cp);
-    cn = wave_sum(cn);
-    cz = wave_sum(cz);
-    const uint32_t lane = tid & 63, wave = tid >> 6;
-    if (lane == 0) {
-        sh_pos[wave] = sp;
-        sh_neg[wave] = sn;
-        sh_cp[wave] = cp;
-        sh_cn[wave] = cn;
-        sh_cz[wave] = cz;
-    }
-    __syncthreads();
+    const Sums t = block_sum(mine);
     if (tid == 0) {
-        double tp = 0.0, tn = 0.0;
-        uint64_t np = 0, nn = 0, nz = 0;
-#pragma unroll
-        for (int k = 0; k < kBlock / 64; ++k) {
-            tp += sh_pos[k];
-            tn += sh_neg[k];
-            np += sh_cp[k];
-            nn += sh_cn[k];
-            nz += sh_cz[k];
-        }
         a2sgd_worker_stats_t r;
-        r.mu_pos = np ? static_cast<float>(tp / static_cast<double>(np)) : 0.0f;
-        r.mu_neg = nn ? static_cast<float>(tn / static_cast<double>(nn)) : 0.0f;
-        r.n_pos = np;
-        r.n_neg = nn;
-        r.n_zero = nz;
-        r.n_nan = covered - np - nn;
+        r.mu_pos = t.n_pos ? static_cast<float>(t.s_pos / static_cast<double>(t.n_pos)) : 0.0f;
+        r.mu_neg = t.n_neg ? static_cast<float>(t.s_neg / static_cast<double>(t.n_neg)) : 0.0f;
+        r.n_pos = t.n_pos;
+        r.n_neg = t.n_neg;
+        r.n_zero = t.n_zero;
+        r.n_nan = covered - t.n_pos - t.n_neg;
         sh_result = r;
     }
     __syncthreads();
@@ -931,15 +868,14 @@ __global__ __launch_bounds__(64) void k_seg_lazy_partials(const PtrTable tab, co
             sign_row(sign, P, b, 1, p)[lane] = static_cast<uint16_t>(bits & 0xffffu);
         }
         acc.flush();
-        const double wp = wave_sum(acc.s_pos), wn = wave_sum(acc.s_neg);
-        if (lane == 0) {
-            const size_t slot = static_cast<size_t>(p) * blocks + b;
-            rec.s_pos[slot] = wp;
-            rec.s_neg[slot] = wn;
-            rec.n_pos[slot] = acc.c_pos;
-            rec.n_neg[slot] = acc.c_neg;
-            rec.n_zero[slot] = acc.c_zero;
-        }
+        Sums total;
+        total.s_pos = wave_sum(acc.s_pos);
+        total.s_neg = wave_sum(acc.s_neg);
+        total.n_pos = acc.c_pos;
+        total.n_neg = acc.c_neg;
+        total.n_zero = acc.c_zero;
+        if (lane == 0)
+            store_record(rec, static_cast<size_t>(p) * blocks + b, total);
         return;
     }
 
@@ -989,16 +925,16 @@ __global__ __launch_bounds__(64) void k_seg_lazy_partials(const PtrTable tab, co
             tail_in = tail_in || in;
         }
         acc.flush();
-        const double wp = wave_sum(acc.s_pos), wn = wave_sum(acc.s_neg);
+        Sums total;
+        total.s_pos = wave_sum(acc.s_pos);
+        total.s_neg = wave_sum(acc.s_neg);
+        total.n_pos = acc.c_pos;
+        total.n_neg = acc.c_neg;
+        total.n_zero = acc.c_zero;
         if (lane == 0) {
             // the block holds the tensor's first element (its first slot) or, failing that, its last one
             const uint32_t k = ts >= blo ? lv.item_lo[t] : lv.item_lo[t + 1] - 1;
-            const size_t slot = static_cast<size_t>(p) * lv.num_items + k;
-            lv.r_spos[slot] = wp;
-            lv.r_sneg[slot] = wn;
-            lv.r_npos[slot] = acc.c_pos;
-            lv.r_nneg[slot] = acc.c_neg;
-            lv.r_nzero[slot] = acc.c_zero;
+            store_record(lv.rec, static_cast<size_t>(p) * lv.num_items + k, total);
         }
     }
     uint32_t bits = 0;
@@ -1038,49 +974,12 @@ __global__ __launch_bounds__(kBlock) void k_seg_lazy_fold(const SegFold *__restr
         return;
     const SegFold f = fold[blockIdx.x];
     const size_t row = static_cast<size_t>(p) * blocks;
-    double sp = 0.0, sn = 0.0;
-    uint64_t cp = 0, cn = 0, cz = 0;
-    for (uint32_t k = f.lo + tid; k < f.hi; k += kBlock) {
-        sp += in.s_pos[row + k];
-        sn += in.s_neg[row + k];
-        cp += in.n_pos[row + k];
-        cn += in.n_neg[row + k];
-        cz += in.n_zero[row + k];
-    }
-    __shared__ double sh_pos[kBlock / 64], sh_neg[kBlock / 64];
-    __shared__ uint64_t sh_cp[kBlock / 64], sh_cn[kBlock / 64], sh_cz[kBlock / 64];
-    sp = wave_sum(sp);
-    sn = wave_sum(sn);
-    cp = wave_sum(cp);
-    cn = wave_sum(cn);
-    cz = wave_sum(cz);
-    const uint32_t lane = tid & 63, wave = tid >> 6;
-    if (lane == 0) {
-        sh_pos[wave] = sp;
-        sh_neg[wave] = sn;
-        sh_cp[wave] = cp;
-        sh_cn[wave] = cn;
-        sh_cz[wave] = cz;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        double tp = 0.0, tn = 0.0;
-        uint64_t np = 0, nn = 0, nz = 0;
-#pragma unroll
-        for (int k = 0; k < kBlock / 64; ++k) {
-            tp += sh_pos[k];
-            tn += sh_neg[k];
-            np += sh_cp[k];
-            nn += sh_cn[k];
-            nz += sh_cz[k];
-        }
-        const size_t slot = static_cast<size_t>(p) * lv.num_items + f.slot;
-        lv.r_spos[slot] = tp;
-        lv.r_sneg[slot] = tn;
-        lv.r_npos[slot] = np;
-        lv.r_nneg[slot] = nn;
-        lv.r_nzero[slot] = nz;
-    }
+    Sums mine;
+    for (uint32_t k = f.lo + tid; k < f.hi; k += kBlock)
+        add_record(mine, in, row + k);
+    const Sums total = block_sum(mine);
+    if (tid == 0)
+        store_record(lv.rec, static_cast<size_t>(p) * lv.num_items + f.slot, total);
 }
 
 // Clears the carried means of every tensor and worker: from here on the state buffers are read as true errors.
@@ -1124,12 +1023,7 @@ static SegView seg_lazy_view(const a2sgd_plan_t &pl, void *ws)
     v.num_items = sp.lz_slot_lo[sp.S];
     v.item = nullptr;  // the lazy passes go by position, not by item
     v.item_lo = reinterpret_cast<const uint32_t *>(b + sp.off_lz_slot_lo);
-    const size_t stride = 8ull * pl.P * v.num_items;
-    v.r_spos = reinterpret_cast<double *>(b + sp.off_lz_folded);
-    v.r_sneg = reinterpret_cast<double *>(b + sp.off_lz_folded + stride);
-    v.r_npos = reinterpret_cast<uint64_t *>(b + sp.off_lz_folded + 2 * stride);
-    v.r_nneg = reinterpret_cast<uint64_t *>(b + sp.off_lz_folded + 3 * stride);
-    v.r_nzero = reinterpret_cast<uint64_t *>(b + sp.off_lz_folded + 4 * stride);
+    v.rec = partials_at(ws, sp.off_lz_folded, pl.P, v.num_items);
     return v;
 }
 
