@@ -727,3 +727,66 @@ def test_tensor_plan_steps_captured_in_a_hip_graph(A, calls, P):
         assert busy == busy
         assert torch.equal(w, expected[k][1]), f"replay {k}: w differs from the eager step"
         assert all(torch.equal(a, b) for a, b in zip(e, expected[k][0])), f"replay {k}: state differs from the eager step"
+
+
+def random_layout(rng, target_n, padded):
+    """Tensor lengths (and offsets, if padded) with boundaries of every kind: tiny tensors, lengths around the sizes the
+    kernels work in (4, 256, 1024, 2048, 4096, 65536 elements), and a few large ones."""
+    lengths = []
+    while sum(lengths) < target_n:
+        kind = rng.random()
+        if kind < 0.25:
+            lengths.append(int(rng.integers(1, 10)))
+        elif kind < 0.55:
+            lengths.append(int(rng.integers(10, 3000)))
+        elif kind < 0.8:
+            unit = int(rng.choice([4, 256, 1024, 2048, 4096, 65_536]))
+            lengths.append(max(1, unit * int(rng.integers(1, 4)) + int(rng.choice([-3, -1, 0, 0, 1, 3]))))
+        else:
+            lengths.append(int(rng.integers(3000, max(3001, target_n // 3))))
+    if not padded:
+        return sum(lengths), lengths, None
+    offsets, pos = [], int(rng.integers(0, 6))
+    for length in lengths:
+        offsets.append(pos)
+        gap = rng.random()
+        pos += length + (0 if gap < 0.6 else int(rng.integers(1, 8)) if gap < 0.8 else
+                         int(rng.integers(255, 258)) if gap < 0.9 else int(rng.integers(1000, 3000)))
+    return pos + int(rng.integers(0, 10)), lengths, offsets
+
+
+def run_random_case(A, rng, case, n, lengths, offsets, P, mode, pooled, path):
+    print(f"case {case}: n={n} S={len(lengths)} padded={offsets is not None} P={P} mode={mode} pooled={pooled} path={path}",
+          flush=True)
+    if path == "step":
+        offs = offsets if offsets is not None else [int(x) for x in np.concatenate([[0], np.cumsum(lengths)[:-1]])]
+        run_padded_case(A, 1000 + case, n, P, mode, lengths, offs, pooled, with_e=bool(mode == 0 or rng.integers(0, 2)))
+    elif path == "lazy":
+        run_lazy_case(A, 1000 + case, n, P, mode, lengths, offsets, pooled, steps=2)
+    else:
+        run_replica_case(A, 1000 + case, n, P, mode, lengths, offsets, pooled)
+
+
+def test_random_tensor_layouts_against_the_oracle(A):
+    """Seeded random draws of the tensor layout (with and without padding), P, mode, pooled means and the path taken
+    (a2sgd_step, the lazy state, one weight vector per worker): the combinations nobody thought of."""
+    rng = np.random.default_rng(20261127)
+    for case in range(36):
+        padded = bool(rng.integers(0, 2))
+        n, lengths, offsets = random_layout(rng, int(rng.choice([60, 3000, 40_000, 300_000])), padded)
+        P = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16]))
+        run_random_case(A, rng, case, n, lengths, offsets, P, int(rng.integers(0, 2)), bool(rng.integers(0, 2)),
+                        str(rng.choice(["step", "lazy", "replicas"])))
+
+
+@pytest.mark.parametrize("P", [8, 9, 16, 33])
+def test_random_tensor_layouts_at_streaming_sizes(A, P):
+    """The same draws at sizes above the cache limit, where the streaming instantiations run (non-temporal loads,
+    write-through stores, the two-kernel apply pass, one worker per workgroup in the replica pass)."""
+    rng = np.random.default_rng(977 + P)
+    need = (192 << 20) // (4 * (2 * P + 1)) + 1
+    for k, path in enumerate(["step", "lazy", "replicas"]):
+        padded = bool((P + k) % 2)
+        n, lengths, offsets = random_layout(rng, need + int(rng.integers(1, 5000)), padded)
+        assert (2 * P + 1) * 4 * n > 192 << 20
+        run_random_case(A, rng, 100 * P + k, n, lengths, offsets, P, int(k == 1 and P == 9), bool(P == 16 and k != 2), path)
