@@ -97,6 +97,13 @@ def test_segmented_plan_validation_and_workspace(A):
     assert A.a2sgd_workspace_bytes(seg) > 4096 + 5 * 8 * 4 * A.a2sgd_plan_blocks_per_worker(whole)
     one = A.a2sgd_plan(1_000_000, 4, 0, 0, seg_lengths=[1_000_000])  # one tensor: the same means, the tensor path
     assert one.num_segments == 1
+    # retained-error mode keeps one sign bit per element and worker for the lazy state and the two-kernel apply pass,
+    # in rows of 2048 elements, at the very end of the workspace; literal mode has no use for them
+    for n, P, lengths in ((1_000_000, 4, [1, 70_000, 3, 929_996]), (2049, 3, [2049]), (3, 1, [1, 2]), (8192, 9, [4096, 4096])):
+        ret = A.a2sgd_plan(n, P, 0, 0, seg_lengths=lengths)
+        lit = A.a2sgd_plan(n, P, 1, 0, seg_lengths=lengths)
+        rows = max(1, -(-(n >> 2) // 512))
+        assert A.a2sgd_workspace_bytes(ret) - A.a2sgd_workspace_bytes(lit) == 256 * P * rows
     # with offsets: ascending, not overlapping, inside [0, n); sizes need not add up to n
     ok = A.a2sgd_plan(100, 2, 0, 0, seg_lengths=[10, 20, 5], seg_offsets=[3, 13, 90])
     assert ok.num_segments == 3
