@@ -113,10 +113,14 @@ def other_config(A, torch, workloads, k, steps, warmup):
            "step_frac_of_peak": bytes_step / (t["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
            "apply_frac_of_peak": bytes_apply / (t["ms_apply"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
            "cache_resident": A.a2sgd_plan_single_launch_cell(plan) >= 0}
+    # a2sgd_step: the same passes in one call with no events recorded between them (what a caller who wants no
+    # per-pass times pays; at the smaller sizes the events cost several percent)
+    t1 = time_steps(A, torch, plan, g, e, w, wl.eta, ws, steps, warmup, single_call=True)
     if out["cache_resident"]:
         # g + e + w fit the last-level cache: the fractions above are not HBM fractions, and a2sgd_step is one launch
-        t1 = time_steps(A, torch, plan, g, e, w, wl.eta, ws, steps, warmup, single_call=True)
         out["ms_per_step_single_launch"] = t1["ms_per_step"]
+    else:
+        out["ms_per_step_one_call"] = t1["ms_per_step"]
     del g, e, w, ws
     torch.cuda.empty_cache()
     return out
